@@ -1,0 +1,135 @@
+"""Oracle: the unified overlap cost model -- TEST INFRASTRUCTURE ONLY.
+
+Follows the paper's Eq. 1 (Z = max(Y, X) with Y = sum_i y_i, X = sum_j x_j) and the
+contention wave model of Eq. 4-6 in the paper's notation (Table 1):
+
+    y_i  = sum_{j=l..k} f_ij * g_ij                                   (Eq. 4)
+    g_ij = ceil( mu_i / ((lambda - NC_j) * TB_i) )                    (Eq. 5)
+    f_ij = theta_i + (lambda - NC_j) * TB_i * D_i / (B - V(NC_j,C_j)) (Eq. 6)
+
+Readings taken where the text leaves a choice:
+
+* mu_i is the total number of workgroups of computation i, TB_i the number resident
+  per compute unit, lambda the number of compute units (Eq. 5's prose).
+* x_j is not modelled by the paper (it is measured); here it comes from a table
+  keyed by the configuration (NC, NT, C), and so does V(NC, C).
+* When one computation overlaps several communications, the two serialized queues
+  are stepped wave by wave: communication j is active on [sum_{<j} x, sum_{<=j} x);
+  a wave that starts while j is active (or after the last one ended: NC = 0, V = 0)
+  retires min(remaining, (lambda - NC_j) * TB_i) workgroups and lasts f_ij, and g_ij
+  counts the waves issued under j.  With a single communication covering the whole
+  computation this is exactly Eq. 4-6 as printed.
+* The last, partial wave costs a full f_ij (Eq. 6 is used literally).
+* There are no cross-stream dependencies (Eq. 1 has none).
+
+Units: time in microseconds, bandwidth in bytes per microsecond, D_i in bytes.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, List, Sequence, Tuple
+
+Cfg = Tuple[int, int, int]  # (NC, NT, C bytes)
+
+
+@dataclass
+class Comp:
+    mu: int          # total workgroups of the computation
+    tb: int          # workgroups resident per compute unit
+    d_bytes: float   # bytes moved per workgroup
+    theta: float     # compute time of one wave, microseconds
+
+
+@dataclass
+class Model:
+    lam: int                       # number of compute units
+    bw_peak: float                 # peak global-memory bandwidth, bytes / microsecond
+    comps: List[Comp]
+    # one table per communication: cfg -> (x microseconds, V bytes/microsecond)
+    tables: List[Dict[Cfg, Tuple[float, float]]] = field(default_factory=list)
+
+
+@dataclass
+class Prediction:
+    x: List[float]
+    y: List[float]
+    g: List[List[int]]   # g[i][j], j = N is "no communication active"
+    X: float
+    Y: float
+    Z: float
+
+
+def wave_count(mu: int, lam: int, nc: int, tb: int) -> int:
+    """Eq. 5."""
+    cap = (lam - nc) * tb
+    if cap <= 0:
+        raise ValueError("communication leaves no compute unit free")
+    return -(-mu // cap)
+
+
+def wave_time(theta: float, lam: int, nc: int, tb: int, d_bytes: float, bw_peak: float, v: float) -> float:
+    """Eq. 6."""
+    if not v < bw_peak:
+        raise ValueError("communication bandwidth reaches the peak")
+    cap = (lam - nc) * tb
+    return theta + (cap * d_bytes) / (bw_peak - v)
+
+
+def predict(model: Model, cfgs: Sequence[Cfg]) -> Prediction:
+    """Eq. 1 over Eq. 4-6 for the whole overlap group."""
+    N = len(model.tables)
+    if len(cfgs) != N:
+        raise ValueError("one configuration per communication")
+    x, v, nc = [], [], []
+    for j, cfg in enumerate(cfgs):
+        key = (int(cfg[0]), int(cfg[1]), int(cfg[2]))
+        if key not in model.tables[j]:
+            raise KeyError(f"communication {j}: configuration {key} not in its table")
+        xj, vj = model.tables[j][key]
+        if key[0] >= model.lam or key[0] < 1:
+            raise ValueError("NC out of range")
+        if not (0.0 <= vj < model.bw_peak) or not xj >= 0.0:
+            raise ValueError("table entry out of range")
+        x.append(float(xj)); v.append(float(vj)); nc.append(key[0])
+    # communication j is active on [T[j], T[j+1])
+    T = [0.0]
+    for xj in x:
+        T.append(T[-1] + xj)
+    X = T[N]
+
+    y_all, g_all = [], []
+    t0 = 0.0
+    for comp in model.comps:
+        if comp.mu < 0 or comp.tb < 1:
+            raise ValueError("bad computation description")
+        g = [0] * (N + 1)
+        f = [0.0] * (N + 1)
+        rem = comp.mu
+        t = t0
+        y = 0.0
+        while rem > 0:
+            slot = N
+            for j in range(N):
+                if t < T[j + 1]:
+                    slot = j
+                    break
+            if slot < N:
+                cap = (model.lam - nc[slot]) * comp.tb
+                f[slot] = wave_time(comp.theta, model.lam, nc[slot], comp.tb, comp.d_bytes, model.bw_peak, v[slot])
+            else:
+                cap = model.lam * comp.tb
+                f[slot] = wave_time(comp.theta, model.lam, 0, comp.tb, comp.d_bytes, model.bw_peak, 0.0)
+            g[slot] += 1
+            rem -= min(rem, cap)
+            y = 0.0
+            for s in range(N + 1):          # Eq. 4, terms in ascending j
+                if g[s] > 0:
+                    y = y + f[s] * g[s]
+            t = t0 + y
+        y_all.append(y)
+        g_all.append(g)
+        t0 = t0 + y
+    Y = 0.0
+    for yi in y_all:
+        Y = Y + yi
+    return Prediction(x=x, y=y_all, g=g_all, X=X, Y=Y, Z=max(X, Y))

@@ -1,0 +1,95 @@
+"""Pins for oracle/cost_model.py: hand-worked fixtures, closed forms and invariants of
+the paper's Eq. 1-6."""
+import itertools
+import json
+import math
+import os
+
+import pytest
+
+from oracle import cost_model as cm
+
+
+def _model(lam, bw, comps, comms):
+    tables = [{(c["nc"], 256, 65536): (c["x"], c["v"])} for c in comms]
+    return cm.Model(lam=lam, bw_peak=bw, comps=[cm.Comp(**c) for c in comps], tables=tables), \
+        [(c["nc"], 256, 65536) for c in comms]
+
+
+def test_hand_worked_fixture(golden_dir):
+    fx = json.load(open(os.path.join(golden_dir, "cost_model_worked.json")))
+    for case in fx["cases"]:
+        model, cfgs = _model(fx["lambda"], fx["bw_peak"], case["comps"], case["comms"])
+        p = cm.predict(model, cfgs)
+        assert p.y == case["y"], case["name"]
+        assert p.g == case["g"], case["name"]
+        assert (p.X, p.Y, p.Z) == (case["X"], case["Y"], case["Z"]), case["name"]
+
+
+def test_single_comm_reduces_to_eq_4_5_6():
+    lam, bw = 256, 8.0e6
+    for nc, v, mu, tb in itertools.product([1, 8, 32, 200], [0.0, 1.0e6, 7.9e6], [1, 255, 1024, 5000], [1, 2]):
+        theta, d = 12.5, 3.0e6
+        g = math.ceil(mu / ((lam - nc) * tb))                              # Eq. 5
+        f = theta + (lam - nc) * tb * d / (bw - v)                         # Eq. 6
+        model = cm.Model(lam, bw, [cm.Comp(mu, tb, d, theta)], [{(nc, 256, 4096): (1e12, v)}])
+        p = cm.predict(model, [(nc, 256, 4096)])
+        assert p.g[0][0] == g and p.g[0][1] == 0
+        assert p.y[0] == pytest.approx(f * g, rel=1e-15)                   # Eq. 4
+        assert cm.wave_count(mu, lam, nc, tb) == g
+        assert p.Z == 1e12 and p.X == 1e12                                 # Eq. 1, communication-bound
+
+
+def test_no_comm_is_textbook_wave_quantisation():
+    lam, bw = 256, 8.0e6
+    for mu, tb in [(1, 1), (256, 1), (257, 1), (1024, 2), (1025, 2)]:
+        model = cm.Model(lam, bw, [cm.Comp(mu, tb, 1.0e6, 3.0)], [])
+        p = cm.predict(model, [])
+        want = math.ceil(mu / (lam * tb)) * (3.0 + lam * tb * 1.0e6 / bw)
+        assert p.Y == pytest.approx(want, rel=1e-15) and p.X == 0.0 and p.Z == p.Y
+
+
+def test_eq1_and_monotone_invariants():
+    lam, bw = 64, 1000.0
+    comps = [cm.Comp(300, 2, 50.0, 2.0), cm.Comp(100, 1, 80.0, 1.0)]
+    ncs, vs = [1, 2, 4, 8, 16, 32], [0.0, 100.0, 400.0, 900.0]
+    for nc in ncs:
+        prev = None
+        for v in vs:
+            table = {(nc, 64, 1024): (1e9, v)}
+            p = cm.predict(cm.Model(lam, bw, comps, [table]), [(nc, 64, 1024)])
+            assert p.Z == max(p.X, p.Y) and p.Y == sum(p.y)       # Eq. 1
+            if prev is not None:
+                assert p.Y > prev                                 # strictly slower as V grows (Eq. 6)
+            prev = p.Y
+    # In NC the printed Eq. 6 charges every wave, also the partial last one, the bytes of a full wave,
+    # so y is monotone in NC only without a partial wave: mu a multiple of every (lambda - NC) * TB.
+    comps = [cm.Comp(192, 1, 50.0, 2.0)]
+    prev = cm.predict(cm.Model(lam, bw, comps, []), []).Y
+    for nc in (16, 32, 48):
+        table = {(nc, 64, 1024): (1e9, 100.0)}
+        p = cm.predict(cm.Model(lam, bw, comps, [table]), [(nc, 64, 1024)])
+        assert p.Y > prev
+        prev = p.Y
+
+
+def test_eq2_separability_when_communication_bound():
+    # if X >= Y for every configuration, the best Z is the sum of the per-communication minima (Eq. 2)
+    lam, bw = 32, 1000.0
+    comps = [cm.Comp(10, 1, 1.0, 0.5)]
+    cfgs = [(1, 64, 1024), (2, 64, 1024), (4, 64, 1024)]
+    t0 = {cfgs[0]: (900.0, 10.0), cfgs[1]: (500.0, 20.0), cfgs[2]: (650.0, 30.0)}
+    t1 = {cfgs[0]: (800.0, 10.0), cfgs[1]: (700.0, 20.0), cfgs[2]: (300.0, 30.0)}
+    model = cm.Model(lam, bw, comps, [t0, t1])
+    best = min(cm.predict(model, [a, b]).Z for a in cfgs for b in cfgs)
+    assert best == min(x for x, _ in t0.values()) + min(x for x, _ in t1.values())
+
+
+def test_rejects_out_of_range_inputs():
+    comps = [cm.Comp(10, 1, 1.0, 0.5)]
+    with pytest.raises(ValueError):
+        cm.predict(cm.Model(8, 100.0, comps, [{(8, 64, 64): (1.0, 1.0)}]), [(8, 64, 64)])     # NC >= lambda
+    with pytest.raises(ValueError):
+        cm.predict(cm.Model(8, 100.0, comps, [{(2, 64, 64): (1.0, 100.0)}]), [(2, 64, 64)])   # V >= B
+    with pytest.raises(KeyError):
+        cm.predict(cm.Model(8, 100.0, comps, [{(2, 64, 64): (1.0, 1.0)}]), [(4, 64, 64)])     # not in the table
