@@ -1,0 +1,285 @@
+/*
+ * lagom.h -- C ABI of the MI355X (gfx950) hot path of Lagom: one GPU's share of an
+ * overlapped training step, and the host-side model and search that tune it.
+ *
+ * Conventions common to every call
+ *   - Plain C types only.  "device pointer" = address in this GPU's HBM (hipMalloc or
+ *     a torch tensor's data_ptr); "host pointer" = ordinary process memory.
+ *   - The caller owns every buffer and both streams.  The library allocates no device
+ *     memory.  Host structs and host pointer arrays are read during the call only.
+ *   - Return value: LAGOM_OK (0) or a negative LAGOM_E* code; lagom_last_error()
+ *     gives the text for the calling thread.  Nothing is thrown across the boundary.
+ *   - Times are microseconds (double), bandwidths bytes per microsecond, sizes bytes.
+ */
+#ifndef LAGOM_H
+#define LAGOM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LAGOM_OK          0
+#define LAGOM_EINVAL    (-1)  /* bad argument (null, out of range, inconsistent)          */
+#define LAGOM_EALIGN    (-2)  /* a device pointer is not 16-byte aligned                  */
+#define LAGOM_EHIP      (-3)  /* the HIP runtime reported an error                        */
+#define LAGOM_ECALLBACK (-4)  /* the profile callback failed; outputs hold best-so-far    */
+
+#define LAGOM_MAX_SRCS     16
+#define LAGOM_MAX_DSTS      4
+#define LAGOM_MAX_LAUNCHES 256  /* kernel launches per stream in one overlap group        */
+#define LAGOM_MAX_COMMS    64   /* tunable communications in one overlap group            */
+
+/* The three resource-related parameters of a communication (Sec. 2.2 and Sec. 3.2):
+ * number of channels NC (= workgroups), threads per block NT, chunk size C in bytes. */
+typedef struct {
+    int32_t nc;
+    int32_t nt;
+    int64_t chunk_bytes;
+} lagom_cfg;
+
+typedef enum { LAGOM_F32 = 0, LAGOM_BF16 = 1 } lagom_dtype;
+typedef enum { LAGOM_REDUCE_COPY = 0, LAGOM_GATHER_COPY = 1 } lagom_op;
+
+const char* lagom_strerror(int code);   /* static text for a LAGOM_E* code              */
+const char* lagom_last_error(void);     /* detail of the calling thread's last failure  */
+
+/* ---------------------------------------------------------------------------------
+ * lagom_comm_kernel -- the local data-movement step of a chunked collective
+ * (Sec. 3.2, "Global Resource Competition": a communication launches NC thread blocks
+ * that move data at granularity C; Sec. 2.1 names the collectives).
+ *
+ *   LAGOM_REDUCE_COPY: for every element i < count and every destination d
+ *       dsts[d][i] = round_dt(((src0[i] + src1[i]) + src2[i]) + ...)
+ *     fp32 additions in source order, bf16 widened exactly, one round-to-nearest-even
+ *     at the store.  Every source and destination holds `count` elements.
+ *   LAGOM_GATHER_COPY: dsts[d][r*count + i] = srcs[r][i]; every destination holds
+ *     nsrc*count elements (concatenation in rank order).
+ *
+ * The grid is cfg->nc workgroups of cfg->nt threads; chunk g (cfg->chunk_bytes bytes,
+ * numbered shard by shard, the last one of a shard may be short) is moved by
+ * workgroup g mod nc.  The result does not depend on cfg.
+ *
+ *   srcs, dsts : HOST arrays of DEVICE pointers, 16-byte aligned, not overlapping.
+ *   nsrc 1..LAGOM_MAX_SRCS, ndst 1..LAGOM_MAX_DSTS, count >= 0 (0 launches nothing).
+ *   cfg        : nc >= 1; nt a multiple of 64 in 64..1024; chunk_bytes a positive
+ *                multiple of 16.
+ *   hip_stream : a hipStream_t (0 = the null stream).  Enqueue only: no synchronisation.
+ * Errors: LAGOM_EINVAL, LAGOM_EALIGN, LAGOM_EHIP.  Byte counts that are not multiples
+ * of 16 are handled (a short tail), not rejected.
+ */
+int lagom_comm_kernel(lagom_op op, lagom_dtype dt,
+                      const void* const* srcs, int nsrc,
+                      void* const* dsts, int ndst,
+                      int64_t count, const lagom_cfg* cfg, void* hip_stream);
+
+/* ---------------------------------------------------------------------------------
+ * lagom_gemm -- the computation whose slow-down under contention is studied
+ * (Sec. 3.2, Fig. 3: an FFN matrix multiply next to a collective).
+ *
+ *   C[M,N] = A[M,K] . B, bf16 inputs, fp32 accumulation on the matrix cores.
+ *   A : device, row-major [M,K] bf16.
+ *   B : device, bf16, row-major [N,K] when b_is_nk != 0 (weight layout), else [K,N].
+ *   C : device, row-major [M,N], bf16 (round-to-nearest-even) or fp32 per out_dt.
+ *   M, N, K >= 1; K a multiple of 8 (16-byte rows); pointers 16-byte aligned.
+ * Enqueue only on hip_stream.  Errors: LAGOM_EINVAL, LAGOM_EALIGN, LAGOM_EHIP.
+ */
+int lagom_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K,
+               int b_is_nk, lagom_dtype out_dt, void* hip_stream);
+
+/* Workgroup geometry of lagom_gemm for a problem size, as the cost model needs it
+ * (Eq. 5-6: mu = total workgroups, TB = workgroups resident per compute unit,
+ * D = bytes each workgroup reads and writes).  Host only. */
+typedef struct {
+    int64_t mu;
+    int32_t tb;
+    double  d_bytes;
+    int32_t tile_m, tile_n, tile_k, threads;
+} lagom_gemm_geometry;
+int lagom_gemm_describe(int64_t M, int64_t N, int64_t K, lagom_dtype out_dt, lagom_gemm_geometry* out);
+
+/* ---------------------------------------------------------------------------------
+ * lagom_overlap_run -- execute one overlap group and time it (Sec. 3.1, Eq. 1:
+ * communications serialized on one stream, computations on another, makespan
+ * Z = time until both have drained; this is also Alg. 2's ProfileTime).
+ */
+typedef struct {
+    int32_t op;                 /* lagom_op                                             */
+    int32_t dtype;              /* lagom_dtype                                          */
+    const void* const* srcs;    /* host array of device pointers                        */
+    int32_t nsrc;
+    void* const* dsts;          /* host array of device pointers                        */
+    int32_t ndst;
+    int64_t count;
+    int32_t comm_id;            /* the tunable communication this launch belongs to:
+                                   index into cfgs; launches of one id are contiguous  */
+} lagom_comm_desc;
+
+typedef struct {
+    const void* A; const void* B; void* C;
+    int64_t M, N, K;
+    int32_t b_is_nk;
+    int32_t out_dtype;
+} lagom_gemm_desc;
+
+typedef enum { LAGOM_ALONE_COMM = 0, LAGOM_ALONE_COMP = 1, LAGOM_CORUN = 2 } lagom_run_mode;
+
+typedef struct {
+    double X_us;      /* communication stream: first kernel start to last kernel end    */
+    double Y_us;      /* computation stream: likewise                                   */
+    double Z_us;      /* common start to the later of the two ends                      */
+    double* x_us;     /* host [ncfg]  per communication (nullable)                      */
+    double* y_us;     /* host [ncomp] per computation   (nullable)                      */
+} lagom_timing;
+
+/*   launches[nlaunch] : communication kernels in stream order; cfgs[ncfg] their
+ *                       parameters, selected by comm_id.
+ *   comps[ncomp]      : GEMMs in stream order.
+ *   comm_stream, comp_stream : two distinct hipStream_t of default priority.
+ *   Each of warmup + iters repetitions starts both streams together behind a gate and
+ *   drains both before the next; every value reported is the median over `iters`.
+ *   The call synchronises both streams and owns its events.
+ * Errors: LAGOM_EINVAL, LAGOM_EALIGN, LAGOM_EHIP.
+ */
+int lagom_overlap_run(const lagom_comm_desc* launches, int nlaunch,
+                      const lagom_cfg* cfgs, int ncfg,
+                      const lagom_gemm_desc* comps, int ncomp,
+                      void* comm_stream, void* comp_stream,
+                      int warmup, int iters, int mode, lagom_timing* out);
+
+/* ---------------------------------------------------------------------------------
+ * lagom_contention_sweep -- the contention profiler (the experiment of Fig. 3,
+ * Sec. 3.2): for every configuration of a list, applied to all communications of
+ * the group, time the communications alone, the computations alone (once), and both
+ * together, and derive the communication's global-memory bandwidth V (Eq. 6).
+ */
+typedef struct {
+    lagom_cfg cfg;
+    double comm_alone_us, comm_corun_us;     /* X                                       */
+    double comp_alone_us, comp_corun_us;     /* Y                                       */
+    double z_corun_us;
+    double v_alone, v_corun;                 /* algorithmic bytes / X, bytes per us     */
+} lagom_sweep_point;
+
+int lagom_contention_sweep(const lagom_comm_desc* launches, int nlaunch, int ncfg,
+                           const lagom_gemm_desc* comps, int ncomp,
+                           const lagom_cfg* points, int npoints,
+                           void* comm_stream, void* comp_stream,
+                           int warmup, int iters, lagom_sweep_point* out /* [npoints] */);
+
+/* Algorithmic bytes of one launch: (S + D) * count * element size for a reduce-copy,
+ * (1 + D) * S * count * element size for a gather-copy.  Host only; -1 on bad input. */
+int64_t lagom_comm_bytes(int op, int dtype, int nsrc, int ndst, int64_t count);
+
+/* ---------------------------------------------------------------------------------
+ * lagom_cost_model -- the unified overlap cost model (Eq. 1) over the contention wave
+ * model (Eq. 4-6, notation of Table 1).  Host only; no GPU is touched.
+ *
+ *   y_i = sum_j f_ij * g_ij,  g_ij = ceil(mu_i / ((lambda - NC_j) * TB_i)),
+ *   f_ij = theta_i + (lambda - NC_j) * TB_i * D_i / (B - V(NC_j, C_j)),
+ *   X = sum_j x_j, Y = sum_i y_i, Z = max(X, Y).
+ * x_j and V come from per-communication tables keyed by the exact (NC, NT, C).
+ * With several communications the two serialized queues are stepped wave by wave:
+ * communication j is active on [sum_{<j} x, sum_{<=j} x); a wave that starts under j
+ * (or after the last one: NC = 0, V = 0) retires min(remaining, (lambda-NC_j)*TB_i)
+ * workgroups and lasts f_ij; g_ij counts the waves issued under j.
+ */
+typedef struct { lagom_cfg cfg; double x_us; double v; } lagom_table_entry;
+typedef struct { const lagom_table_entry* entries; int32_t n; } lagom_comm_table;
+typedef struct { int64_t mu; int32_t tb; double d_bytes; double theta_us; } lagom_comp_model;
+typedef struct {
+    int32_t lambda;                  /* compute units                                   */
+    double  bw_peak;                 /* B, bytes per microsecond                        */
+    const lagom_comp_model* comps;   /* host [ncomp]                                    */
+    int32_t ncomp;
+    const lagom_comm_table* tables;  /* host [ncomm]                                    */
+    int32_t ncomm;
+} lagom_model;
+typedef struct {
+    double X_us, Y_us, Z_us;
+    double*  x_us;   /* host [ncomm] (nullable)                                         */
+    double*  y_us;   /* host [ncomp] (nullable)                                         */
+    int32_t* g;      /* host [ncomp * (ncomm + 1)] wave counts, last column = no
+                        communication active (nullable)                                 */
+} lagom_pred;
+
+/* Errors: LAGOM_EINVAL for a null pointer, ncomm != model ncomm, a configuration that
+ * is not in its table, NC < 1 or NC >= lambda, V < 0 or V >= B, x < 0, mu < 0, TB < 1. */
+int lagom_cost_model(const lagom_model* m, const lagom_cfg* cfgs, int ncomm, lagom_pred* out);
+
+/* ---------------------------------------------------------------------------------
+ * lagom_tune -- priority-based parameter search (Sec. 3.3-3.4: metric H of Eq. 7,
+ * the cost-effectiveness loop of Alg. 1, resource-efficient tuning of Alg. 2), or
+ * exhaustive search over the same space.  Host only; all measuring is done by the
+ * callback.
+ *
+ * Space: communication j moves on a ladder of levels 0..K_j-1; level l stands for
+ * (nc[min(l,n_nc-1)], nt[min(l,n_nt-1)], chunk[min(l,n_chunk-1)]) over strictly
+ * ascending grids, K_j = the longest grid (Alg. 2 raises NC, NT and C together).
+ *
+ * LAGOM_PRIORITY: all communications start at level 0 and are profiled once; if
+ * X < Y the search ends there.  Otherwise, repeatedly: take the not-done
+ * communication with the smallest H (initially 0.01; ties to the lowest index), raise
+ * it to the lowest level at which every parameter reached min(p*(1+lr), p_max) (one
+ * level when it has no lr yet), profile.  If its x rose: done, previous level kept.
+ * Else if X' < Y': done, and the new level is kept only if its Z is smaller.  Else the
+ * step is accepted, H_j = (Y'-Y)/(x_j-x_j') (+inf for a zero denominator),
+ * lr = (x_j-x_j')/x_j', and a communication that reached its top level is done.
+ * At most 1 + sum_j K_j profile calls.
+ * LAGOM_EXHAUSTIVE: every level vector in lexicographic order; the smallest Z wins,
+ * ties to the smallest level sum, then to the lexicographically smallest vector.
+ * Refused (LAGOM_EINVAL) above 2^20 vectors.
+ */
+typedef int (*lagom_profile_fn)(void* user, const lagom_cfg* cfgs, int ncomm,
+                                double* x_us /* out [ncomm] */, double* Y_us /* out */);
+
+typedef struct {
+    const int32_t* nc;    int32_t n_nc;
+    const int32_t* nt;    int32_t n_nt;
+    const int64_t* chunk; int32_t n_chunk;
+} lagom_tune_space;
+
+typedef struct {
+    int32_t comm;         /* -1 for the baseline profile                                */
+    int32_t level_from, level_to;
+    int32_t accepted, done;
+    double  xj_prev, xj_new;     /* NaN on the baseline step                            */
+    double  X, Y, Z;             /* of the profiled (trial) configuration               */
+    double  H, lr;               /* of `comm` after the step; lr NaN while undefined    */
+} lagom_trace_step;
+
+typedef struct {
+    lagom_trace_step* steps;     /* host [capacity] (nullable: then only counters)      */
+    int32_t capacity;
+    int32_t n;                   /* out: steps written (priority mode)                  */
+    int32_t calls;               /* out: profile calls made                             */
+    double  X, Y, Z;             /* out: of the returned configuration                  */
+    int32_t* levels;             /* host [ncomm] out (nullable)                         */
+} lagom_trace;
+
+typedef enum { LAGOM_PRIORITY = 0, LAGOM_EXHAUSTIVE = 1 } lagom_tune_mode;
+
+/*   spaces[ncomm], out_cfgs[ncomm] host arrays; trace nullable.
+ * Errors: LAGOM_EINVAL (null, ncomm < 1 or > LAGOM_MAX_COMMS, empty or non-ascending
+ * grid, trace too small), LAGOM_ECALLBACK (callback returned non-zero or a
+ * non-finite/negative time: out_cfgs holds the best configuration so far). */
+int lagom_tune(const lagom_tune_space* spaces, int ncomm, lagom_profile_fn profile, void* user,
+               int mode, lagom_cfg* out_cfgs, lagom_trace* trace);
+
+/* Ready-made callbacks for lagom_tune. */
+/* user = const lagom_model*: x_j from the tables, Y from lagom_cost_model.             */
+int lagom_model_profile(void* user, const lagom_cfg* cfgs, int ncomm, double* x_us, double* Y_us);
+/* user = const lagom_overlap_ctx*: one measured co-run of the group (ProfileTime).     */
+typedef struct {
+    const lagom_comm_desc* launches; int32_t nlaunch;
+    const lagom_gemm_desc* comps;    int32_t ncomp;
+    void* comm_stream; void* comp_stream;
+    int32_t warmup, iters;
+} lagom_overlap_ctx;
+int lagom_overlap_profile(void* user, const lagom_cfg* cfgs, int ncomm, double* x_us, double* Y_us);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LAGOM_H */

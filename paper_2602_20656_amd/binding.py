@@ -1,0 +1,454 @@
+"""ctypes binding of liblagom.so: argument marshalling only.
+
+Every function here has the name and the meaning of the C entry point it wraps
+(see include/lagom.h); all work is done by the native library.  Device buffers may be
+passed as torch tensors (their ``data_ptr()`` is taken) or as integer addresses; streams
+as ``torch.cuda.Stream`` objects or integer ``hipStream_t`` handles.
+
+There is no fallback: if the shared library has not been built, importing a symbol
+raises, and every call that returns an error code raises ``LagomError``.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import math
+import os
+from dataclasses import dataclass, field
+from typing import Callable, List, Optional, Sequence, Tuple, Union
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblagom.so")
+
+LAGOM_OK, LAGOM_EINVAL, LAGOM_EALIGN, LAGOM_EHIP, LAGOM_ECALLBACK = 0, -1, -2, -3, -4
+LAGOM_F32, LAGOM_BF16 = 0, 1
+LAGOM_REDUCE_COPY, LAGOM_GATHER_COPY = 0, 1
+LAGOM_ALONE_COMM, LAGOM_ALONE_COMP, LAGOM_CORUN = 0, 1, 2
+LAGOM_PRIORITY, LAGOM_EXHAUSTIVE = 0, 1
+LAGOM_MAX_SRCS, LAGOM_MAX_DSTS, LAGOM_MAX_LAUNCHES, LAGOM_MAX_COMMS = 16, 4, 256, 64
+
+EXPORTS = ["lagom_strerror", "lagom_last_error", "lagom_comm_kernel", "lagom_gemm", "lagom_gemm_describe",
+           "lagom_overlap_run", "lagom_contention_sweep", "lagom_comm_bytes", "lagom_cost_model", "lagom_tune",
+           "lagom_model_profile", "lagom_overlap_profile"]
+
+
+class LagomError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"lagom error {code}: {text}")
+        self.code = code
+
+
+# ------------------------------------------------------------------------ C structs
+class lagom_cfg(C.Structure):
+    _fields_ = [("nc", C.c_int32), ("nt", C.c_int32), ("chunk_bytes", C.c_int64)]
+
+
+class lagom_gemm_geometry(C.Structure):
+    _fields_ = [("mu", C.c_int64), ("tb", C.c_int32), ("d_bytes", C.c_double),
+                ("tile_m", C.c_int32), ("tile_n", C.c_int32), ("tile_k", C.c_int32), ("threads", C.c_int32)]
+
+
+class lagom_comm_desc(C.Structure):
+    _fields_ = [("op", C.c_int32), ("dtype", C.c_int32), ("srcs", C.POINTER(C.c_void_p)), ("nsrc", C.c_int32),
+                ("dsts", C.POINTER(C.c_void_p)), ("ndst", C.c_int32), ("count", C.c_int64), ("comm_id", C.c_int32)]
+
+
+class lagom_gemm_desc(C.Structure):
+    _fields_ = [("A", C.c_void_p), ("B", C.c_void_p), ("C", C.c_void_p), ("M", C.c_int64), ("N", C.c_int64),
+                ("K", C.c_int64), ("b_is_nk", C.c_int32), ("out_dtype", C.c_int32)]
+
+
+class lagom_timing(C.Structure):
+    _fields_ = [("X_us", C.c_double), ("Y_us", C.c_double), ("Z_us", C.c_double),
+                ("x_us", C.POINTER(C.c_double)), ("y_us", C.POINTER(C.c_double))]
+
+
+class lagom_sweep_point(C.Structure):
+    _fields_ = [("cfg", lagom_cfg), ("comm_alone_us", C.c_double), ("comm_corun_us", C.c_double),
+                ("comp_alone_us", C.c_double), ("comp_corun_us", C.c_double), ("z_corun_us", C.c_double),
+                ("v_alone", C.c_double), ("v_corun", C.c_double)]
+
+
+class lagom_table_entry(C.Structure):
+    _fields_ = [("cfg", lagom_cfg), ("x_us", C.c_double), ("v", C.c_double)]
+
+
+class lagom_comm_table(C.Structure):
+    _fields_ = [("entries", C.POINTER(lagom_table_entry)), ("n", C.c_int32)]
+
+
+class lagom_comp_model(C.Structure):
+    _fields_ = [("mu", C.c_int64), ("tb", C.c_int32), ("d_bytes", C.c_double), ("theta_us", C.c_double)]
+
+
+class lagom_model(C.Structure):
+    _fields_ = [("lambda_", C.c_int32), ("bw_peak", C.c_double), ("comps", C.POINTER(lagom_comp_model)),
+                ("ncomp", C.c_int32), ("tables", C.POINTER(lagom_comm_table)), ("ncomm", C.c_int32)]
+
+
+class lagom_pred(C.Structure):
+    _fields_ = [("X_us", C.c_double), ("Y_us", C.c_double), ("Z_us", C.c_double),
+                ("x_us", C.POINTER(C.c_double)), ("y_us", C.POINTER(C.c_double)), ("g", C.POINTER(C.c_int32))]
+
+
+class lagom_tune_space(C.Structure):
+    _fields_ = [("nc", C.POINTER(C.c_int32)), ("n_nc", C.c_int32), ("nt", C.POINTER(C.c_int32)), ("n_nt", C.c_int32),
+                ("chunk", C.POINTER(C.c_int64)), ("n_chunk", C.c_int32)]
+
+
+class lagom_trace_step(C.Structure):
+    _fields_ = [("comm", C.c_int32), ("level_from", C.c_int32), ("level_to", C.c_int32), ("accepted", C.c_int32),
+                ("done", C.c_int32), ("xj_prev", C.c_double), ("xj_new", C.c_double), ("X", C.c_double),
+                ("Y", C.c_double), ("Z", C.c_double), ("H", C.c_double), ("lr", C.c_double)]
+
+
+class lagom_trace(C.Structure):
+    _fields_ = [("steps", C.POINTER(lagom_trace_step)), ("capacity", C.c_int32), ("n", C.c_int32),
+                ("calls", C.c_int32), ("X", C.c_double), ("Y", C.c_double), ("Z", C.c_double),
+                ("levels", C.POINTER(C.c_int32))]
+
+
+class lagom_overlap_ctx(C.Structure):
+    _fields_ = [("launches", C.POINTER(lagom_comm_desc)), ("nlaunch", C.c_int32),
+                ("comps", C.POINTER(lagom_gemm_desc)), ("ncomp", C.c_int32),
+                ("comm_stream", C.c_void_p), ("comp_stream", C.c_void_p), ("warmup", C.c_int32), ("iters", C.c_int32)]
+
+
+PROFILE_FN = C.CFUNCTYPE(C.c_int, C.c_void_p, C.POINTER(lagom_cfg), C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double))
+
+# --------------------------------------------------------------------------- loading
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded native library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2602_20656_amd.build` "
+                              "(there is no CPU fallback)")
+        L = C.CDLL(LIB_PATH)
+        L.lagom_strerror.restype = C.c_char_p
+        L.lagom_strerror.argtypes = [C.c_int]
+        L.lagom_last_error.restype = C.c_char_p
+        L.lagom_comm_kernel.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_void_p), C.c_int, C.POINTER(C.c_void_p), C.c_int,
+                                        C.c_int64, C.POINTER(lagom_cfg), C.c_void_p]
+        L.lagom_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_void_p]
+        L.lagom_gemm_describe.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.c_int, C.POINTER(lagom_gemm_geometry)]
+        L.lagom_overlap_run.argtypes = [C.POINTER(lagom_comm_desc), C.c_int, C.POINTER(lagom_cfg), C.c_int,
+                                        C.POINTER(lagom_gemm_desc), C.c_int, C.c_void_p, C.c_void_p,
+                                        C.c_int, C.c_int, C.c_int, C.POINTER(lagom_timing)]
+        L.lagom_contention_sweep.argtypes = [C.POINTER(lagom_comm_desc), C.c_int, C.c_int, C.POINTER(lagom_gemm_desc), C.c_int,
+                                             C.POINTER(lagom_cfg), C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int,
+                                             C.POINTER(lagom_sweep_point)]
+        L.lagom_comm_bytes.restype = C.c_int64
+        L.lagom_comm_bytes.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int64]
+        L.lagom_cost_model.argtypes = [C.POINTER(lagom_model), C.POINTER(lagom_cfg), C.c_int, C.POINTER(lagom_pred)]
+        L.lagom_tune.argtypes = [C.POINTER(lagom_tune_space), C.c_int, C.c_void_p, C.c_void_p, C.c_int,
+                                 C.POINTER(lagom_cfg), C.POINTER(lagom_trace)]
+        for name in EXPORTS:
+            getattr(L, name)
+        _lib = L
+    return _lib
+
+
+def _check(rc: int) -> None:
+    if rc != LAGOM_OK:
+        L = lib()
+        raise LagomError(rc, f"{L.lagom_strerror(rc).decode()}: {L.lagom_last_error().decode()}")
+
+
+def _ptr(x) -> int:
+    return int(x.data_ptr()) if hasattr(x, "data_ptr") else int(x)
+
+
+def _stream(s) -> int:
+    if s is None:
+        return 0
+    return int(s.cuda_stream) if hasattr(s, "cuda_stream") else int(s)
+
+
+def _ptr_array(xs):
+    arr = (C.c_void_p * len(xs))()
+    for i, x in enumerate(xs):
+        arr[i] = _ptr(x)
+    return arr
+
+
+CfgLike = Union[Tuple[int, int, int], lagom_cfg]
+
+
+def _cfg(c: CfgLike) -> lagom_cfg:
+    return c if isinstance(c, lagom_cfg) else lagom_cfg(int(c[0]), int(c[1]), int(c[2]))
+
+
+def _cfg_array(cfgs: Sequence[CfgLike]):
+    arr = (lagom_cfg * max(len(cfgs), 1))()
+    for i, c in enumerate(cfgs):
+        arr[i] = _cfg(c)
+    return arr
+
+
+# ----------------------------------------------------------------------- entry points
+def lagom_comm_kernel(op: int, dt: int, srcs, dsts, count: int, cfg: CfgLike, stream=None) -> None:
+    c = _cfg(cfg)
+    _check(lib().lagom_comm_kernel(op, dt, _ptr_array(srcs), len(srcs), _ptr_array(dsts), len(dsts),
+                                   int(count), C.byref(c), _stream(stream)))
+
+
+def lagom_gemm(A, B, Cmat, M: int, N: int, K: int, b_is_nk: bool = True, out_dt: int = LAGOM_BF16, stream=None) -> None:
+    _check(lib().lagom_gemm(_ptr(A), _ptr(B), _ptr(Cmat), int(M), int(N), int(K), 1 if b_is_nk else 0, out_dt, _stream(stream)))
+
+
+def lagom_gemm_describe(M: int, N: int, K: int, out_dt: int = LAGOM_BF16) -> lagom_gemm_geometry:
+    g = lagom_gemm_geometry()
+    _check(lib().lagom_gemm_describe(int(M), int(N), int(K), out_dt, C.byref(g)))
+    return g
+
+
+def lagom_comm_bytes(op: int, dt: int, nsrc: int, ndst: int, count: int) -> int:
+    return int(lib().lagom_comm_bytes(op, dt, nsrc, ndst, int(count)))
+
+
+@dataclass
+class CommLaunch:
+    op: int
+    dtype: int
+    srcs: Sequence
+    dsts: Sequence
+    count: int
+    comm_id: int = 0
+
+
+@dataclass
+class GemmDesc:
+    A: object
+    B: object
+    C: object
+    M: int
+    N: int
+    K: int
+    b_is_nk: bool = True
+    out_dtype: int = LAGOM_BF16
+
+
+@dataclass
+class Timing:
+    X_us: float
+    Y_us: float
+    Z_us: float
+    x_us: List[float]
+    y_us: List[float]
+
+
+class _Group:
+    """C arrays for one overlap group; keeps the pointer arrays alive."""
+
+    def __init__(self, launches: Sequence[CommLaunch], comps: Sequence[GemmDesc]):
+        self.keep = []
+        self.nlaunch, self.ncomp = len(launches), len(comps)
+        self.L = (lagom_comm_desc * max(self.nlaunch, 1))()
+        for i, l in enumerate(launches):
+            s, d = _ptr_array(l.srcs), _ptr_array(l.dsts)
+            self.keep += [s, d]
+            self.L[i] = lagom_comm_desc(l.op, l.dtype, C.cast(s, C.POINTER(C.c_void_p)), len(l.srcs),
+                                        C.cast(d, C.POINTER(C.c_void_p)), len(l.dsts), int(l.count), int(l.comm_id))
+        self.G = (lagom_gemm_desc * max(self.ncomp, 1))()
+        for i, g in enumerate(comps):
+            self.G[i] = lagom_gemm_desc(_ptr(g.A), _ptr(g.B), _ptr(g.C), int(g.M), int(g.N), int(g.K),
+                                        1 if g.b_is_nk else 0, int(g.out_dtype))
+
+
+def lagom_overlap_run(launches: Sequence[CommLaunch], cfgs: Sequence[CfgLike], comps: Sequence[GemmDesc],
+                      comm_stream, comp_stream, warmup: int = 2, iters: int = 10, mode: int = LAGOM_CORUN) -> Timing:
+    grp = _Group(launches, comps)
+    ncfg = len(cfgs)
+    x = (C.c_double * max(ncfg, 1))()
+    y = (C.c_double * max(grp.ncomp, 1))()
+    t = lagom_timing(0.0, 0.0, 0.0, C.cast(x, C.POINTER(C.c_double)), C.cast(y, C.POINTER(C.c_double)))
+    _check(lib().lagom_overlap_run(grp.L, grp.nlaunch, _cfg_array(cfgs), ncfg, grp.G, grp.ncomp,
+                                   _stream(comm_stream), _stream(comp_stream), warmup, iters, mode, C.byref(t)))
+    return Timing(t.X_us, t.Y_us, t.Z_us, list(x)[:ncfg], list(y)[:grp.ncomp])
+
+
+@dataclass
+class SweepPoint:
+    cfg: Tuple[int, int, int]
+    comm_alone_us: float
+    comm_corun_us: float
+    comp_alone_us: float
+    comp_corun_us: float
+    z_corun_us: float
+    v_alone: float
+    v_corun: float
+
+
+def lagom_contention_sweep(launches: Sequence[CommLaunch], ncfg: int, comps: Sequence[GemmDesc], points: Sequence[CfgLike],
+                           comm_stream, comp_stream, warmup: int = 2, iters: int = 10) -> List[SweepPoint]:
+    grp = _Group(launches, comps)
+    out = (lagom_sweep_point * len(points))()
+    _check(lib().lagom_contention_sweep(grp.L, grp.nlaunch, ncfg, grp.G, grp.ncomp, _cfg_array(points), len(points),
+                                        _stream(comm_stream), _stream(comp_stream), warmup, iters, out))
+    return [SweepPoint((o.cfg.nc, o.cfg.nt, o.cfg.chunk_bytes), o.comm_alone_us, o.comm_corun_us, o.comp_alone_us,
+                       o.comp_corun_us, o.z_corun_us, o.v_alone, o.v_corun) for o in out]
+
+
+# ----------------------------------------------------------------- cost model (host)
+@dataclass
+class CompModel:
+    mu: int
+    tb: int
+    d_bytes: float
+    theta_us: float
+
+
+@dataclass
+class Model:
+    lam: int
+    bw_peak: float                                    # bytes per microsecond
+    comps: List[CompModel]
+    tables: List[dict] = field(default_factory=list)  # per communication: (nc, nt, chunk) -> (x_us, v)
+
+
+@dataclass
+class Pred:
+    X_us: float
+    Y_us: float
+    Z_us: float
+    x_us: List[float]
+    y_us: List[float]
+    g: List[List[int]]
+
+
+class _CModel:
+    def __init__(self, m: Model):
+        self.comps = (lagom_comp_model * max(len(m.comps), 1))()
+        for i, c in enumerate(m.comps):
+            self.comps[i] = lagom_comp_model(int(c.mu), int(c.tb), float(c.d_bytes), float(c.theta_us))
+        self.entry_arrays = []
+        self.tables = (lagom_comm_table * max(len(m.tables), 1))()
+        for j, t in enumerate(m.tables):
+            arr = (lagom_table_entry * max(len(t), 1))()
+            for e, (k, (x, v)) in enumerate(t.items()):
+                arr[e] = lagom_table_entry(lagom_cfg(int(k[0]), int(k[1]), int(k[2])), float(x), float(v))
+            self.entry_arrays.append(arr)
+            self.tables[j] = lagom_comm_table(C.cast(arr, C.POINTER(lagom_table_entry)), len(t))
+        self.c = lagom_model(int(m.lam), float(m.bw_peak), C.cast(self.comps, C.POINTER(lagom_comp_model)), len(m.comps),
+                             C.cast(self.tables, C.POINTER(lagom_comm_table)), len(m.tables))
+
+
+def lagom_cost_model(model: Model, cfgs: Sequence[CfgLike]) -> Pred:
+    cm = _CModel(model)
+    n, mcomp = len(cfgs), len(model.comps)
+    x = (C.c_double * max(n, 1))()
+    y = (C.c_double * max(mcomp, 1))()
+    g = (C.c_int32 * max(mcomp * (n + 1), 1))()
+    p = lagom_pred(0.0, 0.0, 0.0, C.cast(x, C.POINTER(C.c_double)), C.cast(y, C.POINTER(C.c_double)), C.cast(g, C.POINTER(C.c_int32)))
+    _check(lib().lagom_cost_model(C.byref(cm.c), _cfg_array(cfgs), n, C.byref(p)))
+    return Pred(p.X_us, p.Y_us, p.Z_us, list(x)[:n], list(y)[:mcomp],
+                [[g[i * (n + 1) + s] for s in range(n + 1)] for i in range(mcomp)])
+
+
+# ------------------------------------------------------------------------ tuner (host)
+@dataclass
+class Space:
+    nc: Sequence[int]
+    nt: Sequence[int]
+    chunk: Sequence[int]
+
+
+@dataclass
+class TraceStep:
+    comm: int
+    level_from: int
+    level_to: int
+    accepted: bool
+    done: bool
+    xj_prev: float
+    xj_new: float
+    X: float
+    Y: float
+    Z: float
+    H: float
+    lr: float
+
+
+@dataclass
+class TuneResult:
+    cfgs: List[Tuple[int, int, int]]
+    levels: List[int]
+    X: float
+    Y: float
+    Z: float
+    calls: int
+    trace: List[TraceStep]
+    code: int = LAGOM_OK
+
+
+@dataclass
+class OverlapProfile:
+    """Measured ProfileTime: one co-run of the group per call (native callback)."""
+    launches: Sequence[CommLaunch]
+    comps: Sequence[GemmDesc]
+    comm_stream: object
+    comp_stream: object
+    warmup: int = 1
+    iters: int = 5
+
+
+ProfileLike = Union[Callable[[List[Tuple[int, int, int]]], Tuple[Sequence[float], float]], Model, OverlapProfile]
+
+
+def lagom_tune(spaces: Sequence[Space], profile: ProfileLike, mode: int = LAGOM_PRIORITY,
+               raise_on_callback_error: bool = True) -> TuneResult:
+    """`profile` is a Python callable cfgs -> (x list, Y), a ``Model`` (the native cost-model callback is
+    used) or an ``OverlapProfile`` (the native measuring callback is used)."""
+    L = lib()
+    n = len(spaces)
+    keep = []
+    sp = (lagom_tune_space * max(n, 1))()
+    total_levels = 0
+    for j, s in enumerate(spaces):
+        a = (C.c_int32 * max(len(s.nc), 1))(*[int(v) for v in s.nc])
+        b = (C.c_int32 * max(len(s.nt), 1))(*[int(v) for v in s.nt])
+        c = (C.c_int64 * max(len(s.chunk), 1))(*[int(v) for v in s.chunk])
+        keep += [a, b, c]
+        sp[j] = lagom_tune_space(C.cast(a, C.POINTER(C.c_int32)), len(s.nc), C.cast(b, C.POINTER(C.c_int32)), len(s.nt),
+                                 C.cast(c, C.POINTER(C.c_int64)), len(s.chunk))
+        total_levels += max(len(s.nc), len(s.nt), len(s.chunk))
+    cap = total_levels + 2
+    steps = (lagom_trace_step * cap)()
+    levels = (C.c_int32 * max(n, 1))()
+    tr = lagom_trace(C.cast(steps, C.POINTER(lagom_trace_step)), cap, 0, 0, math.nan, math.nan, math.nan,
+                     C.cast(levels, C.POINTER(C.c_int32)))
+    out = (lagom_cfg * max(n, 1))()
+
+    if isinstance(profile, Model):
+        cm = _CModel(profile)
+        keep.append(cm)
+        fn, user = C.cast(L.lagom_model_profile, C.c_void_p), C.cast(C.pointer(cm.c), C.c_void_p)
+    elif isinstance(profile, OverlapProfile):
+        grp = _Group(profile.launches, profile.comps)
+        ctx = lagom_overlap_ctx(C.cast(grp.L, C.POINTER(lagom_comm_desc)), grp.nlaunch,
+                                C.cast(grp.G, C.POINTER(lagom_gemm_desc)), grp.ncomp,
+                                _stream(profile.comm_stream), _stream(profile.comp_stream), profile.warmup, profile.iters)
+        keep += [grp, ctx]
+        fn, user = C.cast(L.lagom_overlap_profile, C.c_void_p), C.cast(C.pointer(ctx), C.c_void_p)
+    else:
+        def _cb(_user, cfgs, ncomm, x_out, y_out):
+            try:
+                x, Y = profile([(cfgs[i].nc, cfgs[i].nt, cfgs[i].chunk_bytes) for i in range(ncomm)])
+                for i in range(ncomm):
+                    x_out[i] = float(x[i])
+                y_out[0] = float(Y)
+                return 0
+            except Exception:
+                return 1
+        cb = PROFILE_FN(_cb)
+        keep.append(cb)
+        fn, user = C.cast(cb, C.c_void_p), None
+    rc = L.lagom_tune(sp, n, fn, user, mode, out, C.byref(tr))
+    if rc != LAGOM_OK and not (rc == LAGOM_ECALLBACK and not raise_on_callback_error):
+        _check(rc)
+    trace = [TraceStep(s.comm, s.level_from, s.level_to, bool(s.accepted), bool(s.done), s.xj_prev, s.xj_new,
+                       s.X, s.Y, s.Z, s.H, s.lr) for s in steps[:tr.n]]
+    return TuneResult([(o.nc, o.nt, o.chunk_bytes) for o in out[:n]], list(levels)[:n], tr.X, tr.Y, tr.Z, tr.calls, trace, rc)

@@ -1,0 +1,282 @@
+// lagom_comm_kernel: the local data-movement step of a chunked collective on gfx950.
+//
+// Mapping of the paper's three resource parameters (Sec. 2.2, Sec. 3.2) onto CDNA4:
+//   NC  channels   -> workgroups of the launch (each occupies wave slots of one CU),
+//   NT  threads    -> workgroup size (NT/64 wavefronts),
+//   C   chunk size -> the unit of work a channel takes at a time: chunk g of the byte
+//                     range is moved by workgroup g mod NC.
+// Inside a chunk every lane moves 16-byte vectors; consecutive lanes touch consecutive
+// vectors, so one wavefront instruction covers 1 KiB of contiguous HBM.  A lane keeps
+// kInFlight vectors per source outstanding before it uses any of them: with NC far below
+// the 256 compute units, bytes in flight per workgroup are what bounds the bandwidth.
+//
+// Arithmetic (reduce-copy): fp32 additions in source order, bf16 widened exactly by a
+// 16-bit shift, one round-to-nearest-even at the store.  Only additions are used, so no
+// fused operation can change the rounding.
+#include <hip/hip_runtime.h>
+#include "common.h"
+
+namespace {
+
+struct CommArgs {
+    const char* src[LAGOM_MAX_SRCS];
+    char* dst[LAGOM_MAX_DSTS];
+    int32_t nsrc, ndst;
+    int64_t shard_bytes;       // bytes per source
+    int64_t chunk_bytes;       // C
+    int64_t chunks_per_shard;
+    int64_t total_chunks;      // reduce: chunks_per_shard; gather: nsrc * chunks_per_shard
+};
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ u32x4 ld16(const char* p) { return *reinterpret_cast<const u32x4*>(p); }
+__device__ __forceinline__ void st16(char* p, u32x4 v) { *reinterpret_cast<u32x4*>(p) = v; }
+
+// bf16 is the upper half of an fp32 pattern.
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// fp32 -> bf16 bits, round to nearest, ties to even; NaN keeps a quiet payload.
+__device__ __forceinline__ uint32_t bf16_round(float f) {
+    const uint32_t u = __float_as_uint(f);
+    const uint32_t upper = u >> 16, lower = u & 0xffffu;
+    const uint32_t up = (lower > 0x8000u || (lower == 0x8000u && (upper & 1u))) ? 1u : 0u;
+    const uint32_t r = upper + up;
+    return ((u & 0x7fffffffu) > 0x7f800000u) ? (upper | 0x0040u) : r;
+}
+
+template <int DT>
+struct Acc;
+
+// fp32: one 16-byte vector = 4 elements
+template <>
+struct Acc<LAGOM_F32> {
+    f32x4 a;
+    __device__ __forceinline__ void init(u32x4 v) { a = __builtin_bit_cast(f32x4, v); }
+    __device__ __forceinline__ void add(u32x4 v) { a = a + __builtin_bit_cast(f32x4, v); }
+    __device__ __forceinline__ u32x4 result() const { return __builtin_bit_cast(u32x4, a); }
+};
+
+// bf16: one 16-byte vector = 8 elements, accumulated as 8 fp32
+template <>
+struct Acc<LAGOM_BF16> {
+    float a[8];
+    __device__ __forceinline__ void init(u32x4 v) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { a[2 * i] = bf16_lo(v[i]); a[2 * i + 1] = bf16_hi(v[i]); }
+    }
+    __device__ __forceinline__ void add(u32x4 v) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { a[2 * i] = a[2 * i] + bf16_lo(v[i]); a[2 * i + 1] = a[2 * i + 1] + bf16_hi(v[i]); }
+    }
+    __device__ __forceinline__ u32x4 result() const {
+        u32x4 r;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r[i] = bf16_round(a[2 * i]) | (bf16_round(a[2 * i + 1]) << 16);
+        return r;
+    }
+};
+
+// One element of a short tail (fewer than 16 bytes left at the end of the buffer).
+template <int DT>
+__device__ __forceinline__ void reduce_tail_element(const CommArgs& p, int64_t byte_off) {
+    if (DT == LAGOM_F32) {
+        float acc = *reinterpret_cast<const float*>(p.src[0] + byte_off);
+        for (int s = 1; s < p.nsrc; ++s) acc = acc + *reinterpret_cast<const float*>(p.src[s] + byte_off);
+        for (int d = 0; d < p.ndst; ++d) *reinterpret_cast<float*>(p.dst[d] + byte_off) = acc;
+    } else {
+        float acc = bf16_lo(*reinterpret_cast<const uint16_t*>(p.src[0] + byte_off));
+        for (int s = 1; s < p.nsrc; ++s) acc = acc + bf16_lo(*reinterpret_cast<const uint16_t*>(p.src[s] + byte_off));
+        const uint16_t r = (uint16_t)bf16_round(acc);
+        for (int d = 0; d < p.ndst; ++d) *reinterpret_cast<uint16_t*>(p.dst[d] + byte_off) = r;
+    }
+}
+
+// S > 0: number of sources known at compile time (all loads of a batch issued before the
+// first add).  S == 0: any number of sources, loaded source by source.
+// U: 16-byte vectors a lane has in flight per source.
+template <int DT, int S, int U>
+__global__ void __launch_bounds__(1024) reduce_copy_kernel(const CommArgs p) {
+    const int nt = blockDim.x;
+    const int tid = threadIdx.x;
+    const int esize = DT == LAGOM_F32 ? 4 : 2;
+    for (int64_t g = blockIdx.x; g < p.total_chunks; g += gridDim.x) {
+        const int64_t base = g * p.chunk_bytes;
+        const int64_t left = p.shard_bytes - base;
+        const int64_t len = left < p.chunk_bytes ? left : p.chunk_bytes;
+        const int64_t nvec = len >> 4;
+        int64_t v = tid;
+        if constexpr (S > 0) {
+            // full batches: U vectors per source per lane, strided by the workgroup size
+            for (; v + (int64_t)(U - 1) * nt < nvec; v += (int64_t)U * nt) {
+                u32x4 r[S][U];
+#pragma unroll
+                for (int s = 0; s < S; ++s)
+#pragma unroll
+                    for (int u = 0; u < U; ++u) r[s][u] = ld16(p.src[s] + base + ((v + (int64_t)u * nt) << 4));
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    Acc<DT> acc;
+                    acc.init(r[0][u]);
+#pragma unroll
+                    for (int s = 1; s < S; ++s) acc.add(r[s][u]);
+                    const u32x4 o = acc.result();
+                    for (int d = 0; d < p.ndst; ++d) st16(p.dst[d] + base + ((v + (int64_t)u * nt) << 4), o);
+                }
+            }
+        }
+        // remaining vectors (and every vector when S == 0)
+        for (; v < nvec; v += nt) {
+            const int64_t off = base + (v << 4);
+            Acc<DT> acc;
+            acc.init(ld16(p.src[0] + off));
+            const int ns = S > 0 ? S : p.nsrc;
+            for (int s = 1; s < ns; ++s) acc.add(ld16(p.src[s] + off));
+            const u32x4 o = acc.result();
+            for (int d = 0; d < p.ndst; ++d) st16(p.dst[d] + off, o);
+        }
+        // fewer than 16 bytes at the very end of the buffer
+        const int tail_elems = (int)(len & 15) / esize;
+        if (tid < tail_elems) reduce_tail_element<DT>(p, base + (nvec << 4) + (int64_t)tid * esize);
+    }
+}
+
+// Gather-copy with 16-byte vectors; needs shard_bytes % 16 == 0 (or a single shard) so that
+// every shard starts 16-byte aligned in the destination.
+template <int U>
+__global__ void __launch_bounds__(1024) gather_copy_kernel(const CommArgs p) {
+    const int nt = blockDim.x;
+    const int tid = threadIdx.x;
+    for (int64_t g = blockIdx.x; g < p.total_chunks; g += gridDim.x) {
+        const int64_t r = g / p.chunks_per_shard;
+        const int64_t base = (g - r * p.chunks_per_shard) * p.chunk_bytes;
+        const int64_t left = p.shard_bytes - base;
+        const int64_t len = left < p.chunk_bytes ? left : p.chunk_bytes;
+        const int64_t nvec = len >> 4;
+        const char* src = p.src[r] + base;
+        const int64_t dst_off = r * p.shard_bytes + base;
+        int64_t v = tid;
+        for (; v + (int64_t)(U - 1) * nt < nvec; v += (int64_t)U * nt) {
+            u32x4 x[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) x[u] = ld16(src + ((v + (int64_t)u * nt) << 4));
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                for (int d = 0; d < p.ndst; ++d) st16(p.dst[d] + dst_off + ((v + (int64_t)u * nt) << 4), x[u]);
+        }
+        for (; v < nvec; v += nt) {
+            const u32x4 x = ld16(src + (v << 4));
+            for (int d = 0; d < p.ndst; ++d) st16(p.dst[d] + dst_off + (v << 4), x);
+        }
+        const int tail = (int)(len & 15);          // single shard only: bytes, copied one by one
+        if (tid < tail) {
+            const char b = src[(nvec << 4) + tid];
+            for (int d = 0; d < p.ndst; ++d) p.dst[d][dst_off + (nvec << 4) + tid] = b;
+        }
+    }
+}
+
+// Gather-copy for shards whose byte length is not a multiple of 16: destinations of shards
+// r >= 1 are then only element-aligned, so elements (2 or 4 bytes) are copied one by one.
+template <typename E>
+__global__ void __launch_bounds__(1024) gather_copy_elements_kernel(const CommArgs p) {
+    const int nt = blockDim.x;
+    for (int64_t g = blockIdx.x; g < p.total_chunks; g += gridDim.x) {
+        const int64_t r = g / p.chunks_per_shard;
+        const int64_t base = (g - r * p.chunks_per_shard) * p.chunk_bytes;
+        const int64_t left = p.shard_bytes - base;
+        const int64_t len = left < p.chunk_bytes ? left : p.chunk_bytes;
+        const int64_t n = len / (int64_t)sizeof(E);
+        const E* src = reinterpret_cast<const E*>(p.src[r] + base);
+        for (int64_t i = threadIdx.x; i < n; i += nt) {
+            const E x = src[i];
+            for (int d = 0; d < p.ndst; ++d) reinterpret_cast<E*>(p.dst[d] + r * p.shard_bytes + base)[i] = x;
+        }
+    }
+}
+
+template <int DT>
+void launch_reduce(const CommArgs& a, dim3 grid, dim3 block, hipStream_t st) {
+    switch (a.nsrc) {
+        case 1: hipLaunchKernelGGL((reduce_copy_kernel<DT, 1, 8>), grid, block, 0, st, a); break;
+        case 2: hipLaunchKernelGGL((reduce_copy_kernel<DT, 2, 8>), grid, block, 0, st, a); break;
+        case 3: hipLaunchKernelGGL((reduce_copy_kernel<DT, 3, 4>), grid, block, 0, st, a); break;
+        case 4: hipLaunchKernelGGL((reduce_copy_kernel<DT, 4, 4>), grid, block, 0, st, a); break;
+        case 8: hipLaunchKernelGGL((reduce_copy_kernel<DT, 8, 2>), grid, block, 0, st, a); break;
+        default: hipLaunchKernelGGL((reduce_copy_kernel<DT, 0, 1>), grid, block, 0, st, a); break;
+    }
+}
+
+}  // namespace
+
+namespace lagom {
+
+int check_cfg(const lagom_cfg* cfg) {
+    if (!cfg) return fail(LAGOM_EINVAL, "null configuration");
+    if (cfg->nc < 1 || cfg->nc > 65535) return fail(LAGOM_EINVAL, "nc=%d outside 1..65535", cfg->nc);
+    if (cfg->nt < 64 || cfg->nt > 1024 || cfg->nt % 64) return fail(LAGOM_EINVAL, "nt=%d must be a multiple of 64 in 64..1024", cfg->nt);
+    if (cfg->chunk_bytes < 16 || cfg->chunk_bytes % 16) return fail(LAGOM_EINVAL, "chunk_bytes=%lld must be a positive multiple of 16", (long long)cfg->chunk_bytes);
+    return LAGOM_OK;
+}
+
+int check_comm_args(int op, int dtype, const void* const* srcs, int nsrc, void* const* dsts, int ndst, int64_t count) {
+    if (op != LAGOM_REDUCE_COPY && op != LAGOM_GATHER_COPY) return fail(LAGOM_EINVAL, "unknown op %d", op);
+    if (elem_size(dtype) == 0) return fail(LAGOM_EINVAL, "unknown dtype %d", dtype);
+    if (!srcs || !dsts) return fail(LAGOM_EINVAL, "null pointer array");
+    if (nsrc < 1 || nsrc > LAGOM_MAX_SRCS) return fail(LAGOM_EINVAL, "nsrc=%d outside 1..%d", nsrc, LAGOM_MAX_SRCS);
+    if (ndst < 1 || ndst > LAGOM_MAX_DSTS) return fail(LAGOM_EINVAL, "ndst=%d outside 1..%d", ndst, LAGOM_MAX_DSTS);
+    if (count < 0 || count > (int64_t)1 << 40) return fail(LAGOM_EINVAL, "count=%lld out of range", (long long)count);
+    for (int s = 0; s < nsrc; ++s) {
+        if (!srcs[s]) return fail(LAGOM_EINVAL, "source %d is null", s);
+        if ((uintptr_t)srcs[s] & 15) return fail(LAGOM_EALIGN, "source %d is not 16-byte aligned", s);
+    }
+    for (int d = 0; d < ndst; ++d) {
+        if (!dsts[d]) return fail(LAGOM_EINVAL, "destination %d is null", d);
+        if ((uintptr_t)dsts[d] & 15) return fail(LAGOM_EALIGN, "destination %d is not 16-byte aligned", d);
+    }
+    return LAGOM_OK;
+}
+
+}  // namespace lagom
+
+extern "C" int64_t lagom_comm_bytes(int op, int dtype, int nsrc, int ndst, int64_t count) {
+    const int es = lagom::elem_size(dtype);
+    if (es == 0 || nsrc < 1 || ndst < 1 || count < 0) return -1;
+    if (op == LAGOM_REDUCE_COPY) return (int64_t)(nsrc + ndst) * count * es;
+    if (op == LAGOM_GATHER_COPY) return (int64_t)(1 + ndst) * nsrc * count * es;
+    return -1;
+}
+
+extern "C" int lagom_comm_kernel(lagom_op op, lagom_dtype dt, const void* const* srcs, int nsrc,
+                                 void* const* dsts, int ndst, int64_t count, const lagom_cfg* cfg, void* hip_stream) {
+    if (int rc = lagom::check_comm_args(op, dt, srcs, nsrc, dsts, ndst, count)) return rc;
+    if (int rc = lagom::check_cfg(cfg)) return rc;
+    if (count == 0) return LAGOM_OK;
+
+    CommArgs a{};
+    for (int s = 0; s < nsrc; ++s) a.src[s] = static_cast<const char*>(srcs[s]);
+    for (int d = 0; d < ndst; ++d) a.dst[d] = static_cast<char*>(dsts[d]);
+    a.nsrc = nsrc; a.ndst = ndst;
+    a.shard_bytes = count * lagom::elem_size(dt);
+    a.chunk_bytes = cfg->chunk_bytes;
+    a.chunks_per_shard = (a.shard_bytes + a.chunk_bytes - 1) / a.chunk_bytes;
+    a.total_chunks = op == LAGOM_REDUCE_COPY ? a.chunks_per_shard : a.chunks_per_shard * nsrc;
+
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const dim3 grid((unsigned)cfg->nc), block((unsigned)cfg->nt);
+    if (op == LAGOM_REDUCE_COPY) {
+        if (dt == LAGOM_F32) launch_reduce<LAGOM_F32>(a, grid, block, st);
+        else launch_reduce<LAGOM_BF16>(a, grid, block, st);
+    } else if (nsrc == 1 || (a.shard_bytes & 15) == 0) {
+        hipLaunchKernelGGL((gather_copy_kernel<8>), grid, block, 0, st, a);
+    } else if (dt == LAGOM_F32) {
+        hipLaunchKernelGGL((gather_copy_elements_kernel<uint32_t>), grid, block, 0, st, a);
+    } else {
+        hipLaunchKernelGGL((gather_copy_elements_kernel<uint16_t>), grid, block, 0, st, a);
+    }
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return lagom::fail(LAGOM_EHIP, "comm kernel launch: %s", hipGetErrorString(e));
+    return LAGOM_OK;
+}

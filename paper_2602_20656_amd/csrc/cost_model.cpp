@@ -1,0 +1,105 @@
+// Unified overlap cost model (Eq. 1) over the contention wave model (Eq. 4-6, Table 1).
+// Host only.  Compiled with floating-point contraction off: every product and sum below
+// is rounded separately, in the order written.
+#include <cmath>
+#include <vector>
+#include "common.h"
+
+namespace {
+
+struct CommPoint { double x, v; int nc; };
+
+int lookup(const lagom_comm_table& t, const lagom_cfg& c, int j, CommPoint* out) {
+    if (t.n < 0 || (t.n > 0 && !t.entries)) return lagom::fail(LAGOM_EINVAL, "communication %d: bad table", j);
+    for (int e = 0; e < t.n; ++e) {
+        const lagom_table_entry& te = t.entries[e];
+        if (te.cfg.nc == c.nc && te.cfg.nt == c.nt && te.cfg.chunk_bytes == c.chunk_bytes) {
+            out->x = te.x_us; out->v = te.v; out->nc = c.nc;
+            return LAGOM_OK;
+        }
+    }
+    return lagom::fail(LAGOM_EINVAL, "communication %d: configuration (nc=%d, nt=%d, chunk=%lld) is not in its table",
+                       j, c.nc, c.nt, (long long)c.chunk_bytes);
+}
+
+// Eq. 6 with cap = (lambda - NC) * TB workgroups in flight.
+inline double wave_time(double theta, int64_t cap, double d_bytes, double bw_peak, double v) {
+    return theta + ((double)cap * d_bytes) / (bw_peak - v);
+}
+
+}  // namespace
+
+extern "C" int lagom_cost_model(const lagom_model* m, const lagom_cfg* cfgs, int ncomm, lagom_pred* out) {
+    if (!m || !out || (ncomm > 0 && !cfgs)) return lagom::fail(LAGOM_EINVAL, "null argument");
+    if (ncomm != m->ncomm || ncomm < 0 || ncomm > LAGOM_MAX_COMMS)
+        return lagom::fail(LAGOM_EINVAL, "ncomm=%d does not match the model's %d (max %d)", ncomm, m->ncomm, LAGOM_MAX_COMMS);
+    if (m->ncomp < 0 || (m->ncomp > 0 && !m->comps) || (ncomm > 0 && !m->tables))
+        return lagom::fail(LAGOM_EINVAL, "bad model arrays");
+    if (m->lambda < 1 || !(m->bw_peak > 0.0)) return lagom::fail(LAGOM_EINVAL, "lambda and peak bandwidth must be positive");
+
+    const int N = ncomm;
+    std::vector<CommPoint> c(N);
+    for (int j = 0; j < N; ++j) {
+        if (int rc = lookup(m->tables[j], cfgs[j], j, &c[j])) return rc;
+        if (c[j].nc < 1 || c[j].nc >= m->lambda)
+            return lagom::fail(LAGOM_EINVAL, "communication %d: NC=%d outside 1..lambda-1", j, c[j].nc);
+        if (!(c[j].v >= 0.0 && c[j].v < m->bw_peak))
+            return lagom::fail(LAGOM_EINVAL, "communication %d: V outside [0, peak bandwidth)", j);
+        if (!(c[j].x >= 0.0) || !std::isfinite(c[j].x))
+            return lagom::fail(LAGOM_EINVAL, "communication %d: x must be finite and non-negative", j);
+    }
+    // communication j is active on [T[j], T[j+1])
+    std::vector<double> T(N + 1, 0.0);
+    for (int j = 0; j < N; ++j) T[j + 1] = T[j] + c[j].x;
+    const double X = T[N];
+
+    std::vector<double> f(N + 1);
+    std::vector<int32_t> g(N + 1);
+    double t0 = 0.0, Y = 0.0;
+    for (int i = 0; i < m->ncomp; ++i) {
+        const lagom_comp_model& cp = m->comps[i];
+        if (cp.mu < 0 || cp.tb < 1 || !(cp.d_bytes >= 0.0) || !std::isfinite(cp.theta_us))
+            return lagom::fail(LAGOM_EINVAL, "computation %d: bad description", i);
+        for (int s = 0; s <= N; ++s) { f[s] = 0.0; g[s] = 0; }
+        int64_t rem = cp.mu;
+        double t = t0, y = 0.0;
+        while (rem > 0) {
+            int slot = N;
+            for (int j = 0; j < N; ++j)
+                if (t < T[j + 1]) { slot = j; break; }
+            int64_t cap;
+            if (slot < N) {
+                cap = (int64_t)(m->lambda - c[slot].nc) * cp.tb;
+                f[slot] = wave_time(cp.theta_us, cap, cp.d_bytes, m->bw_peak, c[slot].v);
+            } else {
+                cap = (int64_t)m->lambda * cp.tb;
+                f[slot] = wave_time(cp.theta_us, cap, cp.d_bytes, m->bw_peak, 0.0);
+            }
+            g[slot] += 1;
+            rem -= rem < cap ? rem : cap;
+            y = 0.0;
+            for (int s = 0; s <= N; ++s)            // Eq. 4, terms in ascending j
+                if (g[s] > 0) y = y + f[s] * (double)g[s];
+            t = t0 + y;
+        }
+        if (out->y_us) out->y_us[i] = y;
+        if (out->g) for (int s = 0; s <= N; ++s) out->g[(int64_t)i * (N + 1) + s] = g[s];
+        t0 = t0 + y;
+        Y = Y + y;
+    }
+    if (out->x_us) for (int j = 0; j < N; ++j) out->x_us[j] = c[j].x;
+    out->X_us = X;
+    out->Y_us = Y;
+    out->Z_us = X > Y ? X : Y;
+    return LAGOM_OK;
+}
+
+extern "C" int lagom_model_profile(void* user, const lagom_cfg* cfgs, int ncomm, double* x_us, double* Y_us) {
+    if (!user || !x_us || !Y_us) return lagom::fail(LAGOM_EINVAL, "null argument");
+    lagom_pred p{};
+    p.x_us = x_us;
+    int rc = lagom_cost_model(static_cast<const lagom_model*>(user), cfgs, ncomm, &p);
+    if (rc) return rc;
+    *Y_us = p.Y_us;
+    return LAGOM_OK;
+}

@@ -1,0 +1,229 @@
+// lagom_gemm: C[M,N] = A[M,K] . B, bf16 inputs, fp32 accumulation on the gfx950 matrix
+// cores (v_mfma_f32_32x32x16_bf16), the computation whose slow-down the overlap model
+// describes (Sec. 3.2, Fig. 3).
+//
+// Tiling: one workgroup of 256 threads (4 wavefronts, 2 x 2) owns a 256 x 256 tile of C and
+// walks K in steps of 64.  Each wavefront owns 128 x 128 = 4 x 4 MFMA tiles of 32 x 32, i.e.
+// 256 fp32 accumulators per lane.  A and B tiles are staged in LDS as rows of 64 bf16
+// (128 bytes = eight 16-byte groups) with the group index XOR-ed by the row's low three bits,
+// so that the 16-byte operand reads of 8 consecutive rows spread over all banks.
+// The next K-step is fetched from HBM/L2 into registers while the matrix cores work on the
+// current one.  Workgroup ids are remapped so that the workgroups of one XCD (ids equal
+// modulo 8) cover a compact block of tiles and share A/B panels in that XCD's L2.
+#include <hip/hip_runtime.h>
+#include "common.h"
+
+namespace {
+
+constexpr int BM = 256, BN = 256, BK = 64, THREADS = 256;
+constexpr int VEC_PER_THREAD = (BM * BK / 8) / THREADS;  // 16-byte vectors of one operand tile per thread = 8
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct GemmArgs {
+    const uint16_t* A;
+    const uint16_t* B;
+    void* C;
+    int64_t M, N, K;
+    int32_t tiles_m, tiles_n;
+};
+
+__device__ __forceinline__ uint32_t bf16_round_bits(float f) {
+    const uint32_t u = __float_as_uint(f);
+    const uint32_t upper = u >> 16, lower = u & 0xffffu;
+    const uint32_t r = upper + ((lower > 0x8000u || (lower == 0x8000u && (upper & 1u))) ? 1u : 0u);
+    return ((u & 0x7fffffffu) > 0x7f800000u) ? (upper | 0x0040u) : r;
+}
+
+// index (in 16-byte units) of group `cg` of row `row` in a swizzled [rows][8] tile
+__device__ __forceinline__ int swz(int row, int cg) { return row * 8 + (cg ^ (row & 7)); }
+
+// Workgroup id -> (tile_m, tile_n).  Hardware deals consecutive ids round-robin to the 8 XCDs;
+// id = x + 8*q is given the q-th tile of the x-th eighth of the tile list, and the list itself
+// runs down columns of 8 tile-rows so that neighbours share B panels and reuse A panels.
+__device__ __forceinline__ void tile_of(int id, int tiles_m, int tiles_n, int* tm, int* tn) {
+    const int total = tiles_m * tiles_n;
+    int lin = id;
+    if ((total & 7) == 0) lin = (id & 7) * (total >> 3) + (id >> 3);
+    constexpr int GROUP = 8;
+    const int per_group = GROUP * tiles_n;
+    const int grp = lin / per_group;
+    const int first_m = grp * GROUP;
+    const int rows = tiles_m - first_m < GROUP ? tiles_m - first_m : GROUP;
+    const int in = lin - grp * per_group;
+    *tm = first_m + in % rows;
+    *tn = in / rows;
+}
+
+template <bool B_NK, bool OUT_BF16>
+__global__ void __launch_bounds__(THREADS) gemm_bf16_kernel(const GemmArgs p) {
+    __shared__ u32x4 sA[BM * 8];
+    __shared__ u32x4 sB[BN * 8];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    int tm, tn;
+    tile_of(blockIdx.x, p.tiles_m, p.tiles_n, &tm, &tn);
+    const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
+    const int64_t M = p.M, N = p.N, K = p.K;
+
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    u32x4 ra[VEC_PER_THREAD], rb[VEC_PER_THREAD];
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+
+    auto fetch = [&](int64_t k0) {
+#pragma unroll
+        for (int i = 0; i < VEC_PER_THREAD; ++i) {
+            const int id = tid + THREADS * i;
+            const int row = id >> 3, cg = id & 7;
+            const int64_t gm = m0 + row, gk = k0 + cg * 8;
+            ra[i] = (gm < M && gk < K) ? *reinterpret_cast<const u32x4*>(p.A + gm * K + gk) : zero;
+        }
+        if (B_NK) {
+#pragma unroll
+            for (int i = 0; i < VEC_PER_THREAD; ++i) {
+                const int id = tid + THREADS * i;
+                const int row = id >> 3, cg = id & 7;
+                const int64_t gn = n0 + row, gk = k0 + cg * 8;
+                rb[i] = (gn < N && gk < K) ? *reinterpret_cast<const u32x4*>(p.B + gn * K + gk) : zero;
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < VEC_PER_THREAD; ++i) {   // B[K,N]: vectors run along N
+                const int id = tid + THREADS * i;
+                const int krow = id >> 5, nv = id & 31;
+                const int64_t gk = k0 + krow, gn = n0 + nv * 8;
+                rb[i] = (gk < K && gn < N) ? *reinterpret_cast<const u32x4*>(p.B + gk * N + gn) : zero;
+            }
+        }
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int i = 0; i < VEC_PER_THREAD; ++i) {
+            const int id = tid + THREADS * i;
+            sA[swz(id >> 3, id & 7)] = ra[i];
+        }
+        if (B_NK) {
+#pragma unroll
+            for (int i = 0; i < VEC_PER_THREAD; ++i) {
+                const int id = tid + THREADS * i;
+                sB[swz(id >> 3, id & 7)] = rb[i];
+            }
+        } else {
+            uint16_t* sb16 = reinterpret_cast<uint16_t*>(sB);
+#pragma unroll
+            for (int i = 0; i < VEC_PER_THREAD; ++i) {   // transpose on the way into LDS
+                const int id = tid + THREADS * i;
+                const int krow = id >> 5, nv = id & 31;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int n = nv * 8 + e;
+                    const uint32_t w = rb[i][e >> 1];
+                    sb16[swz(n, krow >> 3) * 8 + (krow & 7)] = (uint16_t)((e & 1) ? (w >> 16) : (w & 0xffffu));
+                }
+            }
+        }
+    };
+
+    const int64_t ksteps = (K + BK - 1) / BK;
+    fetch(0);
+    stage();
+    __syncthreads();
+    for (int64_t kt = 0; kt < ksteps; ++kt) {
+        if (kt + 1 < ksteps) fetch((kt + 1) * BK);
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            const int cg = kk * 2 + (lane >> 5);
+            bf16x8 a[4], b[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                a[t] = __builtin_bit_cast(bf16x8, sA[swz(wm * 128 + t * 32 + (lane & 31), cg)]);
+                b[t] = __builtin_bit_cast(bf16x8, sB[swz(wn * 128 + t * 32 + (lane & 31), cg)]);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+        __syncthreads();
+        if (kt + 1 < ksteps) {
+            stage();
+            __syncthreads();
+        }
+    }
+
+    // accumulator element v of a 32x32 tile: row 8*(v/4) + 4*(lane/32) + v%4, column lane%32
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int64_t col = n0 + wn * 128 + j * 32 + (lane & 31);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int64_t row = m0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                if (row < M && col < N) {
+                    if (OUT_BF16) reinterpret_cast<uint16_t*>(p.C)[row * N + col] = (uint16_t)bf16_round_bits(acc[i][j][v]);
+                    else reinterpret_cast<float*>(p.C)[row * N + col] = acc[i][j][v];
+                }
+            }
+        }
+}
+
+}  // namespace
+
+namespace lagom {
+int check_gemm_args(const void* A, const void* B, const void* C, int64_t M, int64_t N, int64_t K, int out_dt) {
+    if (!A || !B || !C) return fail(LAGOM_EINVAL, "null matrix pointer");
+    if (M < 1 || N < 1 || K < 1) return fail(LAGOM_EINVAL, "M, N, K must be positive");
+    if (M > (1 << 24) || N > (1 << 24) || K > (1 << 24)) return fail(LAGOM_EINVAL, "dimension above 2^24");
+    if (K % 8) return fail(LAGOM_EINVAL, "K=%lld must be a multiple of 8", (long long)K);
+    if (elem_size(out_dt) == 0) return fail(LAGOM_EINVAL, "unknown output dtype %d", out_dt);
+    if (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C) & 15) return fail(LAGOM_EALIGN, "matrix pointer not 16-byte aligned");
+    return LAGOM_OK;
+}
+}  // namespace lagom
+
+extern "C" int lagom_gemm_describe(int64_t M, int64_t N, int64_t K, lagom_dtype out_dt, lagom_gemm_geometry* out) {
+    if (!out || M < 1 || N < 1 || K < 1 || lagom::elem_size(out_dt) == 0) return lagom::fail(LAGOM_EINVAL, "bad argument");
+    const int64_t tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
+    out->mu = tm * tn;
+    out->tb = 1;   // 64 KiB of LDS and 256 accumulators per lane: one workgroup per compute unit
+    out->d_bytes = (double)(BM + BN) * (double)K * 2.0 + (double)BM * BN * lagom::elem_size(out_dt);
+    out->tile_m = BM; out->tile_n = BN; out->tile_k = BK; out->threads = THREADS;
+    return LAGOM_OK;
+}
+
+extern "C" int lagom_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K,
+                          int b_is_nk, lagom_dtype out_dt, void* hip_stream) {
+    if (int rc = lagom::check_gemm_args(A, B, C, M, N, K, out_dt)) return rc;
+    if (!b_is_nk && (N % 8)) return lagom::fail(LAGOM_EINVAL, "B stored [K,N] needs N to be a multiple of 8");
+    GemmArgs a{static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(B), C, M, N, K,
+               (int32_t)((M + BM - 1) / BM), (int32_t)((N + BN - 1) / BN)};
+    const int64_t tiles = (int64_t)a.tiles_m * a.tiles_n;
+    if (tiles > (1 << 30)) return lagom::fail(LAGOM_EINVAL, "too many tiles");
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const dim3 grid((unsigned)tiles), block(THREADS);
+    const bool bf = out_dt == LAGOM_BF16;
+    if (b_is_nk) {
+        if (bf) hipLaunchKernelGGL((gemm_bf16_kernel<true, true>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((gemm_bf16_kernel<true, false>), grid, block, 0, st, a);
+    } else {
+        if (bf) hipLaunchKernelGGL((gemm_bf16_kernel<false, true>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((gemm_bf16_kernel<false, false>), grid, block, 0, st, a);
+    }
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return lagom::fail(LAGOM_EHIP, "gemm launch: %s", hipGetErrorString(e));
+    return LAGOM_OK;
+}

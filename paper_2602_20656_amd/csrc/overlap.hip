@@ -1,0 +1,227 @@
+// lagom_overlap_run, lagom_contention_sweep, lagom_overlap_profile: execute one overlap
+// group -- communications serialized on one stream, computations on another (Sec. 3.1,
+// Eq. 1) -- and time it with HIP events.  This is Alg. 2's ProfileTime and the experiment
+// behind Fig. 3.
+//
+// Both streams are released together: a short, bounded delay kernel runs on the
+// communication stream while the host enqueues every launch of both streams; the
+// computation stream waits on an event recorded right after it.  The kernels therefore
+// run back to back, unaffected by host launch latency, and start at a common instant.
+#include <hip/hip_runtime.h>
+#include <algorithm>
+#include <vector>
+#include "common.h"
+
+namespace {
+
+#define HIP_TRY(expr)                                                                               \
+    do {                                                                                            \
+        hipError_t e_ = (expr);                                                                     \
+        if (e_ != hipSuccess) return lagom::fail(LAGOM_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+// Holds a stream for about `ticks` of the constant-rate wall clock.  Every exit condition is
+// bounded: the loop ends after `max_iter` sleeps whatever the clock says.
+__global__ void gate_delay_kernel(long long ticks, int max_iter) {
+    if (threadIdx.x == 0) {
+        const long long t0 = wall_clock64();
+        for (int i = 0; i < max_iter; ++i) {
+            if (wall_clock64() - t0 >= ticks) break;
+            __builtin_amdgcn_s_sleep(64);
+        }
+    }
+}
+
+struct Events {
+    std::vector<hipEvent_t> ev;
+    ~Events() { for (hipEvent_t e : ev) (void)hipEventDestroy(e); }
+    int make(int n) {
+        for (int i = 0; i < n; ++i) {
+            hipEvent_t e;
+            HIP_TRY(hipEventCreate(&e));
+            ev.push_back(e);
+        }
+        return LAGOM_OK;
+    }
+};
+
+double median(std::vector<double>& v) {
+    if (v.empty()) return 0.0;
+    std::sort(v.begin(), v.end());
+    const size_t n = v.size();
+    return n & 1 ? v[n / 2] : 0.5 * (v[n / 2 - 1] + v[n / 2]);
+}
+
+int validate(const lagom_comm_desc* L, int nlaunch, const lagom_cfg* cfgs, int ncfg,
+             const lagom_gemm_desc* G, int ncomp, int mode) {
+    if (mode != LAGOM_ALONE_COMM && mode != LAGOM_ALONE_COMP && mode != LAGOM_CORUN)
+        return lagom::fail(LAGOM_EINVAL, "unknown mode %d", mode);
+    if (nlaunch < 0 || nlaunch > LAGOM_MAX_LAUNCHES || ncomp < 0 || ncomp > LAGOM_MAX_LAUNCHES)
+        return lagom::fail(LAGOM_EINVAL, "launch counts outside 0..%d", LAGOM_MAX_LAUNCHES);
+    if (ncfg < 0 || ncfg > LAGOM_MAX_COMMS) return lagom::fail(LAGOM_EINVAL, "ncfg outside 0..%d", LAGOM_MAX_COMMS);
+    if ((nlaunch > 0 && (!L || !cfgs)) || (ncomp > 0 && !G)) return lagom::fail(LAGOM_EINVAL, "null descriptor array");
+    if (mode != LAGOM_ALONE_COMP && nlaunch == 0) return lagom::fail(LAGOM_EINVAL, "no communication to run");
+    if (mode != LAGOM_ALONE_COMM && ncomp == 0) return lagom::fail(LAGOM_EINVAL, "no computation to run");
+    int prev = -1;
+    std::vector<char> seen(ncfg > 0 ? ncfg : 1, 0);
+    for (int i = 0; i < nlaunch; ++i) {
+        const lagom_comm_desc& d = L[i];
+        if (d.comm_id < 0 || d.comm_id >= ncfg) return lagom::fail(LAGOM_EINVAL, "launch %d: comm_id %d outside 0..%d", i, d.comm_id, ncfg - 1);
+        if (d.comm_id != prev) {
+            if (seen[d.comm_id]) return lagom::fail(LAGOM_EINVAL, "launch %d: launches of communication %d are not contiguous", i, d.comm_id);
+            seen[d.comm_id] = 1;
+            prev = d.comm_id;
+        }
+        if (int rc = lagom::check_comm_args(d.op, d.dtype, d.srcs, d.nsrc, d.dsts, d.ndst, d.count)) return rc;
+    }
+    for (int j = 0; j < ncfg; ++j)
+        if (int rc = lagom::check_cfg(&cfgs[j])) return rc;
+    for (int i = 0; i < ncomp; ++i) {
+        const lagom_gemm_desc& g = G[i];
+        if (int rc = lagom::check_gemm_args(g.A, g.B, g.C, g.M, g.N, g.K, g.out_dtype)) return rc;
+    }
+    return LAGOM_OK;
+}
+
+}  // namespace
+
+extern "C" int lagom_overlap_run(const lagom_comm_desc* launches, int nlaunch, const lagom_cfg* cfgs, int ncfg,
+                                 const lagom_gemm_desc* comps, int ncomp, void* comm_stream, void* comp_stream,
+                                 int warmup, int iters, int mode, lagom_timing* out) {
+    if (!out) return lagom::fail(LAGOM_EINVAL, "null output");
+    if (warmup < 0 || iters < 1 || iters > 100000) return lagom::fail(LAGOM_EINVAL, "warmup >= 0 and 1 <= iters <= 100000 required");
+    if (int rc = validate(launches, nlaunch, cfgs, ncfg, comps, ncomp, mode)) return rc;
+    const bool run_comm = mode != LAGOM_ALONE_COMP, run_comp = mode != LAGOM_ALONE_COMM;
+    hipStream_t sa = static_cast<hipStream_t>(comm_stream), sb = static_cast<hipStream_t>(comp_stream);
+    if (run_comm && run_comp && sa == sb) return lagom::fail(LAGOM_EINVAL, "co-run needs two distinct streams");
+
+    // group boundaries on the communication stream: one event before the first launch of every
+    // communication and one after the last launch
+    std::vector<int> group_first;     // launch index where a new comm_id starts
+    std::vector<int> group_id;
+    if (run_comm)
+        for (int i = 0; i < nlaunch; ++i)
+            if (i == 0 || launches[i].comm_id != launches[i - 1].comm_id) { group_first.push_back(i); group_id.push_back(launches[i].comm_id); }
+    const int ngroups = (int)group_first.size();
+    const int n_ev_a = run_comm ? ngroups + 1 : 0;
+    const int n_ev_b = run_comp ? ncomp + 1 : 0;
+    Events E;
+    if (int rc = E.make(1 + n_ev_a + n_ev_b)) return rc;
+    hipEvent_t gate = E.ev[0];
+    hipEvent_t* ea = E.ev.data() + 1;
+    hipEvent_t* eb = E.ev.data() + 1 + n_ev_a;
+
+    int dev = 0, clock_khz = 100000;
+    HIP_TRY(hipGetDevice(&dev));
+    if (hipDeviceGetAttribute(&clock_khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || clock_khz <= 0) clock_khz = 100000;
+    // long enough for the host to enqueue everything: ~12 us per queued item plus a floor
+    const int items = (run_comm ? nlaunch + n_ev_a : 0) + (run_comp ? ncomp + n_ev_b : 0) + 4;
+    const double delay_us = 60.0 + 12.0 * items;
+    const long long ticks = (long long)(delay_us * clock_khz / 1000.0);
+    const int max_iter = 1 << 14;
+
+    std::vector<std::vector<double>> xs(ncfg), ys(ncomp);
+    std::vector<double> Xs, Ys, Zs;
+    hipStream_t gate_stream = run_comm ? sa : sb;
+
+    for (int it = 0; it < warmup + iters; ++it) {
+        hipLaunchKernelGGL(gate_delay_kernel, dim3(1), dim3(64), 0, gate_stream, ticks, max_iter);
+        HIP_TRY(hipGetLastError());
+        HIP_TRY(hipEventRecord(gate, gate_stream));
+        if (run_comm && run_comp) HIP_TRY(hipStreamWaitEvent(sb, gate, 0));
+        if (run_comm) {
+            int g = 0;
+            for (int i = 0; i < nlaunch; ++i) {
+                if (g < ngroups && group_first[g] == i) { HIP_TRY(hipEventRecord(ea[g], sa)); ++g; }
+                const lagom_comm_desc& d = launches[i];
+                if (int rc = lagom_comm_kernel((lagom_op)d.op, (lagom_dtype)d.dtype, d.srcs, d.nsrc, d.dsts, d.ndst,
+                                               d.count, &cfgs[d.comm_id], sa)) return rc;
+            }
+            HIP_TRY(hipEventRecord(ea[ngroups], sa));
+        }
+        if (run_comp) {
+            for (int i = 0; i < ncomp; ++i) {
+                HIP_TRY(hipEventRecord(eb[i], sb));
+                const lagom_gemm_desc& c = comps[i];
+                if (int rc = lagom_gemm(c.A, c.B, c.C, c.M, c.N, c.K, c.b_is_nk, (lagom_dtype)c.out_dtype, sb)) return rc;
+            }
+            HIP_TRY(hipEventRecord(eb[ncomp], sb));
+        }
+        if (run_comm) HIP_TRY(hipStreamSynchronize(sa));
+        if (run_comp) HIP_TRY(hipStreamSynchronize(sb));
+        if (it < warmup) continue;
+
+        float ms = 0.f;
+        double X = 0.0, Y = 0.0, endA = 0.0, endB = 0.0;
+        if (run_comm) {
+            for (int g = 0; g < ngroups; ++g) {
+                HIP_TRY(hipEventElapsedTime(&ms, ea[g], ea[g + 1]));
+                xs[group_id[g]].push_back((double)ms * 1000.0);
+            }
+            HIP_TRY(hipEventElapsedTime(&ms, ea[0], ea[ngroups])); X = (double)ms * 1000.0;
+            HIP_TRY(hipEventElapsedTime(&ms, gate, ea[ngroups])); endA = (double)ms * 1000.0;
+        }
+        if (run_comp) {
+            for (int i = 0; i < ncomp; ++i) {
+                HIP_TRY(hipEventElapsedTime(&ms, eb[i], eb[i + 1]));
+                ys[i].push_back((double)ms * 1000.0);
+            }
+            HIP_TRY(hipEventElapsedTime(&ms, eb[0], eb[ncomp])); Y = (double)ms * 1000.0;
+            HIP_TRY(hipEventElapsedTime(&ms, gate, eb[ncomp])); endB = (double)ms * 1000.0;
+        }
+        Xs.push_back(X); Ys.push_back(Y); Zs.push_back(endA > endB ? endA : endB);
+    }
+    out->X_us = median(Xs);
+    out->Y_us = median(Ys);
+    out->Z_us = median(Zs);
+    if (out->x_us) for (int j = 0; j < ncfg; ++j) out->x_us[j] = median(xs[j]);
+    if (out->y_us) for (int i = 0; i < ncomp; ++i) out->y_us[i] = median(ys[i]);
+    return LAGOM_OK;
+}
+
+extern "C" int lagom_contention_sweep(const lagom_comm_desc* launches, int nlaunch, int ncfg,
+                                      const lagom_gemm_desc* comps, int ncomp, const lagom_cfg* points, int npoints,
+                                      void* comm_stream, void* comp_stream, int warmup, int iters, lagom_sweep_point* out) {
+    if (!points || !out || npoints < 1) return lagom::fail(LAGOM_EINVAL, "need at least one sweep point and an output array");
+    if (ncfg < 1 || ncfg > LAGOM_MAX_COMMS || nlaunch < 1 || ncomp < 1) return lagom::fail(LAGOM_EINVAL, "need communications and computations");
+    double bytes = 0.0;
+    for (int i = 0; i < nlaunch; ++i) {
+        const int64_t b = lagom_comm_bytes(launches[i].op, launches[i].dtype, launches[i].nsrc, launches[i].ndst, launches[i].count);
+        if (b < 0) return lagom::fail(LAGOM_EINVAL, "launch %d: bad descriptor", i);
+        bytes += (double)b;
+    }
+    std::vector<lagom_cfg> cfgs(ncfg, points[0]);
+    lagom_timing t{};
+    if (int rc = lagom_overlap_run(launches, nlaunch, cfgs.data(), ncfg, comps, ncomp, comm_stream, comp_stream,
+                                   warmup, iters, LAGOM_ALONE_COMP, &t)) return rc;
+    const double comp_alone = t.Y_us;
+    for (int p = 0; p < npoints; ++p) {
+        std::fill(cfgs.begin(), cfgs.end(), points[p]);
+        lagom_sweep_point& o = out[p];
+        o.cfg = points[p];
+        o.comp_alone_us = comp_alone;
+        if (int rc = lagom_overlap_run(launches, nlaunch, cfgs.data(), ncfg, comps, ncomp, comm_stream, comp_stream,
+                                       warmup, iters, LAGOM_ALONE_COMM, &t)) return rc;
+        o.comm_alone_us = t.X_us;
+        if (int rc = lagom_overlap_run(launches, nlaunch, cfgs.data(), ncfg, comps, ncomp, comm_stream, comp_stream,
+                                       warmup, iters, LAGOM_CORUN, &t)) return rc;
+        o.comm_corun_us = t.X_us;
+        o.comp_corun_us = t.Y_us;
+        o.z_corun_us = t.Z_us;
+        o.v_alone = o.comm_alone_us > 0.0 ? bytes / o.comm_alone_us : 0.0;
+        o.v_corun = o.comm_corun_us > 0.0 ? bytes / o.comm_corun_us : 0.0;
+    }
+    return LAGOM_OK;
+}
+
+extern "C" int lagom_overlap_profile(void* user, const lagom_cfg* cfgs, int ncomm, double* x_us, double* Y_us) {
+    if (!user || !cfgs || !x_us || !Y_us) return lagom::fail(LAGOM_EINVAL, "null argument");
+    const lagom_overlap_ctx* c = static_cast<const lagom_overlap_ctx*>(user);
+    lagom_timing t{};
+    t.x_us = x_us;
+    int rc = lagom_overlap_run(c->launches, c->nlaunch, cfgs, ncomm, c->comps, c->ncomp, c->comm_stream, c->comp_stream,
+                               c->warmup, c->iters, LAGOM_CORUN, &t);
+    if (rc) return rc;
+    *Y_us = t.Y_us;
+    return LAGOM_OK;
+}

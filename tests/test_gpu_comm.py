@@ -1,0 +1,150 @@
+"""GPU parity: lagom_comm_kernel through the C ABI against the CPU oracle, bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import collective as oc
+from paper_2602_20656_amd import binding as lg, inputs
+from gpu_util import dev, host, same_bits
+
+pytestmark = pytest.mark.gpu
+
+GUARD = 64  # elements of padding on both sides of every destination
+
+
+def _sources(dtype, nsrc, count, seed0):
+    if dtype == "f32":
+        return [inputs.uniform_f32(seed0 + s, count) for s in range(nsrc)]
+    return [inputs.normal_bf16(seed0 + s, count) for s in range(nsrc)]
+
+
+def _run(op, dtype, srcs, ndst, cfg, out_len):
+    np_dt = np.float32 if dtype == "f32" else np.uint16
+    d_srcs = [dev(s) for s in srcs]
+    fill = np.full(out_len + 2 * GUARD, 0x7B if np_dt == np.uint16 else 123.0, dtype=np_dt)
+    d_dsts = [dev(fill) for _ in range(ndst)]
+    esz = np.dtype(np_dt).itemsize
+    ptrs = [d.data_ptr() + GUARD * esz for d in d_dsts]
+    lg.lagom_comm_kernel(op, lg.LAGOM_F32 if dtype == "f32" else lg.LAGOM_BF16, d_srcs, ptrs,
+                         len(srcs[0]), cfg, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    outs = []
+    for d in d_dsts:
+        h = host(d, np_dt)
+        assert same_bits(h[:GUARD], fill[:GUARD]) and same_bits(h[GUARD + out_len:], fill[GUARD + out_len:]), "guard region clobbered"
+        outs.append(h[GUARD:GUARD + out_len])
+    return outs
+
+
+def test_tiny_config_and_its_grid():
+    a, b = inputs.uniform_f32(0, 1 << 20), inputs.uniform_f32(1, 1 << 20)
+    want = oc.reduce_copy([a, b], oc.F32)[0]
+    for nc in (2, 4):
+        for chunk in (64 << 10, 128 << 10):
+            got = _run(lg.LAGOM_REDUCE_COPY, "f32", [a, b], 1, (nc, 256, chunk), 1 << 20)[0]
+            assert same_bits(got, want), (nc, chunk)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("nsrc,ndst", [(1, 1), (2, 1), (2, 2), (3, 1), (4, 4), (5, 1), (8, 1), (16, 2)])
+def test_reduce_copy_ragged_lengths(dtype, nsrc, ndst):
+    for count, cfg in [(1, (1, 64, 16)), (3, (4, 128, 4096)), (1000003, (7, 256, 65536)), (262144 + 5, (32, 1024, 32768)),
+                       (70001, (3, 512, 1 << 20))]:
+        srcs = _sources(dtype, nsrc, count, 100 + nsrc)
+        want = oc.reduce_copy(srcs, dtype, ndst)
+        got = _run(lg.LAGOM_REDUCE_COPY, dtype, srcs, ndst, cfg, count)
+        for g, w in zip(got, want):
+            assert same_bits(g, w), (dtype, nsrc, ndst, count, cfg)
+
+
+def test_result_is_identical_for_every_swept_configuration():
+    count = 1638400 // 4 + 24          # several chunks, ragged tail
+    srcs = _sources("bf16", 2, count, 10)
+    want = oc.reduce_copy(srcs, oc.BF16)[0]
+    for nc in (1, 2, 4, 8, 16, 32, 256, 1000):
+        for chunk in (32 << 10, 256 << 10, 4 << 20, 16, 4080):
+            for nt in (64, 256, 1024):
+                got = _run(lg.LAGOM_REDUCE_COPY, "bf16", srcs, 1, (nc, nt, chunk), count)[0]
+                assert same_bits(got, want), (nc, nt, chunk)
+
+
+def test_special_values_and_rounding_cases():
+    one, eps = 0x3F80, 0x3B80
+    patt = np.array([one, 0x7F80, 0xFF80, 0x7FC0, 0x0001, 0x8000, 0x7F7F, 0x3F81], dtype=np.uint16)
+    a = np.tile(patt, 9)
+    b = np.tile(np.array([eps, 0x7F80, 0x7F80, one, 0x0001, 0x0000, 0x7F7F, eps], dtype=np.uint16), 9)
+    c = np.tile(np.array([eps, one, one, one, 0x8001, 0x8000, 0x0000, 0x0000], dtype=np.uint16), 9)
+    want = oc.reduce_copy([a, b, c], oc.BF16)[0]
+    got = _run(lg.LAGOM_REDUCE_COPY, "bf16", [a, b, c], 1, (2, 64, 64), len(a))[0]
+    assert same_bits(got, want)
+    assert got[0] == 0x3F81                                   # 1 + 2^-8 + 2^-8 rounds once
+    big, o = np.float32(1e8), np.float32(1.0)
+    f = [np.array([big, o, np.inf, np.nan], np.float32), np.array([-big, big, -np.inf, o], np.float32),
+         np.array([o, -big, o, o], np.float32)]
+    gotf = _run(lg.LAGOM_REDUCE_COPY, "f32", f, 1, (1, 64, 16), 4)[0]
+    assert gotf[:2].tolist() == [1.0, 0.0] and np.isnan(gotf[2]) and np.isnan(gotf[3])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_gather_copy(dtype):
+    for P, count, cfg in [(8, 2097152 // 8, (8, 256, 2 << 20)), (8, 1237, (4, 256, 1024)), (3, 70001, (5, 128, 65536)),
+                          (1, 1000003, (6, 256, 32768)), (2, 8, (1, 64, 16)), (16, 4099, (32, 512, 4096))]:
+        shards = _sources(dtype, P, count, 30)
+        want = np.concatenate(shards)
+        for ndst in (1, 2):
+            for g in _run(lg.LAGOM_GATHER_COPY, dtype, shards, ndst, cfg, P * count):
+                assert same_bits(g, want), (dtype, P, count, cfg)
+
+
+def test_empty_input_is_a_no_op():
+    a = dev(np.zeros(16, np.float32)); d = dev(np.ones(16, np.float32))
+    lg.lagom_comm_kernel(lg.LAGOM_REDUCE_COPY, lg.LAGOM_F32, [a], [d], 0, (4, 256, 65536), torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    assert d.cpu().numpy().tolist() == [1.0] * 16
+
+
+@pytest.mark.parametrize("dtype,P,m", [("bf16", 8, 1638400 // 64), ("f32", 4, 1000)])
+def test_ring_all_reduce_emulated_on_one_gpu(dtype, P, m):
+    """Every rank's 2(P-1) local steps run through the kernel; peers are separate allocations."""
+    if dtype == "bf16":
+        buckets = [inputs.normal_bf16(10 + r, P * m, scale=0.125) for r in range(P)]
+    else:
+        buckets = [inputs.uniform_f32(40 + r, P * m) for r in range(P)]
+    want = oc.ring_all_reduce(buckets, dtype)
+    dt = lg.LAGOM_BF16 if dtype == "bf16" else lg.LAGOM_F32
+    esz = 2 if dtype == "bf16" else 4
+    local = [dev(b) for b in buckets]
+    # wire[r] = what rank r sends next (the receive buffer of rank r+1), double-buffered
+    wire = [[torch.empty_like(local[0][:m]) for _ in range(P)] for _ in range(2)]
+    st = torch.cuda.current_stream()
+    cfg = (4, 256, 32768)
+    chunk_ptr = lambda r, c: local[r].data_ptr() + c * m * esz
+    for r in range(P):  # step 0 sends the rank's own chunk r
+        lg.lagom_comm_kernel(lg.LAGOM_GATHER_COPY, dt, [chunk_ptr(r, r)], [wire[0][r]], m, cfg, st)
+    cur = 0
+    for s in range(P - 1):
+        for r in range(P):
+            c = (r - s - 1) % P
+            dsts = [wire[1 - cur][r]] + ([chunk_ptr(r, c)] if s == P - 2 else [])
+            lg.lagom_comm_kernel(lg.LAGOM_REDUCE_COPY, dt, [wire[cur][(r - 1) % P], chunk_ptr(r, c)], dsts, m, cfg, st)
+        cur = 1 - cur
+    for s in range(P - 1):
+        for r in range(P):
+            c = (r - s) % P
+            dsts = [chunk_ptr(r, c)] + ([wire[1 - cur][r]] if s < P - 2 else [])
+            lg.lagom_comm_kernel(lg.LAGOM_GATHER_COPY, dt, [wire[cur][(r - 1) % P]], dsts, m, cfg, st)
+        cur = 1 - cur
+    torch.cuda.synchronize()
+    for r in range(P):
+        assert same_bits(host(local[r], buckets[0].dtype), want[r]), r
+
+
+def test_tp_reduce_scatter_share_full_size_sampled():
+    """Full-size TP share (8 x 4,194,304 bf16) in the benchmark's launch shape; the oracle checks slices."""
+    count = 4194304
+    srcs = [inputs.normal_bf16(20 + s, count) for s in range(8)]
+    got = _run(lg.LAGOM_REDUCE_COPY, "bf16", srcs, 1, (32, 256, 2 << 20), count)[0]
+    rng = np.random.default_rng(0)
+    for lo in [0, count - 4096] + [int(v) for v in rng.integers(0, count - 4096, size=14)]:
+        want = oc.reduce_copy([s[lo:lo + 4096] for s in srcs], oc.BF16)[0]
+        assert same_bits(got[lo:lo + 4096], want), lo

@@ -1,0 +1,77 @@
+"""GPU parity: lagom_gemm through the C ABI against the fp64 oracle, rel-err <= 2e-2
+(bf16 inputs, fp32 accumulation), both error measures."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import collective as oc, gemm as og
+from paper_2602_20656_amd import binding as lg, inputs
+from gpu_util import dev, host
+
+pytestmark = pytest.mark.gpu
+GATE = 2e-2
+
+
+def _gemm(a_bits, b_bits, b_is_nk, out):
+    M, K = a_bits.shape
+    N = b_bits.shape[0] if b_is_nk else b_bits.shape[1]
+    dA, dB = dev(a_bits), dev(b_bits)
+    pad = 256
+    if out == "bf16":
+        dC = dev(np.full(M * N + 2 * pad, 0x7B7B, np.uint16)); esz = 2
+    else:
+        dC = dev(np.full(M * N + 2 * pad, 123.0, np.float32)); esz = 4
+    lg.lagom_gemm(dA, dB, dC.data_ptr() + pad * esz, M, N, K, b_is_nk,
+                  lg.LAGOM_BF16 if out == "bf16" else lg.LAGOM_F32, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    h = host(dC, np.uint16 if out == "bf16" else np.float32)
+    guard = h[:pad].tolist() + h[pad + M * N:].tolist()
+    assert all(v == (0x7B7B if out == "bf16" else 123.0) for v in guard), "guard region clobbered"
+    c = h[pad:pad + M * N].reshape(M, N)
+    return oc.bf16_to_f32(c) if out == "bf16" else c
+
+
+@pytest.mark.parametrize("M,N,K", [(512, 512, 512), (1, 1, 8), (300, 200, 136), (700, 520, 264), (256, 256, 64),
+                                   (257, 255, 72), (33, 1000, 4096)])
+@pytest.mark.parametrize("b_is_nk", [True, False])
+@pytest.mark.parametrize("out", ["bf16", "f32"])
+def test_gemm_small_shapes(M, N, K, b_is_nk, out):
+    if not b_is_nk and N % 8:
+        pytest.skip("[K,N] layout needs N % 8 == 0")
+    a = inputs.normal_bf16(2, (M, K))
+    b = inputs.normal_bf16(3, (N, K) if b_is_nk else (K, N))
+    ref = og.gemm_f64(a, b, b_is_nk)
+    got = _gemm(a, b, b_is_nk, out)
+    e_max, e_fro = og.rel_errors(got, ref)
+    assert e_max <= GATE and e_fro <= GATE, (e_max, e_fro)
+    if out == "f32":   # fp32 accumulation alone is orders of magnitude inside the gate
+        assert e_fro < 1e-5, e_fro
+
+
+def test_gemm_integer_inputs_are_exact():
+    rng = np.random.default_rng(5)
+    ai = rng.integers(-4, 5, size=(260, 320)); bi = rng.integers(-4, 5, size=(270, 320))
+    a, b = inputs.to_bf16_bits(ai.astype(np.float32)), inputs.to_bf16_bits(bi.astype(np.float32))
+    got = _gemm(a, b, True, "f32")
+    assert np.array_equal(got.astype(np.int64), ai @ bi.T)
+
+
+def test_b_kn_layout_rejects_unaligned_n():
+    with pytest.raises(lg.LagomError):
+        lg.lagom_gemm(4096, 8192, 16384, 64, 60, 64, False)
+
+
+@pytest.mark.parametrize("M,N,K", [(4096, 4096, 4096), (4096, 3584, 8192), (8192, 4096, 4096), (8192, 8192, 8192)])
+def test_gemm_full_size_sampled_rows(M, N, K):
+    """Benchmark shapes: 64 seeded rows x all columns, plus the four corner tiles, against the oracle."""
+    a = inputs.normal_bf16(2, (M, K))
+    b = inputs.normal_bf16(3, (N, K), scale=0.02)
+    got = _gemm(a, b, True, "bf16")
+    rng = np.random.default_rng(M + N + K)
+    rows = np.unique(np.concatenate([rng.integers(0, M, size=64), np.arange(0, 4), np.arange(M - 4, M)]))
+    ref = og.gemm_f64(a, b, True, rows=rows)
+    e_max, e_fro = og.rel_errors(got[rows], ref)
+    assert e_max <= GATE and e_fro <= GATE, (e_max, e_fro)
+    corners = ref[:, np.r_[0:32, N - 32:N]]
+    e_max, e_fro = og.rel_errors(got[rows][:, np.r_[0:32, N - 32:N]], corners)
+    assert e_max <= GATE and e_fro <= GATE

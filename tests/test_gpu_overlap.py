@@ -1,0 +1,74 @@
+"""GPU checks of the overlap runner, the contention profiler and the measured tuner."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import collective as oc, gemm as og
+from paper_2602_20656_amd import binding as lg, inputs
+from gpu_util import dev, host, same_bits
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def tiny():
+    a, b = inputs.uniform_f32(0, 1 << 20), inputs.uniform_f32(1, 1 << 20)
+    A, B = inputs.normal_bf16(2, (512, 512)), inputs.normal_bf16(3, (512, 512))
+    d = dict(a=a, b=b, A=A, B=B, da=dev(a), db=dev(b), dout=dev(np.zeros(1 << 20, np.float32)),
+             dA=dev(A), dB=dev(B), dC=dev(np.zeros((512, 512), np.uint16)),
+             s1=torch.cuda.Stream(), s2=torch.cuda.Stream())
+    d["launches"] = [lg.CommLaunch(lg.LAGOM_REDUCE_COPY, lg.LAGOM_F32, [d["da"], d["db"]], [d["dout"]], 1 << 20, 0)]
+    d["comps"] = [lg.GemmDesc(d["dA"], d["dB"], d["dC"], 512, 512, 512)]
+    return d
+
+
+def test_corun_keeps_both_results_correct_and_times_are_consistent(tiny):
+    t = lg.lagom_overlap_run(tiny["launches"], [(4, 256, 128 << 10)], tiny["comps"], tiny["s1"], tiny["s2"], 2, 10, lg.LAGOM_CORUN)
+    torch.cuda.synchronize()
+    assert same_bits(host(tiny["dout"], np.float32), oc.reduce_copy([tiny["a"], tiny["b"]], oc.F32)[0])
+    got = oc.bf16_to_f32(host(tiny["dC"], np.uint16))
+    e_max, e_fro = og.rel_errors(got, og.gemm_f64(tiny["A"], tiny["B"], True))
+    assert e_max <= 2e-2 and e_fro <= 2e-2
+    assert t.X_us > 0 and t.Y_us > 0 and t.Z_us >= max(t.X_us, t.Y_us) * 0.999
+    assert t.x_us[0] == pytest.approx(t.X_us, rel=0.5) and t.y_us[0] == pytest.approx(t.Y_us, rel=0.5)
+    for mode, which in [(lg.LAGOM_ALONE_COMM, "X_us"), (lg.LAGOM_ALONE_COMP, "Y_us")]:
+        r = lg.lagom_overlap_run(tiny["launches"], [(4, 256, 128 << 10)], tiny["comps"], tiny["s1"], tiny["s2"], 1, 5, mode)
+        assert getattr(r, which) > 0
+
+
+def test_runner_rejects_bad_groups(tiny):
+    with pytest.raises(lg.LagomError):   # same stream for both
+        lg.lagom_overlap_run(tiny["launches"], [(4, 256, 65536)], tiny["comps"], tiny["s1"], tiny["s1"], 1, 1, lg.LAGOM_CORUN)
+    with pytest.raises(lg.LagomError):   # comm_id out of range
+        bad = [lg.CommLaunch(lg.LAGOM_REDUCE_COPY, lg.LAGOM_F32, [tiny["da"]], [tiny["dout"]], 16, 3)]
+        lg.lagom_overlap_run(bad, [(4, 256, 65536)], tiny["comps"], tiny["s1"], tiny["s2"], 1, 1, lg.LAGOM_CORUN)
+    with pytest.raises(lg.LagomError):   # non-contiguous ids
+        l0 = lg.CommLaunch(lg.LAGOM_REDUCE_COPY, lg.LAGOM_F32, [tiny["da"]], [tiny["dout"]], 16, 0)
+        l1 = lg.CommLaunch(lg.LAGOM_REDUCE_COPY, lg.LAGOM_F32, [tiny["da"]], [tiny["dout"]], 16, 1)
+        lg.lagom_overlap_run([l0, l1, l0], [(4, 256, 65536)] * 2, tiny["comps"], tiny["s1"], tiny["s2"], 1, 1, lg.LAGOM_CORUN)
+    with pytest.raises(lg.LagomError):
+        lg.lagom_overlap_run(tiny["launches"], [(4, 256, 65536)], tiny["comps"], tiny["s1"], tiny["s2"], 1, 0, lg.LAGOM_CORUN)
+
+
+def test_contention_sweep_on_the_tiny_grid(tiny):
+    points = [(nc, 256, c) for nc in (2, 4) for c in (64 << 10, 128 << 10)]
+    pts = lg.lagom_contention_sweep(tiny["launches"], 1, tiny["comps"], points, tiny["s1"], tiny["s2"], 1, 5)
+    assert [p.cfg for p in pts] == points
+    nbytes = lg.lagom_comm_bytes(lg.LAGOM_REDUCE_COPY, lg.LAGOM_F32, 2, 1, 1 << 20)
+    for p in pts:
+        assert p.comm_alone_us > 0 and p.comm_corun_us > 0 and p.comp_alone_us > 0 and p.comp_corun_us > 0
+        assert p.v_alone == pytest.approx(nbytes / p.comm_alone_us) and p.v_corun == pytest.approx(nbytes / p.comm_corun_us)
+        assert p.z_corun_us >= max(p.comm_corun_us, p.comp_corun_us) * 0.999
+    # four channels move the same bytes faster than two
+    assert pts[2].comm_alone_us < pts[0].comm_alone_us
+
+
+def test_measured_priority_search_stays_on_the_ladder_and_is_linear(tiny):
+    space = lg.Space([1, 2, 4, 8, 16, 32], [256], [32768 << i for i in range(8)])
+    prof = lg.OverlapProfile(tiny["launches"], tiny["comps"], tiny["s1"], tiny["s2"], 1, 3)
+    r = lg.lagom_tune([space], prof, lg.LAGOM_PRIORITY)
+    ladder = [(space.nc[min(l, 5)], 256, space.chunk[l]) for l in range(8)]
+    assert r.cfgs[0] == ladder[r.levels[0]] and 1 <= r.calls <= 9 and len(r.trace) == r.calls
+    assert r.Z > 0
+    torch.cuda.synchronize()
+    assert same_bits(host(tiny["dout"], np.float32), oc.reduce_copy([tiny["a"], tiny["b"]], oc.F32)[0])

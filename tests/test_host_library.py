@@ -1,0 +1,236 @@
+"""Host-side checks that need no GPU: the C-ABI library loads and exports what the header
+declares, and its cost model and tuner equal the oracle bit for bit."""
+import json
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import cost_model as ocm, search as osr
+from paper_2602_20656_amd import binding as lg
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "lagom.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(lagom_[a-z_]+)\s*\(", header)) - {"lagom_profile_fn"}
+    assert {"lagom_comm_kernel", "lagom_gemm", "lagom_overlap_run", "lagom_cost_model", "lagom_tune"} <= declared
+    L = lg.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert set(lg.EXPORTS) == declared
+    assert L.lagom_strerror(lg.LAGOM_EALIGN).decode().startswith("device pointer")
+
+
+def test_host_only_helpers():
+    assert lg.lagom_comm_bytes(lg.LAGOM_REDUCE_COPY, lg.LAGOM_F32, 2, 1, 1 << 20) == 12 << 20
+    assert lg.lagom_comm_bytes(lg.LAGOM_REDUCE_COPY, lg.LAGOM_BF16, 8, 1, 4194304) == 72 << 20
+    assert lg.lagom_comm_bytes(lg.LAGOM_GATHER_COPY, lg.LAGOM_BF16, 8, 1, 2097152) == 64 << 20
+    assert lg.lagom_comm_bytes(7, lg.LAGOM_BF16, 8, 1, 1) == -1
+    g = lg.lagom_gemm_describe(8192, 8192, 8192)
+    assert g.mu == (8192 // g.tile_m) * (8192 // g.tile_n) and g.tb >= 1
+    assert g.d_bytes == (g.tile_m + g.tile_n) * 8192 * 2 + g.tile_m * g.tile_n * 2
+    assert lg.lagom_gemm_describe(100, 300, 64).mu == math.ceil(100 / g.tile_m) * math.ceil(300 / g.tile_n)
+
+
+def test_argument_errors_are_reported_before_any_gpu_work():
+    good = (4, 256, 65536)
+    with pytest.raises(lg.LagomError) as e:
+        lg.lagom_comm_kernel(lg.LAGOM_REDUCE_COPY, lg.LAGOM_F32, [4096, 8192], [16384], 100, (4, 100, 65536))
+    assert e.value.code == lg.LAGOM_EINVAL
+    with pytest.raises(lg.LagomError) as e:
+        lg.lagom_comm_kernel(lg.LAGOM_REDUCE_COPY, lg.LAGOM_F32, [4096, 8200], [16384], 100, good)
+    assert e.value.code == lg.LAGOM_EALIGN
+    for bad in [(0, 256, 65536), (4, 2048, 65536), (4, 256, 24), (4, 256, 0)]:
+        with pytest.raises(lg.LagomError):
+            lg.lagom_comm_kernel(lg.LAGOM_REDUCE_COPY, lg.LAGOM_F32, [4096], [16384], 100, bad)
+    with pytest.raises(lg.LagomError):
+        lg.lagom_comm_kernel(lg.LAGOM_REDUCE_COPY, lg.LAGOM_F32, [4096] * 17, [16384], 100, good)
+    with pytest.raises(lg.LagomError):
+        lg.lagom_comm_kernel(lg.LAGOM_REDUCE_COPY, lg.LAGOM_F32, [4096], [16384], -1, good)
+    with pytest.raises(lg.LagomError) as e:
+        lg.lagom_gemm(4096, 8192, 16384, 64, 64, 12)          # K not a multiple of 8
+    assert e.value.code == lg.LAGOM_EINVAL
+    with pytest.raises(lg.LagomError) as e:
+        lg.lagom_gemm(4096, 8192 + 2, 16384, 64, 64, 64)
+    assert e.value.code == lg.LAGOM_EALIGN
+    # count == 0 is a no-op that touches no device
+    lg.lagom_comm_kernel(lg.LAGOM_REDUCE_COPY, lg.LAGOM_F32, [4096], [16384], 0, good)
+
+
+# ------------------------------------------------------------------- cost model parity
+def _random_model(rng, N, M):
+    lam = int(rng.choice([8, 64, 256]))
+    bw = float(rng.uniform(1e3, 8e6))
+    comps_o, comps_l = [], []
+    for _ in range(M):
+        mu, tb = int(rng.integers(0, 3000)), int(rng.integers(1, 3))
+        d, th = float(rng.uniform(0, 1e7)), float(rng.uniform(0, 50))
+        comps_o.append(ocm.Comp(mu, tb, d, th)); comps_l.append(lg.CompModel(mu, tb, d, th))
+    tables, cfgs = [], []
+    for _ in range(N):
+        t = {}
+        for nc in (1, 2, 4):
+            for c in (4096, 65536):
+                t[(nc, 256, c)] = (float(rng.uniform(0, 400)), float(rng.uniform(0, 0.95 * bw)))
+        tables.append(t)
+        cfgs.append((int(rng.choice([1, 2, 4])), 256, int(rng.choice([4096, 65536]))))
+    return ocm.Model(lam, bw, comps_o, tables), lg.Model(lam, bw, comps_l, tables), cfgs
+
+
+def test_cost_model_equals_oracle_bit_for_bit():
+    rng = np.random.default_rng(11)
+    for _ in range(300):
+        N, M = int(rng.integers(0, 5)), int(rng.integers(0, 5))
+        mo, ml, cfgs = _random_model(rng, N, M)
+        po, pl = ocm.predict(mo, cfgs), lg.lagom_cost_model(ml, cfgs)
+        assert pl.x_us == po.x and pl.y_us == po.y and pl.g == po.g
+        assert (pl.X_us, pl.Y_us, pl.Z_us) == (po.X, po.Y, po.Z)
+
+
+def test_cost_model_on_the_hand_worked_fixture(golden_dir):
+    fx = json.load(open(os.path.join(golden_dir, "cost_model_worked.json")))
+    for case in fx["cases"]:
+        tables = [{(c["nc"], 256, 65536): (c["x"], c["v"])} for c in case["comms"]]
+        model = lg.Model(fx["lambda"], fx["bw_peak"], [lg.CompModel(c["mu"], c["tb"], c["d_bytes"], c["theta"]) for c in case["comps"]], tables)
+        p = lg.lagom_cost_model(model, [(c["nc"], 256, 65536) for c in case["comms"]])
+        assert p.y_us == case["y"] and p.g == case["g"] and (p.X_us, p.Y_us, p.Z_us) == (case["X"], case["Y"], case["Z"])
+
+
+def test_cost_model_rejects_bad_input():
+    comps = [lg.CompModel(10, 1, 1.0, 0.5)]
+    for lam, table, cfg in [(8, {(8, 64, 64): (1.0, 1.0)}, (8, 64, 64)),        # NC >= lambda
+                            (8, {(2, 64, 64): (1.0, 100.0)}, (2, 64, 64)),      # V >= B
+                            (8, {(2, 64, 64): (1.0, 1.0)}, (4, 64, 64)),        # not in the table
+                            (8, {(2, 64, 64): (-1.0, 1.0)}, (2, 64, 64))]:      # negative x
+        with pytest.raises(lg.LagomError) as e:
+            lg.lagom_cost_model(lg.Model(lam, 100.0, comps, [table]), [cfg])
+        assert e.value.code == lg.LAGOM_EINVAL
+
+
+# ------------------------------------------------------------------------ tuner parity
+def _same_trace(lib_trace, oracle_trace):
+    assert len(lib_trace) == len(oracle_trace)
+    for a, b in zip(lib_trace, oracle_trace):
+        assert (a.comm, a.level_from, a.level_to, a.accepted, a.done) == (b.comm, b.level_from, b.level_to, b.accepted, b.done)
+        for u, v in [(a.xj_prev, b.xj_prev), (a.xj_new, b.xj_new), (a.X, b.X), (a.Y, b.Y), (a.Z, b.Z), (a.H, b.H), (a.lr, b.lr)]:
+            assert (math.isnan(u) and math.isnan(v)) or u == v
+
+
+def _random_chain(rng, N):
+    spaces_o, spaces_l = [], []
+    for _ in range(N):
+        nc = sorted(set(int(v) for v in rng.choice([1, 2, 3, 4, 6, 8, 16, 32, 61], size=rng.integers(1, 6), replace=False)))
+        nt = sorted(set(int(v) for v in rng.choice([64, 128, 256, 512, 1024], size=rng.integers(1, 4), replace=False)))
+        ch = sorted(set(int(v) for v in rng.choice([16384, 32768, 65536, 700416, 1398784, 2097152], size=rng.integers(1, 5), replace=False)))
+        spaces_o.append(osr.Space(nc, nt, ch)); spaces_l.append(lg.Space(nc, nt, ch))
+    base = rng.uniform(5, 300, size=N)
+    a = rng.uniform(0.2, 1.2, size=N)
+    pen = rng.uniform(0, 3, size=N)
+    y0 = float(rng.uniform(5, 400))
+    bump = rng.uniform(0, 0.02, size=N)
+
+    def profile(cfgs):
+        x = [float(base[j] / (c[0] ** a[j]) * (1 + bump[j] * c[0]) + 1e-6 * c[2] / c[1]) for j, c in enumerate(cfgs)]
+        Y = y0 + sum(float(pen[j]) * c[0] + 1e-6 * c[2] for j, c in enumerate(cfgs))
+        return x, Y
+    return spaces_o, spaces_l, profile
+
+
+def test_priority_search_equals_oracle_result_and_trace():
+    rng = np.random.default_rng(3)
+    for _ in range(300):
+        N = int(rng.integers(1, 9))
+        so, sl, profile = _random_chain(rng, N)
+        ro = osr.priority_search(so, profile)
+        rl = lg.lagom_tune(sl, profile, lg.LAGOM_PRIORITY)
+        assert rl.cfgs == ro.cfgs and rl.levels == ro.levels and rl.calls == ro.calls
+        assert (rl.X, rl.Y, rl.Z) == (ro.X, ro.Y, ro.Z)
+        _same_trace(rl.trace, ro.trace)
+        assert rl.calls <= 1 + sum(sp.K for sp in so)
+
+
+def test_exhaustive_equals_oracle_brute_force():
+    rng = np.random.default_rng(4)
+    for _ in range(60):
+        N = int(rng.integers(1, 4))
+        so, sl, profile = _random_chain(rng, N)
+        ro = osr.brute_force(so, profile)
+        rl = lg.lagom_tune(sl, profile, lg.LAGOM_EXHAUSTIVE)
+        assert rl.cfgs == ro.cfgs and rl.levels == ro.levels and rl.calls == ro.calls and rl.Z == ro.Z
+    # ties: constant profile -> all-zero levels
+    sl = [lg.Space([1, 2, 4], [64], [16]), lg.Space([1, 2], [64], [16])]
+    assert lg.lagom_tune(sl, lambda c: ([1.0, 1.0], 5.0), lg.LAGOM_EXHAUSTIVE).levels == [0, 0]
+
+
+def test_tuner_on_the_hand_worked_fixture(golden_dir):
+    fx = json.load(open(os.path.join(golden_dir, "search_worked.json")))
+    for case in fx["cases"]:
+        so = [osr.Space(**sp) for sp in case["spaces"]]
+        sl = [lg.Space(**sp) for sp in case["spaces"]]
+        xs, coef = case["x_by_level"], case["Y_coef"]
+
+        def profile(cfgs):
+            lv = [[so[j].cfg(l) for l in range(so[j].K)].index(tuple(c)) for j, c in enumerate(cfgs)]
+            return [xs[j][l] for j, l in enumerate(lv)], coef[0] + sum(coef[1 + j] * l for j, l in enumerate(lv))
+        r = lg.lagom_tune(sl, profile, lg.LAGOM_PRIORITY)
+        assert r.levels == case["final_levels"] and r.Z == case["final_Z"] and r.calls == case["calls"]
+        for got, want in zip(r.trace, case["trace"]):
+            assert (got.comm, got.level_from, got.level_to, got.accepted, got.done) == \
+                (want["comm"], want["from"], want["to"], want["accepted"], want["done"])
+        b = lg.lagom_tune(sl, profile, lg.LAGOM_EXHAUSTIVE)
+        assert b.levels == case["brute_levels"] and b.Z == case["brute_Z"]
+
+
+def test_tuner_with_the_native_model_callback_matches_oracle_on_the_same_model():
+    rng = np.random.default_rng(9)
+    nc_grid, ch_grid = [1, 2, 4, 8, 16, 32], [32768 << i for i in range(8)]
+    lam, bw = 256, 8.0e6
+    for trial in range(20):
+        N = int(rng.integers(1, 4))
+        tables = []
+        for j in range(N):
+            t = {}
+            work = float(rng.uniform(2e7, 2e8))
+            for l in range(8):
+                nc, ch = nc_grid[min(l, 5)], ch_grid[l]
+                v = min(0.9 * bw, nc * 6.0e4 * (1 + 0.1 * l))
+                t[(nc, 256, ch)] = (work / v, v)
+            tables.append(t)
+        comps_o = [ocm.Comp(1024, 1, 4.3e6, 20.0) for _ in range(N)]
+        comps_l = [lg.CompModel(1024, 1, 4.3e6, 20.0) for _ in range(N)]
+        mo, ml = ocm.Model(lam, bw, comps_o, tables), lg.Model(lam, bw, comps_l, tables)
+
+        def profile(cfgs):
+            p = ocm.predict(mo, cfgs)
+            return p.x, p.Y
+        so = [osr.Space(nc_grid, [256], ch_grid) for _ in range(N)]
+        sl = [lg.Space(nc_grid, [256], ch_grid) for _ in range(N)]
+        for mode, oracle_fn in [(lg.LAGOM_PRIORITY, osr.priority_search), (lg.LAGOM_EXHAUSTIVE, osr.brute_force)]:
+            ro, rl = oracle_fn(so, profile), lg.lagom_tune(sl, ml, mode)
+            assert rl.cfgs == ro.cfgs and rl.Z == ro.Z and rl.calls == ro.calls
+
+
+def test_callback_failure_returns_best_so_far():
+    calls = []
+
+    def profile(cfgs):
+        calls.append(cfgs)
+        if len(calls) == 3:
+            raise RuntimeError("boom")
+        return [100.0 / c[0] for c in cfgs], 1.0
+    sl = [lg.Space([1, 2, 4, 8], [256], [65536])]
+    with pytest.raises(lg.LagomError) as e:
+        lg.lagom_tune(sl, profile)
+    assert e.value.code == lg.LAGOM_ECALLBACK
+    calls.clear()
+    r = lg.lagom_tune(sl, profile, raise_on_callback_error=False)
+    assert r.code == lg.LAGOM_ECALLBACK and r.cfgs == [(2, 256, 65536)] and r.calls == 2
+    with pytest.raises(lg.LagomError):
+        lg.lagom_tune([lg.Space([2, 1], [256], [65536])], profile)
+    with pytest.raises(lg.LagomError):
+        lg.lagom_tune([lg.Space([1], [256], [65536])], lambda c: ([float("nan")], 1.0))
