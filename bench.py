@@ -1,0 +1,282 @@
+#!/usr/bin/env python3
+"""Benchmark of the Lagom hot path on one MI355X.
+
+One "step" is one pass of the whole overlapped group of the chosen workload (every
+communication launch on one stream, every GEMM on the other, through lagom_overlap_run)
+with the parameters the priority search picked.  Before the timed region the contention
+profiler sweeps the workload's (NC, C[, NT]) grid, the cost model is filled from it, and
+lagom_tune runs once with measured profiles and once with the model.
+
+Prints ONE JSON line:  value = makespan(default NC=8, C=2 MiB, NT=256) / makespan(tuned).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+BF16_PEAK_TFLOPS = 2500.0       # MI355X dense bf16 MFMA, published
+LAMBDA = 256                    # compute units
+DEFAULT_CFG = (8, 256, 2 << 20)  # the collective library default the paper quotes (Sec. 4.3), NT from the tiny config
+
+
+def _up(x):
+    import torch
+    return torch.from_numpy(x.view(np.int16) if x.dtype == np.uint16 else x).cuda()
+
+
+def build_workload(name: str):
+    """Device buffers + launch descriptors of one of the five synthetic overlap groups."""
+    import torch
+    from paper_2602_20656_amd import binding as lg, inputs
+    w = inputs.WORKLOADS[name]
+    M, N, K = w.gemm
+    keep = []
+    launches = []
+    dt = lg.LAGOM_F32 if w.comm.dtype == "f32" else lg.LAGOM_BF16
+    gen = (lambda seed, n: inputs.uniform_f32(seed, n)) if w.comm.dtype == "f32" else \
+          (lambda seed, n: inputs.normal_bf16(seed, n, w.scale))
+    np_dt = np.float32 if w.comm.dtype == "f32" else np.uint16
+
+    if name == "dp_bucket":
+        P, m = 8, w.comm.count
+        local = _up(gen(w.seeds[0], P * m))
+        wire_in = [_up(gen(w.seeds[1 + i], m)) for i in range(2)]
+        wire_out = [_up(np.zeros(m, np_dt)) for _ in range(2)]
+        keep += [local, wire_in, wire_out]
+        esz = 2
+        chunk = lambda c: local.data_ptr() + c * m * esz
+        r = 0
+        for s in range(P - 1):                       # reduce-scatter phase: out = incoming + local
+            c = (r - s - 1) % P
+            dsts = [wire_out[s % 2]] + ([chunk(c)] if s == P - 2 else [])
+            launches.append(lg.CommLaunch(lg.LAGOM_REDUCE_COPY, dt, [wire_in[s % 2], chunk(c)], dsts, m, 0))
+        for s in range(P - 1):                       # all-gather phase: store and forward
+            c = (r - s) % P
+            dsts = [chunk(c)] + ([wire_out[s % 2]] if s < P - 2 else [])
+            launches.append(lg.CommLaunch(lg.LAGOM_GATHER_COPY, dt, [wire_in[s % 2]], dsts, m, 0))
+        ncomm = 1
+    elif name == "fsdp_chain":
+        ncomm = w.ncomm
+        weights = []
+        for j in range(ncomm):
+            shards = [_up(gen(w.seeds[j] * 100 + p, w.comm.count)) for p in range(w.comm.nsrc)]
+            full = _up(np.zeros(w.comm.nsrc * w.comm.count, np_dt))
+            keep += [shards, full]
+            weights.append(full)
+            launches.append(lg.CommLaunch(lg.LAGOM_GATHER_COPY, dt, shards, [full], w.comm.count, j))
+    else:
+        ncomm = 1
+        reps = 1
+        if name == "compute_bound":
+            reps = int(os.environ.get("LAGOM_BENCH_CB_REPS", "24"))
+        for rep in range(reps):
+            srcs = [_up(gen(w.seeds[s % len(w.seeds)] + 1000 * rep, w.comm.count)) for s in range(w.comm.nsrc)]
+            dst = _up(np.zeros(w.comm.count, np_dt))
+            keep += [srcs, dst]
+            launches.append(lg.CommLaunch(lg.LAGOM_REDUCE_COPY, dt, srcs, [dst], w.comm.count, 0))
+
+    comps = []
+    A = _up(inputs.normal_bf16(2, (M, K)))
+    keep.append(A)
+    for i in range(w.ncomp):
+        if name == "fsdp_chain":
+            # GEMM i multiplies by the weight gathered one pair earlier (pair 0 uses its own, pre-filled)
+            B = _up(inputs.normal_bf16(3 + i, (N, K), 0.02))
+        else:
+            B = _up(inputs.normal_bf16(3, (N, K), 0.02 if name != "tiny" else 1.0))
+        Cm = torch.zeros((M, N), dtype=torch.int16, device="cuda")
+        keep += [B, Cm]
+        comps.append(lg.GemmDesc(A, B, Cm, M, N, K, True, lg.LAGOM_BF16))
+    return w, launches, comps, ncomm, keep
+
+
+def comm_bytes(launches):
+    from paper_2602_20656_amd import binding as lg
+    return [lg.lagom_comm_bytes(l.op, l.dtype, len(l.srcs), len(l.dsts), l.count) for l in launches]
+
+
+def standalone_comm_roofline(st1, st2, iters):
+    """Best standalone reduce-copy bandwidth over an extended NC set, on buffers rotated through
+    more than the 256 MB last-level cache so that HBM has to serve them."""
+    import torch
+    from paper_2602_20656_amd import binding as lg
+    count = 4194304                               # 16 MiB fp32 per buffer, 48 MiB moved per launch
+    nrot = 12                                     # 12 x 48 MiB = 576 MiB of distinct memory per pass
+    bufs = [[torch.empty(count, dtype=torch.float32, device="cuda").uniform_(-1, 1) for _ in range(3)] for _ in range(nrot)]
+    launches = [lg.CommLaunch(lg.LAGOM_REDUCE_COPY, lg.LAGOM_F32, [b[0], b[1]], [b[2]], count, 0) for b in bufs]
+    per_launch = lg.lagom_comm_bytes(lg.LAGOM_REDUCE_COPY, lg.LAGOM_F32, 2, 1, count)
+    best = None
+    for nc in (256, 512, 1024, 2048, 4096):
+        for nt in (256, 512, 1024):
+            for chunk in (16 << 10, 64 << 10, 256 << 10):
+                if nc * chunk > count * 4:
+                    continue
+                t = lg.lagom_overlap_run(launches, [(nc, nt, chunk)], [], st1, st2, 1, iters, lg.LAGOM_ALONE_COMM)
+                us = t.X_us / nrot
+                if best is None or us < best[0]:
+                    best = (us, (nc, nt, chunk))
+    us, cfg = best
+    gbps = per_launch / us / 1e3
+    return {"bound": "hbm", "kernel": "reduce_copy_kernel<f32, 2 sources>", "achieved": gbps, "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS, "traffic": None, "us_per_launch": us,
+            "bytes_per_launch": per_launch, "cfg": list(cfg), "rotation_mib": nrot * 48}
+
+
+def cpu_baseline(name, seconds_target=12.0):
+    """The oracle's plain C loops, timed on the host cores on a bounded sample of the same workload."""
+    from oracle import cloops
+    from paper_2602_20656_amd import inputs
+    w = inputs.WORKLOADS[name]
+    threads = cloops.max_threads()
+    # communication: the operator's launches, full size
+    if w.comm.dtype == "f32":
+        srcs = [inputs.uniform_f32(s, w.comm.count) for s in range(w.comm.nsrc)]
+    else:
+        srcs = [inputs.normal_bf16(s, w.comm.count, w.scale) for s in range(w.comm.nsrc)]
+    t0 = time.perf_counter()
+    if w.comm.op == "reduce_copy":
+        cloops.reduce_copy(srcs, w.comm.dtype, w.comm.ndst, threads)
+    else:
+        cloops.gather_copy(srcs, w.comm.ndst, threads)
+    comm_us = (time.perf_counter() - t0) * 1e6 * w.comm.launches * w.ncomm
+    # GEMM: a slice of rows, all columns, all of K, scaled linearly to M rows
+    M, N, K = w.gemm
+    a = inputs.normal_bf16(2, (M, K)); b = inputs.normal_bf16(3, (N, K), 0.02)
+    rows = min(M, 2 * threads)
+    t0 = time.perf_counter(); cloops.gemm(a, b, True, 0, rows, threads); dt = time.perf_counter() - t0
+    rows2 = int(min(M, max(rows, rows * seconds_target / max(dt, 1e-3)) // threads * threads))
+    if rows2 > rows:
+        t0 = time.perf_counter(); cloops.gemm(a, b, True, 0, rows2, threads); dt = time.perf_counter() - t0
+        rows = rows2
+    gemm_us = dt * 1e6 * (M / rows) * w.ncomp
+    return {"value": comm_us + gemm_us, "unit": "us/step", "cores": threads, "kind": "oracle",
+            "sample": f"communication launches at full size ({comm_us:.0f} us); GEMM rows 0..{rows} of {M}, all columns and K, "
+                      f"scaled by {M / rows:.1f} ({gemm_us:.0f} us); no overlap on the CPU",
+            "comm_us": comm_us, "gemm_us": gemm_us}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="dp_bucket", choices=["tiny", "dp_bucket", "tp_layer", "fsdp_chain", "compute_bound"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep-iters", type=int, default=5)
+    ap.add_argument("--dump", default=None, help="write the sweep table and tuner traces to this JSON file")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build covers one GPU's share of the overlapped step; run with --gpus 1 "
+              "(peer buffers are emulated in this GPU's HBM, there is no multi-GPU path)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2602_20656_amd import binding as lg
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    s_comm, s_comp = torch.cuda.Stream(), torch.cuda.Stream()
+
+    w, launches, comps, ncomm, keep = build_workload(args.workload)
+    nbytes = comm_bytes(launches)
+    M, N, K = w.gemm
+    flops = 2.0 * M * N * K
+
+    # ---- contention profiler over the workload's grid (NT fixed at 256 unless the workload sweeps it)
+    points = [(nc, nt, c) for nt in w.nt_grid for nc in w.nc_grid for c in w.chunk_grid]
+    t0 = time.perf_counter()
+    sweep = lg.lagom_contention_sweep(launches, ncomm, comps, points, s_comm, s_comp, 1, args.sweep_iters)
+    sweep_s = time.perf_counter() - t0
+
+    # ---- cost model filled from the sweep: x and V per configuration, theta fitted to the standalone GEMM
+    geo = lg.lagom_gemm_describe(M, N, K)
+    bw = HBM_PEAK_GBPS * 1e3                                     # bytes per microsecond
+    y_alone = sweep[0].comp_alone_us / len(comps)
+    g0 = -(-geo.mu // (LAMBDA * geo.tb))
+    theta = max(0.0, y_alone / g0 - LAMBDA * geo.tb * geo.d_bytes / bw)
+    tables = [{p.cfg: (p.comm_corun_us / ncomm, min(p.v_corun, 0.99 * bw)) for p in sweep} for _ in range(ncomm)]
+    model = lg.Model(LAMBDA, bw, [lg.CompModel(geo.mu, geo.tb, geo.d_bytes, theta) for _ in comps], tables)
+
+    # ---- the search: Alg. 1/2 with measured profiles, and with the model as ProfileTime
+    nt_grid = list(w.nt_grid) if len(w.nt_grid) > 1 else [256]
+    spaces = [lg.Space(list(w.nc_grid), nt_grid, list(w.chunk_grid)) for _ in range(ncomm)]
+    ladder_ok = all(tuple(c) in tables[0] for c in
+                    [(spaces[0].nc[min(l, len(spaces[0].nc) - 1)], spaces[0].nt[min(l, len(spaces[0].nt) - 1)],
+                      spaces[0].chunk[min(l, len(spaces[0].chunk) - 1)]) for l in range(max(len(spaces[0].nc), len(spaces[0].nt), len(spaces[0].chunk)))])
+    t0 = time.perf_counter()
+    tuned = lg.lagom_tune(spaces, lg.OverlapProfile(launches, comps, s_comm, s_comp, 1, args.sweep_iters), lg.LAGOM_PRIORITY)
+    tune_s = time.perf_counter() - t0
+    tuned_model = lg.lagom_tune(spaces, model, lg.LAGOM_PRIORITY) if ladder_ok else None
+
+    # ---- timed region: W warm-up steps, then exactly K steps with the tuned parameters
+    default_cfgs = [DEFAULT_CFG] * ncomm
+    lg.lagom_overlap_run(launches, tuned.cfgs, comps, s_comm, s_comp, args.warmup, 1, lg.LAGOM_CORUN)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    t_tuned = lg.lagom_overlap_run(launches, tuned.cfgs, comps, s_comm, s_comp, 0, args.steps, lg.LAGOM_CORUN)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    t_default = lg.lagom_overlap_run(launches, default_cfgs, comps, s_comm, s_comp, args.warmup, args.steps, lg.LAGOM_CORUN)
+    best_sweep = min(sweep, key=lambda p: p.z_corun_us)
+    comm_opt = min(sweep, key=lambda p: p.comm_alone_us)
+    t_commopt = lg.lagom_overlap_run(launches, [comm_opt.cfg] * ncomm, comps, s_comm, s_comp, args.warmup, args.steps, lg.LAGOM_CORUN)
+    t_model = (lg.lagom_overlap_run(launches, tuned_model.cfgs, comps, s_comm, s_comp, args.warmup, args.steps, lg.LAGOM_CORUN)
+               if tuned_model else None)
+
+    # ---- roofline of the dominant kernel (the GEMM), measured live with HIP events on its own stream
+    t_gemm = lg.lagom_overlap_run(launches, default_cfgs, comps, s_comm, s_comp, args.warmup, args.steps, lg.LAGOM_ALONE_COMP)
+    gemm_us = t_gemm.Y_us / len(comps)
+    tflops = flops / gemm_us / 1e6
+    roofline = {"bound": "mfma", "kernel": "gemm_bf16_kernel", "achieved": tflops, "peak": BF16_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": tflops / BF16_PEAK_TFLOPS, "traffic": None,
+                "us_per_launch": gemm_us, "flop_per_launch": flops}
+    roofline_comm = standalone_comm_roofline(s_comm, s_comp, 5)
+    # the workload's own communication, standalone, at its fastest swept point
+    t_comm = lg.lagom_overlap_run(launches, [comm_opt.cfg] * ncomm, comps, s_comm, s_comp, args.warmup, args.steps, lg.LAGOM_ALONE_COMM)
+
+    out = {
+        "metric": "overlap makespan speedup vs default params",
+        "value": t_default.Z_us / t_tuned.Z_us,
+        "unit": "x",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall_ms / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "comm": f"{w.comm.op} {w.comm.dtype} S={w.comm.nsrc} count={w.comm.count} "
+                   f"launches={len(launches)} comms={ncomm}", "gemm": f"{M}x{N}x{K} bf16 x{len(comps)}",
+                   "default_cfg": list(DEFAULT_CFG), "tuned_cfgs": [list(c) for c in tuned.cfgs]},
+        "z_tuned_us": t_tuned.Z_us, "z_default_us": t_default.Z_us,
+        "x_tuned_us": t_tuned.X_us, "y_tuned_us": t_tuned.Y_us, "x_default_us": t_default.X_us, "y_default_us": t_default.Y_us,
+        "z_comm_optimal_us": t_commopt.Z_us, "comm_optimal_cfg": list(comm_opt.cfg),
+        "z_best_swept_us": best_sweep.z_corun_us, "best_swept_cfg": list(best_sweep.cfg),
+        "z_model_tuned_us": t_model.Z_us if t_model else None,
+        "model_tuned_cfgs": [list(c) for c in tuned_model.cfgs] if tuned_model else None,
+        "model_predicted_z_us": tuned_model.Z if tuned_model else None,
+        "tune_profile_calls": tuned.calls, "tune_seconds": tune_s, "sweep_points": len(points), "sweep_seconds": sweep_s,
+        "gemm_alone_us": gemm_us, "gemm_mfma_util": tflops / BF16_PEAK_TFLOPS,
+        "gemm_slowdown_default": t_default.Y_us / t_gemm.Y_us, "gemm_slowdown_tuned": t_tuned.Y_us / t_gemm.Y_us,
+        "comm_alone_us": t_comm.X_us, "comm_alone_gbps": sum(nbytes) / t_comm.X_us / 1e3,
+        "comm_hbm_gbps": roofline_comm["achieved"],
+        "roofline": roofline, "roofline_comm": roofline_comm,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.workload)
+    if args.dump:
+        with open(args.dump, "w") as f:
+            json.dump({"sweep": [p.__dict__ for p in sweep],
+                       "trace": [s.__dict__ for s in tuned.trace],
+                       "model_trace": [s.__dict__ for s in tuned_model.trace] if tuned_model else None,
+                       "theta_us": theta, "geometry": {"mu": geo.mu, "tb": geo.tb, "d_bytes": geo.d_bytes}}, f, indent=1, default=str)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
