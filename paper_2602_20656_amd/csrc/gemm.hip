@@ -2,14 +2,29 @@
 // cores (v_mfma_f32_32x32x16_bf16), the computation whose slow-down the overlap model
 // describes (Sec. 3.2, Fig. 3).
 //
-// Tiling: one workgroup of 256 threads (4 wavefronts, 2 x 2) owns a 256 x 256 tile of C and
-// walks K in steps of 64.  Each wavefront owns 128 x 128 = 4 x 4 MFMA tiles of 32 x 32, i.e.
-// 256 fp32 accumulators per lane.  A and B tiles are staged in LDS as rows of 64 bf16
-// (128 bytes = eight 16-byte groups) with the group index XOR-ed by the row's low three bits,
-// so that the 16-byte operand reads of 8 consecutive rows spread over all banks.
-// The next K-step is fetched from HBM/L2 into registers while the matrix cores work on the
-// current one.  Workgroup ids are remapped so that the workgroups of one XCD (ids equal
-// modulo 8) cover a compact block of tiles and share A/B panels in that XCD's L2.
+// Tiling (both kernels): one workgroup of 256 threads (4 wavefronts, 2 x 2) owns a 256 x 256
+// tile of C and walks K in steps of 64; each wavefront owns 128 x 128 = 4 x 4 MFMA tiles of
+// 32 x 32, i.e. 256 fp32 accumulators per lane (the whole AGPR file), so one workgroup is
+// resident per compute unit.  Workgroup ids are remapped so that the workgroups of one XCD
+// (ids equal modulo 8) cover a compact block of tiles and share A/B panels in that XCD's L2.
+//
+// Fast kernel (B stored [N,K], K a multiple of 64):
+//   * A and B tiles go from global memory straight into LDS (global_load_lds_dwordx4), double
+//     buffered (2 x 64 KiB), the 16 load instructions of a wavefront spread one per group of
+//     four MFMAs: a wavefront that issues them in one burst stalls on the texture-address
+//     queue for most of the load time and starves the matrix core.
+//   * LDS rows are 128 bytes (64 bf16 = eight 16-byte groups); group g of row r is stored at
+//     position g ^ ((r >> 1) & 7).  LDS on gfx950 has 64 banks of 4 bytes, so two rows share a
+//     bank line; this swizzle makes the 16 lanes of a ds_read_b128 phase hit 16 distinct
+//     16-byte bank groups (measured: no bank-conflict cycles, against +50 % with r & 7).
+//   * Operand fragments are double buffered in registers: the reads for k-slice kk+1 are issued
+//     between the MFMAs of slice kk.
+//   * The MFMA is issued with the B fragment as first operand, so a lane ends up holding four
+//     consecutive columns of one row of C; bf16 results are packed (v_cvt_pk_bf16_f32), staged
+//     through LDS and written to HBM as full 16-byte vectors, 256 contiguous bytes per row.
+// General kernel (any K multiple of 8, either B layout): tiles are fetched into registers with
+// bounds checks and zero fill, then stored to LDS; single buffered.  Slower; used for ragged
+// K and for B stored [K,N].
 #include <hip/hip_runtime.h>
 #include "common.h"
 
@@ -58,7 +73,7 @@ __device__ __forceinline__ void tile_of(int id, int tiles_m, int tiles_n, int* t
 }
 
 template <bool B_NK, bool OUT_BF16>
-__global__ void __launch_bounds__(THREADS) gemm_bf16_kernel(const GemmArgs p) {
+__global__ void __launch_bounds__(THREADS) gemm_bf16_general_kernel(const GemmArgs p) {
     __shared__ u32x4 sA[BM * 8];
     __shared__ u32x4 sB[BN * 8];
 
@@ -181,6 +196,172 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_kernel(const GemmArgs p) {
         }
 }
 
+
+// ------------------------------------------------------------------------- fast kernel
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+constexpr int FAST_LDS_BYTES = 2 * (BM + BN) * BK * 2;   // two stages of an A and a B tile = 128 KiB
+constexpr int TILE_SLOTS = BM * 8;                       // 16-byte slots of one operand tile
+
+__device__ __forceinline__ int swz64(int row, int cg) { return row * 8 + (cg ^ ((row >> 1) & 7)); }
+
+// 16 bytes per lane from global memory straight into LDS: the wavefront writes 64 consecutive
+// 16-byte slots starting at `lds` (which must be wave-uniform).
+__device__ __forceinline__ void load_to_lds16(const void* g, void* lds) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                     (__attribute__((address_space(3))) void*)lds, 16, 0, 0);
+}
+
+template <bool OUT_BF16>
+__global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p) {
+    extern __shared__ u32x4 smem[];   // [stage][A 2048 slots | B 2048 slots]
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    int tm, tn;
+    tile_of(blockIdx.x, p.tiles_m, p.tiles_n, &tm, &tn);
+    const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
+    const int64_t M = p.M, N = p.N, K = p.K;
+
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    // Load instruction d (0..7 for A, 8..15 for B) of this wavefront fills slots [(d%8*4+wave)*64, +64):
+    // lane -> row (d%8*4+wave)*8 + lane/8, stored group lane%8, i.e. source group (lane%8) ^ ((row>>1)&7).
+    // (row>>1)&7 does not depend on d because rows of successive d differ by 32.
+    const int srow = wave * 8 + (lane >> 3);
+    const int scg = (lane & 7) ^ ((srow >> 1) & 7);
+    const uint16_t* ga = p.A + scg * 8;
+    const uint16_t* gb = p.B + scg * 8;
+    int64_t a_off[8], b_off[8];   // element offsets of the 8 source rows; rows past the edge re-read the last row
+#pragma unroll
+    for (int d = 0; d < 8; ++d) {
+        const int64_t ra = m0 + srow + 32 * d, rb = n0 + srow + 32 * d;
+        a_off[d] = (ra < M ? ra : M - 1) * K;
+        b_off[d] = (rb < N ? rb : N - 1) * K;
+    }
+    auto load_one = [&](int stage, int64_t k0, int d) {
+        u32x4* sa = smem + stage * 2 * TILE_SLOTS;
+        u32x4* sb = sa + TILE_SLOTS;
+        if (d < 8) load_to_lds16(ga + a_off[d] + k0, sa + (d * 4 + wave) * 64);
+        else load_to_lds16(gb + b_off[d - 8] + k0, sb + ((d - 8) * 4 + wave) * 64);
+    };
+
+    const int64_t ksteps = K / BK;
+#pragma unroll
+    for (int d = 0; d < 16; ++d) load_one(0, 0, d);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+
+    const int arow = wm * 128 + (lane & 31), brow = wn * 128 + (lane & 31), khalf = lane >> 5;
+    bf16x8 fa[2][4], fb[2][4];
+    auto read_frag = [&](const u32x4* sa, const u32x4* sb, int kk, int r, int slot) {   // r: A0..A3, B0..B3
+        if (r < 4) fa[slot][r] = __builtin_bit_cast(bf16x8, sa[swz64(arow + r * 32, kk * 2 + khalf)]);
+        else fb[slot][r - 4] = __builtin_bit_cast(bf16x8, sb[swz64(brow + (r - 4) * 32, kk * 2 + khalf)]);
+    };
+#pragma unroll
+    for (int r = 0; r < 8; ++r) read_frag(smem, smem + TILE_SLOTS, 0, r, 0);
+
+    for (int64_t kt = 0; kt < ksteps; ++kt) {
+        const int cur = (int)(kt & 1);
+        const u32x4* sa = smem + cur * 2 * TILE_SLOTS;
+        const u32x4* sb = sa + TILE_SLOTS;
+        const bool more = kt + 1 < ksteps;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                if (more) load_one(cur ^ 1, (kt + 1) * BK, kk * 4 + g);
+                if (kk < 3) {
+                    read_frag(sa, sb, kk + 1, g * 2, (kk + 1) & 1);
+                    read_frag(sa, sb, kk + 1, g * 2 + 1, (kk + 1) & 1);
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j)   // B fragment first: the lane's 16 results are C[row lane%32][4 x 4 consecutive columns]
+                    acc[g][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk & 1][j], fa[kk & 1][g], acc[g][j], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);   // keep this load / read / MFMA grouping
+            }
+        }
+        // the next tile has landed (this wavefront's part) and everyone is done reading this one
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        if (more) {
+            const u32x4* na = smem + (cur ^ 1) * 2 * TILE_SLOTS;
+#pragma unroll
+            for (int r = 0; r < 8; ++r) read_frag(na, na + TILE_SLOTS, 0, r, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+
+    // acc[i][j][v]: row i*32 + lane%32, column j*32 + 8*(v/4) + 4*(lane/32) + v%4 of the wavefront's 128 x 128 block
+    const int r_in = lane & 31, c_half = 4 * (lane >> 5);
+    if (OUT_BF16 && (N & 7) == 0) {
+        // stage the block as bf16 rows of 256 bytes (sixteen 16-byte groups, group c stored at c ^ (row & 15))
+        char* st = reinterpret_cast<char*>(smem) + wave * (128 * 256);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const int r = i * 32 + r_in;
+                    const int c = j * 32 + 8 * b + c_half;          // first of four consecutive columns
+                    const bf16x2 lo = __builtin_convertvector(f32x2{acc[i][j][4 * b], acc[i][j][4 * b + 1]}, bf16x2);
+                    const bf16x2 hi = __builtin_convertvector(f32x2{acc[i][j][4 * b + 2], acc[i][j][4 * b + 3]}, bf16x2);
+                    uint2 v;
+                    v.x = __builtin_bit_cast(uint32_t, lo);
+                    v.y = __builtin_bit_cast(uint32_t, hi);
+                    *reinterpret_cast<uint2*>(st + r * 256 + (((c >> 3) ^ (r & 15)) << 4) + ((c & 7) << 1)) = v;
+                }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // own writes only: a wavefront reads back its own block
+#pragma unroll 4
+        for (int t = 0; t < 32; ++t) {
+            const int r = (lane >> 4) + 4 * t, cv = lane & 15;
+            const u32x4 val = *reinterpret_cast<const u32x4*>(st + r * 256 + ((cv ^ (r & 15)) << 4));
+            const int64_t grow = m0 + wm * 128 + r, gcol = n0 + wn * 128 + cv * 8;
+            if (grow < M && gcol < N) *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(p.C) + grow * N + gcol) = val;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const int64_t row = m0 + wm * 128 + i * 32 + r_in;
+                    const int64_t col = n0 + wn * 128 + j * 32 + 8 * b + c_half;
+                    if (row >= M) continue;
+                    if (!OUT_BF16 && (N & 3) == 0 && col + 4 <= N) {
+                        *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(p.C) + row * N + col) =
+                            f32x4{acc[i][j][4 * b], acc[i][j][4 * b + 1], acc[i][j][4 * b + 2], acc[i][j][4 * b + 3]};
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (col + e < N) {
+                                if (OUT_BF16) reinterpret_cast<uint16_t*>(p.C)[row * N + col + e] = (uint16_t)bf16_round_bits(acc[i][j][4 * b + e]);
+                                else reinterpret_cast<float*>(p.C)[row * N + col + e] = acc[i][j][4 * b + e];
+                            }
+                    }
+                }
+    }
+}
+
+template <bool OUT_BF16>
+int launch_fast(const GemmArgs& a, dim3 grid, hipStream_t st) {
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_nk_kernel<OUT_BF16>),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, FAST_LDS_BYTES);
+    if (attr != hipSuccess) return lagom::fail(LAGOM_EHIP, "gemm: cannot raise the LDS limit: %s", hipGetErrorString(attr));
+    hipLaunchKernelGGL((gemm_bf16_nk_kernel<OUT_BF16>), grid, dim3(THREADS), FAST_LDS_BYTES, st, a);
+    return LAGOM_OK;
+}
+
 }  // namespace
 
 namespace lagom {
@@ -199,7 +380,7 @@ extern "C" int lagom_gemm_describe(int64_t M, int64_t N, int64_t K, lagom_dtype 
     if (!out || M < 1 || N < 1 || K < 1 || lagom::elem_size(out_dt) == 0) return lagom::fail(LAGOM_EINVAL, "bad argument");
     const int64_t tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
     out->mu = tm * tn;
-    out->tb = 1;   // 64 KiB of LDS and 256 accumulators per lane: one workgroup per compute unit
+    out->tb = 1;   // 256 accumulators per lane fill the AGPR file: one workgroup per compute unit
     out->d_bytes = (double)(BM + BN) * (double)K * 2.0 + (double)BM * BN * lagom::elem_size(out_dt);
     out->tile_m = BM; out->tile_n = BN; out->tile_k = BK; out->threads = THREADS;
     return LAGOM_OK;
@@ -216,12 +397,14 @@ extern "C" int lagom_gemm(const void* A, const void* B, void* C, int64_t M, int6
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const dim3 grid((unsigned)tiles), block(THREADS);
     const bool bf = out_dt == LAGOM_BF16;
-    if (b_is_nk) {
-        if (bf) hipLaunchKernelGGL((gemm_bf16_kernel<true, true>), grid, block, 0, st, a);
-        else hipLaunchKernelGGL((gemm_bf16_kernel<true, false>), grid, block, 0, st, a);
+    if (b_is_nk && K % BK == 0) {
+        if (int rc = bf ? launch_fast<true>(a, grid, st) : launch_fast<false>(a, grid, st)) return rc;
+    } else if (b_is_nk) {
+        if (bf) hipLaunchKernelGGL((gemm_bf16_general_kernel<true, true>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((gemm_bf16_general_kernel<true, false>), grid, block, 0, st, a);
     } else {
-        if (bf) hipLaunchKernelGGL((gemm_bf16_kernel<false, true>), grid, block, 0, st, a);
-        else hipLaunchKernelGGL((gemm_bf16_kernel<false, false>), grid, block, 0, st, a);
+        if (bf) hipLaunchKernelGGL((gemm_bf16_general_kernel<false, true>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((gemm_bf16_general_kernel<false, false>), grid, block, 0, st, a);
     }
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return lagom::fail(LAGOM_EHIP, "gemm launch: %s", hipGetErrorString(e));
