@@ -105,6 +105,6 @@ WORKLOADS = {
     "fsdp_chain": Workload("fsdp_chain", CommShape("gather_copy", "bf16", 8, 1, 2097152), 8,
                            (8192, 4096, 4096), 8, _NC, _C, (256,), tuple(range(30, 38)), scale=0.02),
     # back-to-back 16 MiB fp32 two-buffer reduce-copies against one 8192^3 GEMM
-    "compute_bound": Workload("compute_bound", CommShape("reduce_copy", "f32", 2, 1, 4194304), 1,
+    "compute_bound": Workload("compute_bound", CommShape("reduce_copy", "f32", 2, 1, 4194304, launches=3), 1,
                               (8192, 8192, 8192), 1, _NC, _C, (128, 256, 512, 1024), (40, 41)),
 }

@@ -148,3 +148,27 @@ def test_tp_reduce_scatter_share_full_size_sampled():
     for lo in [0, count - 4096] + [int(v) for v in rng.integers(0, count - 4096, size=14)]:
         want = oc.reduce_copy([s[lo:lo + 4096] for s in srcs], oc.BF16)[0]
         assert same_bits(got[lo:lo + 4096], want), lo
+
+
+def test_full_size_workload_launches_sampled():
+    """The other benchmark launches at full size and in their benchmark launch shapes; the oracle checks slices."""
+    rng = np.random.default_rng(1)
+    # DP bucket ring step: 1,638,400 bf16, two sources, two destinations (last reduce step)
+    m = 1638400
+    srcs = [inputs.normal_bf16(10 + s, m, scale=0.125) for s in range(2)]
+    outs = _run(lg.LAGOM_REDUCE_COPY, "bf16", srcs, 2, (32, 256, 128 << 10), m)
+    want = oc.reduce_copy(srcs, oc.BF16)[0]            # 1.6M elements: the oracle does all of them
+    assert same_bits(outs[0], want) and same_bits(outs[1], want)
+    # compute-bound: 4,194,304 fp32, two sources
+    n = 4194304
+    f = [inputs.uniform_f32(40 + s, n) for s in range(2)]
+    got = _run(lg.LAGOM_REDUCE_COPY, "f32", f, 1, (8, 256, 2 << 20), n)[0]
+    assert same_bits(got, oc.reduce_copy(f, oc.F32)[0])
+    # FSDP all-gather: 8 shards of 2,097,152 bf16 into one 32 MiB weight buffer
+    shards = [inputs.normal_bf16(3000 + p, 2097152, scale=0.02) for p in range(8)]
+    full = _run(lg.LAGOM_GATHER_COPY, "bf16", shards, 1, (8, 256, 2 << 20), 8 * 2097152)[0]
+    assert same_bits(full, oc.gather_copy(shards)[0])
+    # extended channel counts used for the standalone bandwidth figure
+    for cfg in [(512, 512, 16 << 10), (256, 1024, 32 << 10), (1024, 512, 64 << 10)]:
+        got = _run(lg.LAGOM_REDUCE_COPY, "f32", f, 1, cfg, n)[0]
+        assert same_bits(got, oc.reduce_copy(f, oc.F32)[0]), cfg
