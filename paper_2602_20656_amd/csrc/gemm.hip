@@ -9,10 +9,14 @@
 // (ids equal modulo 8) cover a compact block of tiles and share A/B panels in that XCD's L2.
 //
 // Fast kernel (B stored [N,K], K a multiple of 64):
-//   * A and B tiles go from global memory straight into LDS (global_load_lds_dwordx4), double
-//     buffered (2 x 64 KiB), the 16 load instructions of a wavefront spread one per group of
-//     four MFMAs: a wavefront that issues them in one burst stalls on the texture-address
-//     queue for most of the load time and starves the matrix core.
+//   * A and B tiles go from global memory straight into LDS (global_load_lds_dwordx4).  LDS
+//     holds five 32 KiB slots used as a ring A0,B0,A1,B1,A2,...: while step kt multiplies the
+//     tiles in two slots, B(kt+1) is loaded during its first half and A(kt+2) during its second
+//     half, so every load has at least half a step to land before it is needed and 1.5 tiles
+//     are in flight on average (one CU's load path delivers 65 GB/s with one tile in flight and
+//     90 GB/s with two; 77 GB/s are needed at full MFMA rate).  The 16 load instructions of a
+//     wavefront per step are spread one per group of four MFMAs: issued as a burst they stall
+//     the wavefront on the address queue for most of the load time and starve the matrix core.
 //   * LDS rows are 128 bytes (64 bf16 = eight 16-byte groups); group g of row r is stored at
 //     position g ^ ((r >> 1) & 7).  LDS on gfx950 has 64 banks of 4 bytes, so two rows share a
 //     bank line; this swizzle makes the 16 lanes of a ds_read_b128 phase hit 16 distinct
@@ -201,7 +205,8 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_general_kernel(const GemmAr
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-constexpr int FAST_LDS_BYTES = 2 * (BM + BN) * BK * 2;   // two stages of an A and a B tile = 128 KiB
+constexpr int LDS_SLOTS = 5;                             // ring of operand tiles: A0 B0 A1 B1 A2 ...
+constexpr int FAST_LDS_BYTES = LDS_SLOTS * BM * BK * 2;  // 160 KiB: all of a compute unit's LDS
 constexpr int TILE_SLOTS = BM * 8;                       // 16-byte slots of one operand tile
 
 __device__ __forceinline__ int swz64(int row, int cg) { return row * 8 + (cg ^ ((row >> 1) & 7)); }
@@ -215,7 +220,7 @@ __device__ __forceinline__ void load_to_lds16(const void* g, void* lds) {
 
 template <bool OUT_BF16>
 __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p) {
-    extern __shared__ u32x4 smem[];   // [stage][A 2048 slots | B 2048 slots]
+    extern __shared__ u32x4 smem[];   // LDS_SLOTS operand tiles of 2048 16-byte slots
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -233,8 +238,8 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    // Load instruction d (0..7 for A, 8..15 for B) of this wavefront fills slots [(d%8*4+wave)*64, +64):
-    // lane -> row (d%8*4+wave)*8 + lane/8, stored group lane%8, i.e. source group (lane%8) ^ ((row>>1)&7).
+    // Load instruction d (0..7) of an operand tile fills its 16-byte slots [(d*4+wave)*64, +64):
+    // lane -> row (d*4+wave)*8 + lane/8, stored group lane%8, i.e. source group (lane%8) ^ ((row>>1)&7).
     // (row>>1)&7 does not depend on d because rows of successive d differ by 32.
     const int srow = wave * 8 + (lane >> 3);
     const int scg = (lane & 7) ^ ((srow >> 1) & 7);
@@ -247,17 +252,23 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
         a_off[d] = (ra < M ? ra : M - 1) * K;
         b_off[d] = (rb < N ? rb : N - 1) * K;
     }
-    auto load_one = [&](int stage, int64_t k0, int d) {
-        u32x4* sa = smem + stage * 2 * TILE_SLOTS;
-        u32x4* sb = sa + TILE_SLOTS;
-        if (d < 8) load_to_lds16(ga + a_off[d] + k0, sa + (d * 4 + wave) * 64);
-        else load_to_lds16(gb + b_off[d - 8] + k0, sb + ((d - 8) * 4 + wave) * 64);
-    };
+    auto slot_ptr = [&](int slot) -> u32x4* { return smem + slot * TILE_SLOTS; };
+    auto load_a = [&](int slot, int64_t kt, int d) { load_to_lds16(ga + a_off[d] + kt * BK, slot_ptr(slot) + (d * 4 + wave) * 64); };
+    auto load_b = [&](int slot, int64_t kt, int d) { load_to_lds16(gb + b_off[d] + kt * BK, slot_ptr(slot) + (d * 4 + wave) * 64); };
 
     const int64_t ksteps = K / BK;
+    // prologue: A0 -> slot 0, B0 -> slot 1, A1 -> slot 2
 #pragma unroll
-    for (int d = 0; d < 16; ++d) load_one(0, 0, d);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    for (int d = 0; d < 8; ++d) load_a(0, 0, d);
+#pragma unroll
+    for (int d = 0; d < 8; ++d) load_b(1, 0, d);
+    if (ksteps > 1) {
+#pragma unroll
+        for (int d = 0; d < 8; ++d) load_a(2, 1, d);
+        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");   // loads complete in issue order: A0 and B0 are in
+    } else {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
     __builtin_amdgcn_s_barrier();
 
     const int arow = wm * 128 + (lane & 31), brow = wn * 128 + (lane & 31), khalf = lane >> 5;
@@ -267,18 +278,21 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
         else fb[slot][r - 4] = __builtin_bit_cast(bf16x8, sb[swz64(brow + (r - 4) * 32, kk * 2 + khalf)]);
     };
 #pragma unroll
-    for (int r = 0; r < 8; ++r) read_frag(smem, smem + TILE_SLOTS, 0, r, 0);
+    for (int r = 0; r < 8; ++r) read_frag(slot_ptr(0), slot_ptr(1), 0, r, 0);
 
+    int s_a = 0;   // slot of A(kt); B(kt), A(kt+1), B(kt+1), A(kt+2) follow at +1..+4 modulo 5
     for (int64_t kt = 0; kt < ksteps; ++kt) {
-        const int cur = (int)(kt & 1);
-        const u32x4* sa = smem + cur * 2 * TILE_SLOTS;
-        const u32x4* sb = sa + TILE_SLOTS;
-        const bool more = kt + 1 < ksteps;
+        const int s_b = (s_a + 1) % LDS_SLOTS, s_a1 = (s_a + 2) % LDS_SLOTS, s_b1 = (s_a + 3) % LDS_SLOTS, s_a2 = (s_a + 4) % LDS_SLOTS;
+        const u32x4* sa = slot_ptr(s_a);
+        const u32x4* sb = slot_ptr(s_b);
+        const bool more1 = kt + 1 < ksteps, more2 = kt + 2 < ksteps;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                if (more) load_one(cur ^ 1, (kt + 1) * BK, kk * 4 + g);
+                const int q = kk * 4 + g;
+                if (q < 8) { if (more1) load_b(s_b1, kt + 1, q); }        // slot freed by B(kt-1)
+                else { if (more2) load_a(s_a2, kt + 2, q - 8); }          // slot freed by A(kt-1)
                 if (kk < 3) {
                     read_frag(sa, sb, kk + 1, g * 2, (kk + 1) & 1);
                     read_frag(sa, sb, kk + 1, g * 2 + 1, (kk + 1) & 1);
@@ -289,15 +303,17 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
                 __builtin_amdgcn_sched_barrier(0);   // keep this load / read / MFMA grouping
             }
         }
-        // the next tile has landed (this wavefront's part) and everyone is done reading this one
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        // tile kt+1 has landed (this wavefront's part; the 8 youngest loads, A(kt+2), may still fly)
+        // and after the barrier everyone is done reading tile kt
+        if (more2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
-        if (more) {
-            const u32x4* na = smem + (cur ^ 1) * 2 * TILE_SLOTS;
+        if (more1) {
 #pragma unroll
-            for (int r = 0; r < 8; ++r) read_frag(na, na + TILE_SLOTS, 0, r, 0);
+            for (int r = 0; r < 8; ++r) read_frag(slot_ptr(s_a1), slot_ptr(s_b1), 0, r, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
+        s_a = s_a1;
     }
 
     // acc[i][j][v]: row i*32 + lane%32, column j*32 + 8*(v/4) + 4*(lane/32) + v%4 of the wavefront's 128 x 128 block
