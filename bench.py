@@ -25,6 +25,13 @@ import numpy as np  # noqa: E402
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 BF16_PEAK_TFLOPS = 2500.0       # MI355X dense bf16 MFMA, published
 LAMBDA = 256                    # compute units
+# Bytes past L2 per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by the same counters' reading of a plain
+# 64 MiB copy (factors 1.9985 and 0.9991); figures and commands: profiles/bench_dp_bucket_hbm_counters.md
+MEASURED_TRAFFIC_BYTES = {
+    "gemm 4096x4096x4096": int(226.9 * (1 << 20)),
+    "reduce_copy bf16 S=8 D=1 count=4194304": int(72.0 * (1 << 20)),
+    "reduce_copy f32 S=2 D=1 count=4194304": int(48.0 * (1 << 20)),
+}
 DEFAULT_CFG = (8, 256, 2 << 20)  # the collective library default the paper quotes (Sec. 4.3), NT from the tiny config
 
 
@@ -127,7 +134,8 @@ def standalone_comm_roofline(st1, st2, iters):
                     gbps = per_launch / us / 1e3
                     if best is None or gbps > best["achieved"]:
                         best = {"bound": "hbm", "kernel": "reduce_copy_kernel", "workload": name, "achieved": gbps,
-                                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS, "traffic": None,
+                                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS,
+                                "traffic": MEASURED_TRAFFIC_BYTES.get(name),
                                 "us_per_launch": us, "bytes_per_launch": per_launch, "cfg": [nc, nt, chunk],
                                 "rotation_mib": nrot * per_launch >> 20}
         del bufs, launches
@@ -239,11 +247,19 @@ def main():
     gemm_us = t_gemm.Y_us / len(comps)
     tflops = flops / gemm_us / 1e6
     roofline = {"bound": "mfma", "kernel": "gemm_bf16_nk_kernel", "achieved": tflops, "peak": BF16_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": tflops / BF16_PEAK_TFLOPS, "traffic": None,
+                "unit": "TFLOP/s", "frac": tflops / BF16_PEAK_TFLOPS,
+                "traffic": MEASURED_TRAFFIC_BYTES.get(f"gemm {M}x{N}x{K}"),
                 "us_per_launch": gemm_us, "flop_per_launch": flops}
     roofline_comm = standalone_comm_roofline(s_comm, s_comp, 5)
     # the workload's own communication, standalone, at its fastest swept point
     t_comm = lg.lagom_overlap_run(launches, [comm_opt.cfg] * ncomm, comps, s_comm, s_comp, args.warmup, args.steps, lg.LAGOM_ALONE_COMM)
+
+    # one plain copy of known size (64 MiB read, 64 MiB written): the reference that rocprofv3's FETCH_SIZE /
+    # WRITE_SIZE readings of the other kernels are scaled by
+    cal_src = torch.empty(16 << 20, dtype=torch.float32, device="cuda").uniform_(-1, 1)
+    cal_dst = torch.empty_like(cal_src)
+    lg.lagom_comm_kernel(lg.LAGOM_GATHER_COPY, lg.LAGOM_F32, [cal_src], [cal_dst], 16 << 20, (1000, 512, 64 << 10), s_comm)
+    torch.cuda.synchronize()
 
     out = {
         "metric": "overlap makespan speedup vs default params",

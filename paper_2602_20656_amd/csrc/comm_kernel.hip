@@ -108,8 +108,8 @@ __device__ __forceinline__ void reduce_tail_element(const CommArgs& p, int64_t b
 // S > 0: number of sources known at compile time (all loads of a batch issued before the
 // first add).  S == 0: any number of sources, loaded source by source.
 // U: 16-byte vectors a lane has in flight per source.
-template <int DT, int S, int U, bool STREAM>
-__global__ void __launch_bounds__(1024) reduce_copy_kernel(const CommArgs p) {
+template <int DT, int S, int U, bool STREAM, int MAXNT>
+__global__ void __launch_bounds__(MAXNT) reduce_copy_kernel(const CommArgs p) {
     const int nt = blockDim.x;
     const int tid = threadIdx.x;
     const int esize = DT == LAGOM_F32 ? 4 : 2;
@@ -156,8 +156,8 @@ __global__ void __launch_bounds__(1024) reduce_copy_kernel(const CommArgs p) {
 
 // Gather-copy with 16-byte vectors; needs shard_bytes % 16 == 0 (or a single shard) so that
 // every shard starts 16-byte aligned in the destination.
-template <int U, bool STREAM>
-__global__ void __launch_bounds__(1024) gather_copy_kernel(const CommArgs p) {
+template <int U, bool STREAM, int MAXNT>
+__global__ void __launch_bounds__(MAXNT) gather_copy_kernel(const CommArgs p) {
     const int nt = blockDim.x;
     const int tid = threadIdx.x;
     for (int64_t g = blockIdx.x; g < p.total_chunks; g += gridDim.x) {
@@ -208,16 +208,31 @@ __global__ void __launch_bounds__(1024) gather_copy_elements_kernel(const CommAr
     }
 }
 
-template <int DT, bool STREAM>
+// MAXNT is the launch bound the kernel is compiled for: 512 threads leave 256 registers per lane,
+// 1024 only 128.  Measured on the eight-source bf16 reduce: the same code compiled for 1024 threads
+// loses up to 40 % at 512 threads because the loads of a batch no longer stay in flight together.
+template <int DT, bool STREAM, int MAXNT>
 void launch_reduce(const CommArgs& a, dim3 grid, dim3 block, hipStream_t st) {
     switch (a.nsrc) {
-        case 1: hipLaunchKernelGGL((reduce_copy_kernel<DT, 1, 4, STREAM>), grid, block, 0, st, a); break;
-        case 2: hipLaunchKernelGGL((reduce_copy_kernel<DT, 2, 4, STREAM>), grid, block, 0, st, a); break;
-        case 3: hipLaunchKernelGGL((reduce_copy_kernel<DT, 3, 4, STREAM>), grid, block, 0, st, a); break;
-        case 4: hipLaunchKernelGGL((reduce_copy_kernel<DT, 4, 4, STREAM>), grid, block, 0, st, a); break;
-        case 8: hipLaunchKernelGGL((reduce_copy_kernel<DT, 8, 2, STREAM>), grid, block, 0, st, a); break;
-        default: hipLaunchKernelGGL((reduce_copy_kernel<DT, 0, 1, STREAM>), grid, block, 0, st, a); break;
+        case 1: hipLaunchKernelGGL((reduce_copy_kernel<DT, 1, 4, STREAM, MAXNT>), grid, block, 0, st, a); break;
+        case 2: hipLaunchKernelGGL((reduce_copy_kernel<DT, 2, 4, STREAM, MAXNT>), grid, block, 0, st, a); break;
+        case 3: hipLaunchKernelGGL((reduce_copy_kernel<DT, 3, 4, STREAM, MAXNT>), grid, block, 0, st, a); break;
+        case 4: hipLaunchKernelGGL((reduce_copy_kernel<DT, 4, 4, STREAM, MAXNT>), grid, block, 0, st, a); break;
+        case 8: hipLaunchKernelGGL((reduce_copy_kernel<DT, 8, 2, STREAM, MAXNT>), grid, block, 0, st, a); break;
+        default: hipLaunchKernelGGL((reduce_copy_kernel<DT, 0, 1, STREAM, MAXNT>), grid, block, 0, st, a); break;
     }
+}
+
+template <int DT, bool STREAM>
+void launch_reduce_nt(const CommArgs& a, dim3 grid, dim3 block, hipStream_t st) {
+    if (block.x <= 512) launch_reduce<DT, STREAM, 512>(a, grid, block, st);
+    else launch_reduce<DT, STREAM, 1024>(a, grid, block, st);
+}
+
+template <bool STREAM>
+void launch_gather(const CommArgs& a, dim3 grid, dim3 block, hipStream_t st) {
+    if (block.x <= 512) hipLaunchKernelGGL((gather_copy_kernel<4, STREAM, 512>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((gather_copy_kernel<4, STREAM, 1024>), grid, block, 0, st, a);
 }
 
 }  // namespace
@@ -279,11 +294,10 @@ extern "C" int lagom_comm_kernel(lagom_op op, lagom_dtype dt, const void* const*
     const dim3 grid((unsigned)cfg->nc), block((unsigned)cfg->nt);
     const bool stream = cfg->nc >= kStreamLoadsFromNC;
     if (op == LAGOM_REDUCE_COPY) {
-        if (dt == LAGOM_F32) stream ? launch_reduce<LAGOM_F32, true>(a, grid, block, st) : launch_reduce<LAGOM_F32, false>(a, grid, block, st);
-        else stream ? launch_reduce<LAGOM_BF16, true>(a, grid, block, st) : launch_reduce<LAGOM_BF16, false>(a, grid, block, st);
+        if (dt == LAGOM_F32) stream ? launch_reduce_nt<LAGOM_F32, true>(a, grid, block, st) : launch_reduce_nt<LAGOM_F32, false>(a, grid, block, st);
+        else stream ? launch_reduce_nt<LAGOM_BF16, true>(a, grid, block, st) : launch_reduce_nt<LAGOM_BF16, false>(a, grid, block, st);
     } else if (nsrc == 1 || (a.shard_bytes & 15) == 0) {
-        if (stream) hipLaunchKernelGGL((gather_copy_kernel<4, true>), grid, block, 0, st, a);
-        else hipLaunchKernelGGL((gather_copy_kernel<4, false>), grid, block, 0, st, a);
+        stream ? launch_gather<true>(a, grid, block, st) : launch_gather<false>(a, grid, block, st);
     } else if (dt == LAGOM_F32) {
         hipLaunchKernelGGL((gather_copy_elements_kernel<uint32_t>), grid, block, 0, st, a);
     } else {
