@@ -226,6 +226,8 @@ def main():
     tuned = lg.lagom_tune(spaces, lg.OverlapProfile(launches, comps, s_comm, s_comp, 1, args.sweep_iters), lg.LAGOM_PRIORITY)
     tune_s = time.perf_counter() - t0
     tuned_model = lg.lagom_tune(spaces, model, lg.LAGOM_PRIORITY) if ladder_ok else None
+    # the communication-bound reference (Eq. 2): per-communication coordinate descent on x_j alone
+    comm_cd = lg.lagom_tune(spaces, lg.OverlapProfile(launches, comps, s_comm, s_comp, 1, args.sweep_iters), lg.LAGOM_COMM_OPTIMAL)
 
     # ---- timed region: W warm-up steps, then exactly K steps with the tuned parameters
     default_cfgs = [DEFAULT_CFG] * ncomm
@@ -239,6 +241,7 @@ def main():
     best_sweep = min(sweep, key=lambda p: p.z_corun_us)
     comm_opt = min(sweep, key=lambda p: p.comm_alone_us)
     t_commopt = lg.lagom_overlap_run(launches, [comm_opt.cfg] * ncomm, comps, s_comm, s_comp, args.warmup, args.steps, lg.LAGOM_CORUN)
+    t_commcd = lg.lagom_overlap_run(launches, comm_cd.cfgs, comps, s_comm, s_comp, args.warmup, args.steps, lg.LAGOM_CORUN)
     t_model = (lg.lagom_overlap_run(launches, tuned_model.cfgs, comps, s_comm, s_comp, args.warmup, args.steps, lg.LAGOM_CORUN)
                if tuned_model else None)
 
@@ -275,6 +278,7 @@ def main():
         "z_tuned_us": t_tuned.Z_us, "z_default_us": t_default.Z_us,
         "x_tuned_us": t_tuned.X_us, "y_tuned_us": t_tuned.Y_us, "x_default_us": t_default.X_us, "y_default_us": t_default.Y_us,
         "z_comm_optimal_us": t_commopt.Z_us, "comm_optimal_cfg": list(comm_opt.cfg),
+        "z_comm_descent_us": t_commcd.Z_us, "comm_descent_cfgs": [list(c) for c in comm_cd.cfgs], "comm_descent_calls": comm_cd.calls,
         "z_best_swept_us": best_sweep.z_corun_us, "best_swept_cfg": list(best_sweep.cfg),
         "z_model_tuned_us": t_model.Z_us if t_model else None,
         "model_tuned_cfgs": [list(c) for c in tuned_model.cfgs] if tuned_model else None,

@@ -230,6 +230,13 @@ int lagom_cost_model(const lagom_model* m, const lagom_cfg* cfgs, int ncomm, lag
  * LAGOM_EXHAUSTIVE: every level vector in lexicographic order; the smallest Z wins,
  * ties to the smallest level sum, then to the lexicographically smallest vector.
  * Refused (LAGOM_EINVAL) above 2^20 vectors.
+ * LAGOM_COMM_OPTIMAL: the communication-bound regime (Eq. 2), where Z = sum_j x_j separates:
+ * each x_j is minimised on its own over the full (NC, NT, C) product by coordinate descent with
+ * measured feedback -- communications in index order, the others staying where they are; start
+ * at the minimum of every grid, sweep the coordinates NC, C, NT: one grid step up while x_j falls
+ * strictly, else down while it falls strictly; repeat until a sweep changes nothing.  This is
+ * the point a tuner that looks at communication time only would pick.  trace->levels receives
+ * the NC grid index of every communication; no steps are recorded.
  */
 typedef int (*lagom_profile_fn)(void* user, const lagom_cfg* cfgs, int ncomm,
                                 double* x_us /* out [ncomm] */, double* Y_us /* out */);
@@ -258,7 +265,7 @@ typedef struct {
     int32_t* levels;             /* host [ncomm] out (nullable)                         */
 } lagom_trace;
 
-typedef enum { LAGOM_PRIORITY = 0, LAGOM_EXHAUSTIVE = 1 } lagom_tune_mode;
+typedef enum { LAGOM_PRIORITY = 0, LAGOM_EXHAUSTIVE = 1, LAGOM_COMM_OPTIMAL = 2 } lagom_tune_mode;
 
 /*   spaces[ncomm], out_cfgs[ncomm] host arrays; trace nullable.
  * Errors: LAGOM_EINVAL (null, ncomm < 1 or > LAGOM_MAX_COMMS, empty or non-ascending

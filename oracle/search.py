@@ -212,3 +212,59 @@ def brute_force_full_product(spaces: Sequence[Space], profile: ProfileFn):
         if best is None or Z < best[1]:
             best = (list(cfgs), Z)
     return best[0], best[1], calls
+
+
+def coordinate_descent(spaces: Sequence[Space], profile: ProfileFn) -> Result:
+    """Communication-bound regime (Eq. 2): the makespan is the sum of the x_j and separates per
+    communication, so each x_j is minimised on its own over the full (NC, NT, C) product.
+
+    The paper only names the method of its predecessor for this regime (coordinate descent over the
+    resource parameters with measured feedback) and gives no steps; this build's definition:
+    communications are taken in index order, the others staying where they are (the grid minimum
+    until they have been tuned); for one communication, starting from the minimum of every grid,
+    sweep the coordinates in the order NC, C, NT; along a coordinate go one grid step up while x_j
+    falls strictly, and if the first step up did not help go down while x_j falls strictly; repeat
+    the sweeps until one changes nothing.  Every probe is one profile call.
+    """
+    N = len(spaces)
+    idx = [[0, 0, 0] for _ in range(N)]               # indices into (nc, nt, chunk)
+    grids = [(sp.nc, sp.nt, sp.chunk) for sp in spaces]
+    calls = 0
+
+    def cfgs_of(ix):
+        return [(g[0][i[0]], g[1][i[1]], g[2][i[2]]) for g, i in zip(grids, ix)]
+
+    def probe(ix):
+        nonlocal calls
+        x, Y = profile(cfgs_of(ix))
+        calls += 1
+        return [float(v) for v in x], float(Y)
+
+    x, Y = probe(idx)
+    for j in range(N):
+        best = x[j]
+        changed = True
+        while changed:
+            changed = False
+            for p in (0, 2, 1):                       # NC, C, NT
+                moved_up = False
+                while idx[j][p] + 1 < len(grids[j][p]):
+                    idx[j][p] += 1
+                    x2, Y2 = probe(idx)
+                    if x2[j] < best:
+                        best, x, Y, moved_up, changed = x2[j], x2, Y2, True, True
+                    else:
+                        idx[j][p] -= 1
+                        break
+                if moved_up:
+                    continue
+                while idx[j][p] - 1 >= 0:
+                    idx[j][p] -= 1
+                    x2, Y2 = probe(idx)
+                    if x2[j] < best:
+                        best, x, Y, changed = x2[j], x2, Y2, True
+                    else:
+                        idx[j][p] += 1
+                        break
+    X = _sum(x)
+    return Result(levels=[i[0] for i in idx], cfgs=cfgs_of(idx), x=x, X=X, Y=Y, Z=max(X, Y), calls=calls)

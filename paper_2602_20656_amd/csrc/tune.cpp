@@ -1,6 +1,7 @@
 // Priority-based parameter search (metric H of Eq. 7, Alg. 1 driving Alg. 2) and the
 // exhaustive search over the same ladder space.  Host only; measuring is the callback's.
 // Compiled with floating-point contraction off.
+#include <array>
 #include <cmath>
 #include <limits>
 #include <vector>
@@ -167,13 +168,81 @@ int exhaustive(const std::vector<Ladder>& L, lagom_profile_fn profile, void* use
     return LAGOM_OK;
 }
 
+
+// Communication-bound regime (Eq. 2): Z is the sum of the x_j and separates per communication, so
+// each x_j is minimised on its own over the full (NC, NT, C) product by coordinate descent with
+// measured feedback.  Communications in index order, the others staying where they are; for one
+// communication start at the minimum of every grid and sweep the coordinates NC, C, NT: one grid
+// step up while x_j falls strictly, and if the first step up did not help, down while x_j falls
+// strictly; repeat the sweeps until one changes nothing.  Every probe is one profile call.
+int comm_optimal(const std::vector<Ladder>& L, lagom_profile_fn profile, void* user, lagom_cfg* out_cfgs, lagom_trace* tr) {
+    const int N = (int)L.size();
+    std::vector<std::array<int, 3>> idx(N, std::array<int, 3>{0, 0, 0});
+    std::vector<lagom_cfg> cfgs(N);
+    std::vector<double> x(N), x2(N);
+    double Y = 0.0, Y2 = 0.0;
+    int calls = 0;
+    auto size_of = [&](int j, int p) { return p == 0 ? L[j].sp->n_nc : (p == 1 ? L[j].sp->n_nt : L[j].sp->n_chunk); };
+    auto fill = [&]() {
+        for (int j = 0; j < N; ++j)
+            cfgs[j] = lagom_cfg{L[j].sp->nc[idx[j][0]], L[j].sp->nt[idx[j][1]], L[j].sp->chunk[idx[j][2]]};
+    };
+    auto finish = [&](int rc) {
+        fill();
+        for (int j = 0; j < N; ++j) out_cfgs[j] = cfgs[j];
+        if (tr) {
+            tr->calls = calls;
+            double X = 0.0;
+            for (int j = 0; j < N; ++j) X = X + x[j];
+            tr->X = X; tr->Y = Y; tr->Z = X > Y ? X : Y;
+            if (tr->levels) for (int j = 0; j < N; ++j) tr->levels[j] = idx[j][0];
+        }
+        return rc;
+    };
+    auto probe = [&](std::vector<double>& xs, double* y) -> int {
+        fill();
+        if (profile(user, cfgs.data(), N, xs.data(), y) != 0) return LAGOM_ECALLBACK;
+        for (int j = 0; j < N; ++j)
+            if (!(xs[j] >= 0.0) || !std::isfinite(xs[j])) return LAGOM_ECALLBACK;
+        if (!(*y >= 0.0) || !std::isfinite(*y)) return LAGOM_ECALLBACK;
+        ++calls;
+        return LAGOM_OK;
+    };
+    if (int rc = probe(x, &Y)) return finish(lagom::fail(rc, "baseline profile failed"));
+    static const int order[3] = {0, 2, 1};   // NC, C, NT
+    for (int j = 0; j < N; ++j) {
+        double best = x[j];
+        bool changed = true;
+        while (changed) {
+            changed = false;
+            for (int p : order) {
+                bool moved_up = false;
+                while (idx[j][p] + 1 < size_of(j, p)) {
+                    idx[j][p] += 1;
+                    if (int rc = probe(x2, &Y2)) { idx[j][p] -= 1; return finish(lagom::fail(rc, "profile call %d failed", calls + 1)); }
+                    if (x2[j] < best) { best = x2[j]; x = x2; Y = Y2; moved_up = true; changed = true; }
+                    else { idx[j][p] -= 1; break; }
+                }
+                if (moved_up) continue;
+                while (idx[j][p] - 1 >= 0) {
+                    idx[j][p] -= 1;
+                    if (int rc = probe(x2, &Y2)) { idx[j][p] += 1; return finish(lagom::fail(rc, "profile call %d failed", calls + 1)); }
+                    if (x2[j] < best) { best = x2[j]; x = x2; Y = Y2; changed = true; }
+                    else { idx[j][p] += 1; break; }
+                }
+            }
+        }
+    }
+    return finish(LAGOM_OK);
+}
+
 }  // namespace
 
 extern "C" int lagom_tune(const lagom_tune_space* spaces, int ncomm, lagom_profile_fn profile, void* user,
                           int mode, lagom_cfg* out_cfgs, lagom_trace* trace) {
     if (!spaces || !profile || !out_cfgs) return lagom::fail(LAGOM_EINVAL, "null argument");
     if (ncomm < 1 || ncomm > LAGOM_MAX_COMMS) return lagom::fail(LAGOM_EINVAL, "ncomm=%d outside 1..%d", ncomm, LAGOM_MAX_COMMS);
-    if (mode != LAGOM_PRIORITY && mode != LAGOM_EXHAUSTIVE) return lagom::fail(LAGOM_EINVAL, "unknown mode %d", mode);
+    if (mode != LAGOM_PRIORITY && mode != LAGOM_EXHAUSTIVE && mode != LAGOM_COMM_OPTIMAL) return lagom::fail(LAGOM_EINVAL, "unknown mode %d", mode);
     std::vector<Ladder> L(ncomm);
     for (int j = 0; j < ncomm; ++j) {
         const lagom_tune_space& s = spaces[j];
@@ -186,6 +255,7 @@ extern "C" int lagom_tune(const lagom_tune_space* spaces, int ncomm, lagom_profi
         trace->n = 0; trace->calls = 0;
         if (trace->steps && trace->capacity < 0) return lagom::fail(LAGOM_EINVAL, "negative trace capacity");
     }
-    return mode == LAGOM_PRIORITY ? priority(L, profile, user, out_cfgs, trace)
-                                  : exhaustive(L, profile, user, out_cfgs, trace);
+    if (mode == LAGOM_PRIORITY) return priority(L, profile, user, out_cfgs, trace);
+    if (mode == LAGOM_EXHAUSTIVE) return exhaustive(L, profile, user, out_cfgs, trace);
+    return comm_optimal(L, profile, user, out_cfgs, trace);
 }

@@ -234,3 +234,13 @@ def test_callback_failure_returns_best_so_far():
         lg.lagom_tune([lg.Space([2, 1], [256], [65536])], profile)
     with pytest.raises(lg.LagomError):
         lg.lagom_tune([lg.Space([1], [256], [65536])], lambda c: ([float("nan")], 1.0))
+
+
+def test_comm_optimal_mode_equals_oracle_coordinate_descent():
+    rng = np.random.default_rng(21)
+    for _ in range(200):
+        N = int(rng.integers(1, 6))
+        so, sl, profile = _random_chain(rng, N)
+        ro = osr.coordinate_descent(so, profile)
+        rl = lg.lagom_tune(sl, profile, lg.LAGOM_COMM_OPTIMAL)
+        assert rl.cfgs == ro.cfgs and rl.calls == ro.calls and (rl.X, rl.Y, rl.Z) == (ro.X, ro.Y, ro.Z)

@@ -174,3 +174,51 @@ def test_profile_callback_sees_only_ladder_configurations():
     res = os_.priority_search([sp], profile)
     assert seen <= {sp.cfg(l) for l in range(sp.K)}
     assert res.levels == [3] and res.cfgs == [(8, 256, 16384)]      # communication-bound: climbs to the top
+
+
+# ------------------------------------------------------- communication-bound regime (Eq. 2)
+def _separable_table(rng, sp):
+    """x(nc, nt, c) = f(nc) + g(nt) + h(c) with each term unimodal along its grid."""
+    def unimodal(n):
+        turn = int(rng.integers(0, n))
+        v = [float(rng.uniform(20, 60))]
+        for i in range(1, n):
+            v.append(v[-1] * (rng.uniform(0.5, 0.95) if i <= turn else rng.uniform(1.05, 1.6)))
+        return v
+    return unimodal(len(sp.nc)), unimodal(len(sp.nt)), unimodal(len(sp.chunk))
+
+
+def test_coordinate_descent_finds_the_separable_minimum_of_every_communication():
+    rng = np.random.default_rng(77)
+    for _ in range(100):
+        N = int(rng.integers(1, 4))
+        spaces = [os_.Space(sorted(rng.choice(64, size=rng.integers(1, 6), replace=False) + 1),
+                            [64 << i for i in range(int(rng.integers(1, 5)))],
+                            [1024 << i for i in range(int(rng.integers(1, 6)))]) for _ in range(N)]
+        tabs = [_separable_table(rng, sp) for sp in spaces]
+
+        def profile(cfgs):
+            x = []
+            for j, c in enumerate(cfgs):
+                sp, (f, g, h) = spaces[j], tabs[j]
+                x.append(f[list(sp.nc).index(c[0])] + g[list(sp.nt).index(c[1])] + h[list(sp.chunk).index(c[2])])
+            return x, 1.0                                  # communication-bound: Y is irrelevant
+        res = os_.coordinate_descent(spaces, profile)
+        for j, sp in enumerate(spaces):
+            f, g, h = tabs[j]
+            want = (sp.nc[int(np.argmin(f))], sp.nt[int(np.argmin(g))], sp.chunk[int(np.argmin(h))])
+            assert res.cfgs[j] == want
+        # Eq. 2: the minimum of the sum is the sum of the minima, and equals exhaustive search over the full product
+        assert res.X == pytest.approx(sum(min(f) + min(g) + min(h) for f, g, h in tabs), rel=1e-12)
+        if N == 1:
+            cfgs, Z, _ = os_.brute_force_full_product(spaces, profile)
+            assert cfgs == res.cfgs and Z == pytest.approx(res.Z)
+        assert res.calls <= 1 + sum(3 * (len(sp.nc) + len(sp.nt) + len(sp.chunk) + 3) for sp in spaces)
+
+
+def test_coordinate_descent_climbs_when_more_resources_always_help_and_stays_when_they_never_do():
+    sp = os_.Space([1, 2, 4, 8], [128, 256], [4096, 8192, 16384])
+    up = os_.coordinate_descent([sp], lambda c: ([1e6 / (c[0][0] * c[0][1] * c[0][2])], 0.0))
+    assert up.cfgs == [(8, 256, 16384)]
+    stay = os_.coordinate_descent([sp], lambda c: ([float(c[0][0] + c[0][1] + c[0][2])], 0.0))
+    assert stay.cfgs == [(1, 128, 4096)] and stay.calls == 1 + 3   # one failed probe per coordinate
