@@ -114,6 +114,8 @@ typedef struct {
     int64_t count;
     int32_t comm_id;            /* the tunable communication this launch belongs to:
                                    index into cfgs; launches of one id are contiguous  */
+    int32_t after_comp;         /* index of a computation that must have finished before this
+                                   launch starts, or -1 (honoured in LAGOM_CORUN only)  */
 } lagom_comm_desc;
 
 typedef struct {
@@ -121,6 +123,8 @@ typedef struct {
     int64_t M, N, K;
     int32_t b_is_nk;
     int32_t out_dtype;
+    int32_t after_comm_id;      /* communication (comm_id) whose last launch must have finished
+                                   before this GEMM starts, or -1 (LAGOM_CORUN only)    */
 } lagom_gemm_desc;
 
 typedef enum { LAGOM_ALONE_COMM = 0, LAGOM_ALONE_COMP = 1, LAGOM_CORUN = 2 } lagom_run_mode;
@@ -139,6 +143,10 @@ typedef struct {
  *   comm_stream, comp_stream : two distinct hipStream_t of default priority.
  *   Each of warmup + iters repetitions starts both streams together behind a gate and
  *   drains both before the next; every value reported is the median over `iters`.
+ *   Cross-stream dependencies (after_comp / after_comm_id) are enforced with events in
+ *   LAGOM_CORUN; the two enqueue orders are merged on the host so that every awaited event
+ *   has been recorded first, and a dependency cycle is LAGOM_EINVAL.  With dependencies X and
+ *   Y still run from a stream's first kernel start to its last kernel end (waits included).
  *   The call synchronises both streams and owns its events.
  * Errors: LAGOM_EINVAL, LAGOM_EALIGN, LAGOM_EHIP.
  */
@@ -184,6 +192,10 @@ int64_t lagom_comm_bytes(int op, int dtype, int nsrc, int ndst, int64_t count);
  * communication j is active on [sum_{<j} x, sum_{<=j} x); a wave that starts under j
  * (or after the last one: NC = 0, V = 0) retires min(remaining, (lambda-NC_j)*TB_i)
  * workgroups and lasts f_ij; g_ij counts the waves issued under j.
+ * With dependencies each stream stays serial, an operator starts at the later of its stream
+ * being free and its dependency having ended, the wave stepping is unchanged, and Z is the later
+ * of the two stream ends (X and Y remain the sums of the x_j and y_i).  A dependency cycle is
+ * LAGOM_EINVAL.
  */
 typedef struct { lagom_cfg cfg; double x_us; double v; } lagom_table_entry;
 typedef struct { const lagom_table_entry* entries; int32_t n; } lagom_comm_table;
@@ -195,6 +207,13 @@ typedef struct {
     int32_t ncomp;
     const lagom_comm_table* tables;  /* host [ncomm]                                    */
     int32_t ncomm;
+    /* Optional cross-stream dependencies (both nullable = none, the literal Eq. 1).  The overlap
+     * patterns of Sec. 2.1 have them: an FSDP layer's GEMM needs its all-gathered weights, a
+     * pipelined TP batch's all-reduce needs that batch's GEMM.                                  */
+    const int32_t* comp_after_comm;  /* host [ncomp]: communication that must have ended before
+                                        computation i starts, or -1                              */
+    const int32_t* comm_after_comp;  /* host [ncomm]: computation that must have ended before
+                                        communication j starts, or -1                            */
 } lagom_model;
 typedef struct {
     double X_us, Y_us, Z_us;

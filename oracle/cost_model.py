@@ -20,7 +20,14 @@ Readings taken where the text leaves a choice:
   counts the waves issued under j.  With a single communication covering the whole
   computation this is exactly Eq. 4-6 as printed.
 * The last, partial wave costs a full f_ij (Eq. 6 is used literally).
-* There are no cross-stream dependencies (Eq. 1 has none).
+* Eq. 1 has no cross-stream dependencies, and none are assumed by default.  The overlap
+  patterns of Sec. 2.1 do have them (FSDP: a layer's GEMM needs its all-gathered weights;
+  TP with batch pipelining: a batch's all-reduce needs that batch's GEMM), so they can be
+  given: computation i may name a communication that must have ended before it starts and
+  communication j a computation likewise.  Each stream is then still serial, an operator
+  starts at the later of its stream being free and its dependency having ended, the wave
+  stepping is unchanged, and the makespan is the later of the two stream ends (without
+  dependencies that is max(X, Y) again).
 
 Units: time in microseconds, bandwidth in bytes per microsecond, D_i in bytes.
 """
@@ -75,8 +82,14 @@ def wave_time(theta: float, lam: int, nc: int, tb: int, d_bytes: float, bw_peak:
     return theta + (cap * d_bytes) / (bw_peak - v)
 
 
-def predict(model: Model, cfgs: Sequence[Cfg]) -> Prediction:
-    """Eq. 1 over Eq. 4-6 for the whole overlap group."""
+def predict(model: Model, cfgs: Sequence[Cfg], comp_after_comm=None, comm_after_comp=None) -> Prediction:
+    """Eq. 1 over Eq. 4-6 for the whole overlap group.
+
+    comp_after_comm[i] = j (or -1): computation i starts only after communication j has ended;
+    comm_after_comp[j] = i (or -1): communication j starts only after computation i has ended.
+    """
+    if comp_after_comm is not None or comm_after_comp is not None:
+        return _predict_dependent(model, cfgs, comp_after_comm, comm_after_comp)
     N = len(model.tables)
     if len(cfgs) != N:
         raise ValueError("one configuration per communication")
@@ -133,3 +146,79 @@ def predict(model: Model, cfgs: Sequence[Cfg]) -> Prediction:
     for yi in y_all:
         Y = Y + yi
     return Prediction(x=x, y=y_all, g=g_all, X=X, Y=Y, Z=max(X, Y))
+
+
+def _predict_dependent(model: Model, cfgs: Sequence[Cfg], comp_after_comm, comm_after_comp) -> Prediction:
+    N, M = len(model.tables), len(model.comps)
+    free = predict(model, cfgs)                       # validates the inputs; x_j do not depend on the timeline
+    x = free.x
+    nc = [int(c[0]) for c in cfgs]
+    v = [model.tables[j][(int(c[0]), int(c[1]), int(c[2]))][1] for j, c in enumerate(cfgs)]
+    cac = list(comp_after_comm) if comp_after_comm is not None else [-1] * M
+    cap_ = list(comm_after_comp) if comm_after_comp is not None else [-1] * N
+    if len(cac) != M or len(cap_) != N or any(not -1 <= d < N for d in cac) or any(not -1 <= d < M for d in cap_):
+        raise ValueError("bad dependency arrays")
+    comm_start, comm_end, comp_end = [None] * N, [None] * N, [None] * M
+    y_all, g_all = [0.0] * M, [[0] * (N + 1) for _ in range(M)]
+    j_next, i_next = 0, 0
+    tc, ty = 0.0, 0.0                                 # when each stream becomes free
+    # state of the computation in progress
+    running, rem, t0, f = False, 0, 0.0, [0.0] * (N + 1)
+    while j_next < N or i_next < M:
+        progressed = False
+        # start every communication whose turn and dependency have come
+        while j_next < N and (cap_[j_next] < 0 or comp_end[cap_[j_next]] is not None):
+            dep = cap_[j_next]
+            start = tc if dep < 0 else max(tc, comp_end[dep])
+            comm_start[j_next], comm_end[j_next] = start, start + x[j_next]
+            tc = comm_end[j_next]
+            j_next += 1
+            progressed = True
+        if i_next < M:
+            comp = model.comps[i_next]
+            if not running:
+                dep = cac[i_next]
+                if dep < 0 or comm_end[dep] is not None:
+                    t0 = ty if dep < 0 else max(ty, comm_end[dep])
+                    running, rem, f = True, comp.mu, [0.0] * (N + 1)
+                    progressed = True
+            if running:
+                g = g_all[i_next]
+                y = 0.0
+                for s in range(N + 1):
+                    if g[s] > 0:
+                        y = y + f[s] * g[s]
+                if rem > 0:
+                    t = t0 + y
+                    slot = N
+                    for j in range(N):
+                        if comm_start[j] is not None and comm_start[j] <= t < comm_end[j]:
+                            slot = j
+                            break
+                    if slot < N:
+                        cap = (model.lam - nc[slot]) * comp.tb
+                        f[slot] = wave_time(comp.theta, model.lam, nc[slot], comp.tb, comp.d_bytes, model.bw_peak, v[slot])
+                    else:
+                        cap = model.lam * comp.tb
+                        f[slot] = wave_time(comp.theta, model.lam, 0, comp.tb, comp.d_bytes, model.bw_peak, 0.0)
+                    g[slot] += 1
+                    rem -= min(rem, cap)
+                    progressed = True
+                else:
+                    y_all[i_next] = y
+                    comp_end[i_next] = t0 + y
+                    ty = comp_end[i_next]
+                    running = False
+                    i_next += 1
+                    progressed = True
+        if not progressed:
+            raise ValueError("the dependencies form a cycle")
+    X = 0.0
+    for xj in x:
+        X = X + xj
+    Y = 0.0
+    for yi in y_all:
+        Y = Y + yi
+    end_comm = tc if N else 0.0
+    end_comp = ty if M else 0.0
+    return Prediction(x=x, y=y_all, g=g_all, X=X, Y=Y, Z=max(end_comm, end_comp))

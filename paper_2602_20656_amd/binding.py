@@ -49,12 +49,13 @@ class lagom_gemm_geometry(C.Structure):
 
 class lagom_comm_desc(C.Structure):
     _fields_ = [("op", C.c_int32), ("dtype", C.c_int32), ("srcs", C.POINTER(C.c_void_p)), ("nsrc", C.c_int32),
-                ("dsts", C.POINTER(C.c_void_p)), ("ndst", C.c_int32), ("count", C.c_int64), ("comm_id", C.c_int32)]
+                ("dsts", C.POINTER(C.c_void_p)), ("ndst", C.c_int32), ("count", C.c_int64), ("comm_id", C.c_int32),
+                ("after_comp", C.c_int32)]
 
 
 class lagom_gemm_desc(C.Structure):
     _fields_ = [("A", C.c_void_p), ("B", C.c_void_p), ("C", C.c_void_p), ("M", C.c_int64), ("N", C.c_int64),
-                ("K", C.c_int64), ("b_is_nk", C.c_int32), ("out_dtype", C.c_int32)]
+                ("K", C.c_int64), ("b_is_nk", C.c_int32), ("out_dtype", C.c_int32), ("after_comm_id", C.c_int32)]
 
 
 class lagom_timing(C.Structure):
@@ -82,7 +83,8 @@ class lagom_comp_model(C.Structure):
 
 class lagom_model(C.Structure):
     _fields_ = [("lambda_", C.c_int32), ("bw_peak", C.c_double), ("comps", C.POINTER(lagom_comp_model)),
-                ("ncomp", C.c_int32), ("tables", C.POINTER(lagom_comm_table)), ("ncomm", C.c_int32)]
+                ("ncomp", C.c_int32), ("tables", C.POINTER(lagom_comm_table)), ("ncomm", C.c_int32),
+                ("comp_after_comm", C.POINTER(C.c_int32)), ("comm_after_comp", C.POINTER(C.c_int32))]
 
 
 class lagom_pred(C.Structure):
@@ -217,6 +219,7 @@ class CommLaunch:
     dsts: Sequence
     count: int
     comm_id: int = 0
+    after_comp: int = -1        # computation that must have finished before this launch starts
 
 
 @dataclass
@@ -229,6 +232,7 @@ class GemmDesc:
     K: int
     b_is_nk: bool = True
     out_dtype: int = LAGOM_BF16
+    after_comm_id: int = -1     # communication that must have finished before this GEMM starts
 
 
 @dataclass
@@ -251,11 +255,12 @@ class _Group:
             s, d = _ptr_array(l.srcs), _ptr_array(l.dsts)
             self.keep += [s, d]
             self.L[i] = lagom_comm_desc(l.op, l.dtype, C.cast(s, C.POINTER(C.c_void_p)), len(l.srcs),
-                                        C.cast(d, C.POINTER(C.c_void_p)), len(l.dsts), int(l.count), int(l.comm_id))
+                                        C.cast(d, C.POINTER(C.c_void_p)), len(l.dsts), int(l.count), int(l.comm_id),
+                                        int(l.after_comp))
         self.G = (lagom_gemm_desc * max(self.ncomp, 1))()
         for i, g in enumerate(comps):
             self.G[i] = lagom_gemm_desc(_ptr(g.A), _ptr(g.B), _ptr(g.C), int(g.M), int(g.N), int(g.K),
-                                        1 if g.b_is_nk else 0, int(g.out_dtype))
+                                        1 if g.b_is_nk else 0, int(g.out_dtype), int(g.after_comm_id))
 
 
 def lagom_overlap_run(launches: Sequence[CommLaunch], cfgs: Sequence[CfgLike], comps: Sequence[GemmDesc],
@@ -307,6 +312,8 @@ class Model:
     bw_peak: float                                    # bytes per microsecond
     comps: List[CompModel]
     tables: List[dict] = field(default_factory=list)  # per communication: (nc, nt, chunk) -> (x_us, v)
+    comp_after_comm: Optional[Sequence[int]] = None   # per computation: communication it waits for, or -1
+    comm_after_comp: Optional[Sequence[int]] = None   # per communication: computation it waits for, or -1
 
 
 @dataclass
@@ -332,8 +339,13 @@ class _CModel:
                 arr[e] = lagom_table_entry(lagom_cfg(int(k[0]), int(k[1]), int(k[2])), float(x), float(v))
             self.entry_arrays.append(arr)
             self.tables[j] = lagom_comm_table(C.cast(arr, C.POINTER(lagom_table_entry)), len(t))
+        self.cac = (C.c_int32 * max(len(m.comps), 1))(*[int(v) for v in m.comp_after_comm]) if m.comp_after_comm is not None else None
+        self.cap = (C.c_int32 * max(len(m.tables), 1))(*[int(v) for v in m.comm_after_comp]) if m.comm_after_comp is not None else None
+        null = C.POINTER(C.c_int32)()
         self.c = lagom_model(int(m.lam), float(m.bw_peak), C.cast(self.comps, C.POINTER(lagom_comp_model)), len(m.comps),
-                             C.cast(self.tables, C.POINTER(lagom_comm_table)), len(m.tables))
+                             C.cast(self.tables, C.POINTER(lagom_comm_table)), len(m.tables),
+                             C.cast(self.cac, C.POINTER(C.c_int32)) if self.cac is not None else null,
+                             C.cast(self.cap, C.POINTER(C.c_int32)) if self.cap is not None else null)
 
 
 def lagom_cost_model(model: Model, cfgs: Sequence[CfgLike]) -> Pred:

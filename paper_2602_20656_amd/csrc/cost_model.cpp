@@ -48,49 +48,133 @@ extern "C" int lagom_cost_model(const lagom_model* m, const lagom_cfg* cfgs, int
         if (!(c[j].x >= 0.0) || !std::isfinite(c[j].x))
             return lagom::fail(LAGOM_EINVAL, "communication %d: x must be finite and non-negative", j);
     }
-    // communication j is active on [T[j], T[j+1])
-    std::vector<double> T(N + 1, 0.0);
-    for (int j = 0; j < N; ++j) T[j + 1] = T[j] + c[j].x;
-    const double X = T[N];
-
-    std::vector<double> f(N + 1);
-    std::vector<int32_t> g(N + 1);
-    double t0 = 0.0, Y = 0.0;
     for (int i = 0; i < m->ncomp; ++i) {
         const lagom_comp_model& cp = m->comps[i];
         if (cp.mu < 0 || cp.tb < 1 || !(cp.d_bytes >= 0.0) || !std::isfinite(cp.theta_us))
             return lagom::fail(LAGOM_EINVAL, "computation %d: bad description", i);
-        for (int s = 0; s <= N; ++s) { f[s] = 0.0; g[s] = 0; }
-        int64_t rem = cp.mu;
-        double t = t0, y = 0.0;
-        while (rem > 0) {
-            int slot = N;
-            for (int j = 0; j < N; ++j)
-                if (t < T[j + 1]) { slot = j; break; }
-            int64_t cap;
-            if (slot < N) {
-                cap = (int64_t)(m->lambda - c[slot].nc) * cp.tb;
-                f[slot] = wave_time(cp.theta_us, cap, cp.d_bytes, m->bw_peak, c[slot].v);
-            } else {
-                cap = (int64_t)m->lambda * cp.tb;
-                f[slot] = wave_time(cp.theta_us, cap, cp.d_bytes, m->bw_peak, 0.0);
+    }
+    const int M = m->ncomp;
+    double X = 0.0, Y = 0.0, Z = 0.0;
+    for (int j = 0; j < N; ++j) X = X + c[j].x;
+    std::vector<double> f(N + 1);
+    std::vector<int32_t> g(N + 1);
+
+    if (!m->comp_after_comm && !m->comm_after_comp) {
+        // communication j is active on [T[j], T[j+1])
+        std::vector<double> T(N + 1, 0.0);
+        for (int j = 0; j < N; ++j) T[j + 1] = T[j] + c[j].x;
+        double t0 = 0.0;
+        for (int i = 0; i < M; ++i) {
+            const lagom_comp_model& cp = m->comps[i];
+            for (int s = 0; s <= N; ++s) { f[s] = 0.0; g[s] = 0; }
+            int64_t rem = cp.mu;
+            double t = t0, y = 0.0;
+            while (rem > 0) {
+                int slot = N;
+                for (int j = 0; j < N; ++j)
+                    if (t < T[j + 1]) { slot = j; break; }
+                int64_t cap;
+                if (slot < N) {
+                    cap = (int64_t)(m->lambda - c[slot].nc) * cp.tb;
+                    f[slot] = wave_time(cp.theta_us, cap, cp.d_bytes, m->bw_peak, c[slot].v);
+                } else {
+                    cap = (int64_t)m->lambda * cp.tb;
+                    f[slot] = wave_time(cp.theta_us, cap, cp.d_bytes, m->bw_peak, 0.0);
+                }
+                g[slot] += 1;
+                rem -= rem < cap ? rem : cap;
+                y = 0.0;
+                for (int s = 0; s <= N; ++s)            // Eq. 4, terms in ascending j
+                    if (g[s] > 0) y = y + f[s] * (double)g[s];
+                t = t0 + y;
             }
-            g[slot] += 1;
-            rem -= rem < cap ? rem : cap;
-            y = 0.0;
-            for (int s = 0; s <= N; ++s)            // Eq. 4, terms in ascending j
-                if (g[s] > 0) y = y + f[s] * (double)g[s];
-            t = t0 + y;
+            if (out->y_us) out->y_us[i] = y;
+            if (out->g) for (int s = 0; s <= N; ++s) out->g[(int64_t)i * (N + 1) + s] = g[s];
+            t0 = t0 + y;
+            Y = Y + y;
         }
-        if (out->y_us) out->y_us[i] = y;
-        if (out->g) for (int s = 0; s <= N; ++s) out->g[(int64_t)i * (N + 1) + s] = g[s];
-        t0 = t0 + y;
-        Y = Y + y;
+        Z = T[N] > Y ? T[N] : Y;
+    } else {
+        // dependent chains: both streams advance together; a communication is placed as soon as its
+        // predecessor on the stream and the computation it waits for have ended, a computation is
+        // stepped wave by wave against the communications placed so far
+        std::vector<int> cac(M, -1), cap_dep(N, -1);
+        for (int i = 0; i < M && m->comp_after_comm; ++i) cac[i] = m->comp_after_comm[i];
+        for (int j = 0; j < N && m->comm_after_comp; ++j) cap_dep[j] = m->comm_after_comp[j];
+        for (int i = 0; i < M; ++i) if (cac[i] < -1 || cac[i] >= N) return lagom::fail(LAGOM_EINVAL, "computation %d waits for communication %d", i, cac[i]);
+        for (int j = 0; j < N; ++j) if (cap_dep[j] < -1 || cap_dep[j] >= M) return lagom::fail(LAGOM_EINVAL, "communication %d waits for computation %d", j, cap_dep[j]);
+        std::vector<double> cs(N, 0.0), ce(N, 0.0), pe(M, 0.0), ys(M, 0.0);
+        std::vector<char> c_known(N, 0), p_known(M, 0);
+        std::vector<int32_t> gall((size_t)M * (N + 1), 0);
+        int jn = 0, in = 0;
+        double tc = 0.0, ty = 0.0, t0 = 0.0;
+        bool running = false;
+        int64_t rem = 0;
+        while (jn < N || in < M) {
+            bool progressed = false;
+            while (jn < N && (cap_dep[jn] < 0 || p_known[cap_dep[jn]])) {
+                const int dep = cap_dep[jn];
+                const double start = dep < 0 ? tc : (tc > pe[dep] ? tc : pe[dep]);
+                cs[jn] = start; ce[jn] = start + c[jn].x; c_known[jn] = 1;
+                tc = ce[jn];
+                ++jn;
+                progressed = true;
+            }
+            if (in < M) {
+                const lagom_comp_model& cp = m->comps[in];
+                if (!running) {
+                    const int dep = cac[in];
+                    if (dep < 0 || c_known[dep]) {
+                        t0 = dep < 0 ? ty : (ty > ce[dep] ? ty : ce[dep]);
+                        running = true; rem = cp.mu;
+                        for (int s = 0; s <= N; ++s) f[s] = 0.0;
+                        progressed = true;
+                    }
+                }
+                if (running) {
+                    int32_t* gi = &gall[(size_t)in * (N + 1)];
+                    double y = 0.0;
+                    for (int s = 0; s <= N; ++s)
+                        if (gi[s] > 0) y = y + f[s] * (double)gi[s];
+                    if (rem > 0) {
+                        const double t = t0 + y;
+                        int slot = N;
+                        for (int j = 0; j < N; ++j)
+                            if (c_known[j] && cs[j] <= t && t < ce[j]) { slot = j; break; }
+                        int64_t cap;
+                        if (slot < N) {
+                            cap = (int64_t)(m->lambda - c[slot].nc) * cp.tb;
+                            f[slot] = wave_time(cp.theta_us, cap, cp.d_bytes, m->bw_peak, c[slot].v);
+                        } else {
+                            cap = (int64_t)m->lambda * cp.tb;
+                            f[slot] = wave_time(cp.theta_us, cap, cp.d_bytes, m->bw_peak, 0.0);
+                        }
+                        gi[slot] += 1;
+                        rem -= rem < cap ? rem : cap;
+                    } else {
+                        ys[in] = y;
+                        pe[in] = t0 + y; p_known[in] = 1;
+                        ty = pe[in];
+                        running = false;
+                        ++in;
+                    }
+                    progressed = true;
+                }
+            }
+            if (!progressed) return lagom::fail(LAGOM_EINVAL, "the dependencies form a cycle");
+        }
+        for (int i = 0; i < M; ++i) {
+            Y = Y + ys[i];
+            if (out->y_us) out->y_us[i] = ys[i];
+        }
+        if (out->g) for (size_t k = 0; k < gall.size(); ++k) out->g[k] = gall[k];
+        const double end_comm = N ? tc : 0.0, end_comp = M ? ty : 0.0;
+        Z = end_comm > end_comp ? end_comm : end_comp;
     }
     if (out->x_us) for (int j = 0; j < N; ++j) out->x_us[j] = c[j].x;
     out->X_us = X;
     out->Y_us = Y;
-    out->Z_us = X > Y ? X : Y;
+    out->Z_us = Z;
     return LAGOM_OK;
 }
 

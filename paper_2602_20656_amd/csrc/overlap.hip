@@ -72,12 +72,15 @@ int validate(const lagom_comm_desc* L, int nlaunch, const lagom_cfg* cfgs, int n
             seen[d.comm_id] = 1;
             prev = d.comm_id;
         }
+        if (d.after_comp < -1 || d.after_comp >= ncomp) return lagom::fail(LAGOM_EINVAL, "launch %d: after_comp %d outside -1..%d", i, d.after_comp, ncomp - 1);
         if (int rc = lagom::check_comm_args(d.op, d.dtype, d.srcs, d.nsrc, d.dsts, d.ndst, d.count)) return rc;
     }
     for (int j = 0; j < ncfg; ++j)
         if (int rc = lagom::check_cfg(&cfgs[j])) return rc;
     for (int i = 0; i < ncomp; ++i) {
         const lagom_gemm_desc& g = G[i];
+        if (g.after_comm_id < -1 || g.after_comm_id >= ncfg || (g.after_comm_id >= 0 && !seen[g.after_comm_id]))
+            return lagom::fail(LAGOM_EINVAL, "computation %d: after_comm_id %d names no communication of the group", i, g.after_comm_id);
         if (int rc = lagom::check_gemm_args(g.A, g.B, g.C, g.M, g.N, g.K, g.out_dtype)) return rc;
     }
     return LAGOM_OK;
@@ -95,27 +98,33 @@ extern "C" int lagom_overlap_run(const lagom_comm_desc* launches, int nlaunch, c
     hipStream_t sa = static_cast<hipStream_t>(comm_stream), sb = static_cast<hipStream_t>(comp_stream);
     if (run_comm && run_comp && sa == sb) return lagom::fail(LAGOM_EINVAL, "co-run needs two distinct streams");
 
-    // group boundaries on the communication stream: one event before the first launch of every
-    // communication and one after the last launch
-    std::vector<int> group_first;     // launch index where a new comm_id starts
-    std::vector<int> group_id;
+    // launches of one communication form a group; every group and every GEMM gets a start and an end event
+    std::vector<int> group_first, group_last, group_id, group_of(ncfg > 0 ? ncfg : 1, -1);
     if (run_comm)
-        for (int i = 0; i < nlaunch; ++i)
-            if (i == 0 || launches[i].comm_id != launches[i - 1].comm_id) { group_first.push_back(i); group_id.push_back(launches[i].comm_id); }
+        for (int i = 0; i < nlaunch; ++i) {
+            if (i == 0 || launches[i].comm_id != launches[i - 1].comm_id) {
+                group_of[launches[i].comm_id] = (int)group_first.size();
+                group_first.push_back(i); group_last.push_back(i); group_id.push_back(launches[i].comm_id);
+            } else {
+                group_last.back() = i;
+            }
+        }
     const int ngroups = (int)group_first.size();
-    const int n_ev_a = run_comm ? ngroups + 1 : 0;
-    const int n_ev_b = run_comp ? ncomp + 1 : 0;
+    const int ncomp_run = run_comp ? ncomp : 0;
+    const bool deps = run_comm && run_comp;        // dependencies only matter when both streams run
     Events E;
-    if (int rc = E.make(1 + n_ev_a + n_ev_b)) return rc;
+    if (int rc = E.make(1 + 2 * ngroups + 2 * ncomp_run)) return rc;
     hipEvent_t gate = E.ev[0];
-    hipEvent_t* ea = E.ev.data() + 1;
-    hipEvent_t* eb = E.ev.data() + 1 + n_ev_a;
+    hipEvent_t* ga_start = E.ev.data() + 1;
+    hipEvent_t* ga_end = ga_start + ngroups;
+    hipEvent_t* gb_start = ga_end + ngroups;
+    hipEvent_t* gb_end = gb_start + ncomp_run;
 
     int dev = 0, clock_khz = 100000;
     HIP_TRY(hipGetDevice(&dev));
     if (hipDeviceGetAttribute(&clock_khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || clock_khz <= 0) clock_khz = 100000;
     // long enough for the host to enqueue everything: ~12 us per queued item plus a floor
-    const int items = (run_comm ? nlaunch + n_ev_a : 0) + (run_comp ? ncomp + n_ev_b : 0) + 4;
+    const int items = (run_comm ? nlaunch + 2 * ngroups : 0) + 3 * ncomp_run + 4;
     const double delay_us = 60.0 + 12.0 * items;
     const long long ticks = (long long)(delay_us * clock_khz / 1000.0);
     const int max_iter = 1 << 14;
@@ -123,29 +132,53 @@ extern "C" int lagom_overlap_run(const lagom_comm_desc* launches, int nlaunch, c
     std::vector<std::vector<double>> xs(ncfg), ys(ncomp);
     std::vector<double> Xs, Ys, Zs;
     hipStream_t gate_stream = run_comm ? sa : sb;
+    std::vector<char> group_done(ngroups > 0 ? ngroups : 1), comp_done(ncomp > 0 ? ncomp : 1);
 
     for (int it = 0; it < warmup + iters; ++it) {
         hipLaunchKernelGGL(gate_delay_kernel, dim3(1), dim3(64), 0, gate_stream, ticks, max_iter);
         HIP_TRY(hipGetLastError());
         HIP_TRY(hipEventRecord(gate, gate_stream));
         if (run_comm && run_comp) HIP_TRY(hipStreamWaitEvent(sb, gate, 0));
-        if (run_comm) {
-            int g = 0;
-            for (int i = 0; i < nlaunch; ++i) {
-                if (g < ngroups && group_first[g] == i) { HIP_TRY(hipEventRecord(ea[g], sa)); ++g; }
-                const lagom_comm_desc& d = launches[i];
-                if (int rc = lagom_comm_kernel((lagom_op)d.op, (lagom_dtype)d.dtype, d.srcs, d.nsrc, d.dsts, d.ndst,
-                                               d.count, &cfgs[d.comm_id], sa)) return rc;
+        // The two enqueue orders are merged so that an awaited event has always been recorded first.
+        std::fill(group_done.begin(), group_done.end(), 0);
+        std::fill(comp_done.begin(), comp_done.end(), 0);
+        int li = 0, ci = 0;
+        const int nl = run_comm ? nlaunch : 0;
+        while (li < nl || ci < ncomp_run) {
+            bool progressed = false;
+            if (li < nl) {
+                const lagom_comm_desc& d = launches[li];
+                const int dep = deps ? d.after_comp : -1;
+                if (dep < 0 || comp_done[dep]) {
+                    const int g = group_of[d.comm_id];
+                    if (dep >= 0) HIP_TRY(hipStreamWaitEvent(sa, gb_end[dep], 0));
+                    if (li == group_first[g]) HIP_TRY(hipEventRecord(ga_start[g], sa));
+                    if (int rc = lagom_comm_kernel((lagom_op)d.op, (lagom_dtype)d.dtype, d.srcs, d.nsrc, d.dsts, d.ndst,
+                                                   d.count, &cfgs[d.comm_id], sa)) return rc;
+                    if (li == group_last[g]) { HIP_TRY(hipEventRecord(ga_end[g], sa)); group_done[g] = 1; }
+                    ++li;
+                    progressed = true;
+                }
             }
-            HIP_TRY(hipEventRecord(ea[ngroups], sa));
-        }
-        if (run_comp) {
-            for (int i = 0; i < ncomp; ++i) {
-                HIP_TRY(hipEventRecord(eb[i], sb));
-                const lagom_gemm_desc& c = comps[i];
-                if (int rc = lagom_gemm(c.A, c.B, c.C, c.M, c.N, c.K, c.b_is_nk, (lagom_dtype)c.out_dtype, sb)) return rc;
+            if (ci < ncomp_run) {
+                const lagom_gemm_desc& c = comps[ci];
+                const int dep = deps ? c.after_comm_id : -1;
+                if (dep < 0 || group_done[group_of[dep]]) {
+                    if (dep >= 0) HIP_TRY(hipStreamWaitEvent(sb, ga_end[group_of[dep]], 0));
+                    HIP_TRY(hipEventRecord(gb_start[ci], sb));
+                    if (int rc = lagom_gemm(c.A, c.B, c.C, c.M, c.N, c.K, c.b_is_nk, (lagom_dtype)c.out_dtype, sb)) return rc;
+                    HIP_TRY(hipEventRecord(gb_end[ci], sb));
+                    comp_done[ci] = 1;
+                    ++ci;
+                    progressed = true;
+                }
             }
-            HIP_TRY(hipEventRecord(eb[ncomp], sb));
+            if (!progressed) {
+                // nothing of this repetition may stay queued behind the gate: drain, then report
+                (void)hipStreamSynchronize(sa);
+                (void)hipStreamSynchronize(sb);
+                return lagom::fail(LAGOM_EINVAL, "the cross-stream dependencies form a cycle (launch %d, computation %d)", li, ci);
+            }
         }
         if (run_comm) HIP_TRY(hipStreamSynchronize(sa));
         if (run_comp) HIP_TRY(hipStreamSynchronize(sb));
@@ -155,19 +188,19 @@ extern "C" int lagom_overlap_run(const lagom_comm_desc* launches, int nlaunch, c
         double X = 0.0, Y = 0.0, endA = 0.0, endB = 0.0;
         if (run_comm) {
             for (int g = 0; g < ngroups; ++g) {
-                HIP_TRY(hipEventElapsedTime(&ms, ea[g], ea[g + 1]));
+                HIP_TRY(hipEventElapsedTime(&ms, ga_start[g], ga_end[g]));
                 xs[group_id[g]].push_back((double)ms * 1000.0);
             }
-            HIP_TRY(hipEventElapsedTime(&ms, ea[0], ea[ngroups])); X = (double)ms * 1000.0;
-            HIP_TRY(hipEventElapsedTime(&ms, gate, ea[ngroups])); endA = (double)ms * 1000.0;
+            HIP_TRY(hipEventElapsedTime(&ms, ga_start[0], ga_end[ngroups - 1])); X = (double)ms * 1000.0;
+            HIP_TRY(hipEventElapsedTime(&ms, gate, ga_end[ngroups - 1])); endA = (double)ms * 1000.0;
         }
         if (run_comp) {
             for (int i = 0; i < ncomp; ++i) {
-                HIP_TRY(hipEventElapsedTime(&ms, eb[i], eb[i + 1]));
+                HIP_TRY(hipEventElapsedTime(&ms, gb_start[i], gb_end[i]));
                 ys[i].push_back((double)ms * 1000.0);
             }
-            HIP_TRY(hipEventElapsedTime(&ms, eb[0], eb[ncomp])); Y = (double)ms * 1000.0;
-            HIP_TRY(hipEventElapsedTime(&ms, gate, eb[ncomp])); endB = (double)ms * 1000.0;
+            HIP_TRY(hipEventElapsedTime(&ms, gb_start[0], gb_end[ncomp - 1])); Y = (double)ms * 1000.0;
+            HIP_TRY(hipEventElapsedTime(&ms, gate, gb_end[ncomp - 1])); endB = (double)ms * 1000.0;
         }
         Xs.push_back(X); Ys.push_back(Y); Zs.push_back(endA > endB ? endA : endB);
     }

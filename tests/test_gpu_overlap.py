@@ -72,3 +72,41 @@ def test_measured_priority_search_stays_on_the_ladder_and_is_linear(tiny):
     assert r.Z > 0
     torch.cuda.synchronize()
     assert same_bits(host(tiny["dout"], np.float32), oc.reduce_copy([tiny["a"], tiny["b"]], oc.F32)[0])
+
+
+def test_cross_stream_dependencies_are_honoured():
+    """FSDP-like: the GEMM multiplies by the weight an all-gather is still writing, so it must wait for it;
+    TP-like: a reduce-copy consumes the GEMM's output, so it must wait for the GEMM."""
+    M = N = K = 512
+    shards = [inputs.normal_bf16(300 + p, N * K // 8, scale=0.05) for p in range(8)]
+    A = inputs.normal_bf16(2, (M, K))
+    other = inputs.normal_bf16(7, M * N)
+    d_sh = [dev(s) for s in shards]
+    dW = dev(np.zeros(N * K, np.uint16))                       # zeros until the gather has run
+    dA, dC = dev(A), dev(np.zeros(M * N, np.uint16))
+    d_other, d_sum = dev(other), dev(np.zeros(M * N, np.uint16))
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    launches = [lg.CommLaunch(lg.LAGOM_GATHER_COPY, lg.LAGOM_BF16, d_sh, [dW], N * K // 8, 0),
+                lg.CommLaunch(lg.LAGOM_REDUCE_COPY, lg.LAGOM_BF16, [dC, d_other], [d_sum], M * N, 1, after_comp=0)]
+    comps = [lg.GemmDesc(dA, dW, dC, M, N, K, True, lg.LAGOM_BF16, after_comm_id=0)]
+    cfgs = [(1, 64, 16384), (2, 256, 65536)]                   # one slow channel: the gather outlasts an unsynchronised GEMM
+    t = lg.lagom_overlap_run(launches, cfgs, comps, s1, s2, 1, 3, lg.LAGOM_CORUN)
+    torch.cuda.synchronize()
+    W = oc.gather_copy(shards)[0].reshape(N, K)
+    assert same_bits(host(dW, np.uint16), W.reshape(-1))
+    ref = og.gemm_f64(A, W, True)
+    got_bits = host(dC, np.uint16)
+    e_max, e_fro = og.rel_errors(oc.bf16_to_f32(got_bits).reshape(M, N), ref)
+    assert e_max <= 2e-2 and e_fro <= 2e-2, "the GEMM did not wait for its weights"
+    want_sum = oc.reduce_copy([got_bits, other], oc.BF16)[0]   # exact on the bits the GEMM produced
+    assert same_bits(host(d_sum, np.uint16), want_sum), "the reduce-copy did not wait for the GEMM"
+    # the chain is serial: gather -> GEMM -> reduce, so the makespan holds all three
+    assert t.Z_us >= 0.98 * (t.x_us[0] + t.y_us[0] + t.x_us[1])
+    # a cycle is refused and leaves nothing queued
+    cyc_l = [lg.CommLaunch(lg.LAGOM_GATHER_COPY, lg.LAGOM_BF16, d_sh, [dW], N * K // 8, 0, after_comp=0)]
+    with pytest.raises(lg.LagomError) as e:
+        lg.lagom_overlap_run(cyc_l, cfgs[:1], comps, s1, s2, 0, 1, lg.LAGOM_CORUN)
+    assert e.value.code == lg.LAGOM_EINVAL
+    torch.cuda.synchronize()
+    # alone modes ignore dependencies
+    assert lg.lagom_overlap_run(cyc_l, cfgs[:1], comps, s1, s2, 0, 2, lg.LAGOM_ALONE_COMP).Y_us > 0

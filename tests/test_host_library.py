@@ -244,3 +244,26 @@ def test_comm_optimal_mode_equals_oracle_coordinate_descent():
         ro = osr.coordinate_descent(so, profile)
         rl = lg.lagom_tune(sl, profile, lg.LAGOM_COMM_OPTIMAL)
         assert rl.cfgs == ro.cfgs and rl.calls == ro.calls and (rl.X, rl.Y, rl.Z) == (ro.X, ro.Y, ro.Z)
+
+
+def test_dependent_cost_model_equals_oracle_bit_for_bit(golden_dir):
+    rng = np.random.default_rng(31)
+    for _ in range(300):
+        N, M = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+        mo, ml, cfgs = _random_model(rng, N, M)
+        cac = [int(rng.integers(-1, min(i + 1, N))) for i in range(M)]
+        cap = [int(rng.integers(-1, min(j, M))) if j > 0 else -1 for j in range(N)]
+        ml.comp_after_comm, ml.comm_after_comp = cac, cap
+        po, pl = ocm.predict(mo, cfgs, cac, cap), lg.lagom_cost_model(ml, cfgs)
+        assert pl.y_us == po.y and pl.g == po.g and (pl.X_us, pl.Y_us, pl.Z_us) == (po.X, po.Y, po.Z)
+    fx = json.load(open(os.path.join(golden_dir, "cost_model_worked.json")))
+    for case in fx["dependent_cases"]:
+        tables = [{(c["nc"], 256, 65536): (c["x"], c["v"])} for c in case["comms"]]
+        model = lg.Model(fx["lambda"], fx["bw_peak"], [lg.CompModel(c["mu"], c["tb"], c["d_bytes"], c["theta"]) for c in case["comps"]],
+                         tables, case["comp_after_comm"], case["comm_after_comp"])
+        p = lg.lagom_cost_model(model, [(c["nc"], 256, 65536) for c in case["comms"]])
+        assert p.y_us == case["y"] and p.g == case["g"] and (p.X_us, p.Y_us, p.Z_us) == (case["X"], case["Y"], case["Z"])
+    cyc = lg.Model(8, 100.0, [lg.CompModel(10, 1, 1.0, 0.5)], [{(2, 64, 64): (5.0, 1.0)}], [0], [0])
+    with pytest.raises(lg.LagomError) as e:
+        lg.lagom_cost_model(cyc, [(2, 64, 64)])
+    assert e.value.code == lg.LAGOM_EINVAL

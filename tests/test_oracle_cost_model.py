@@ -93,3 +93,42 @@ def test_rejects_out_of_range_inputs():
         cm.predict(cm.Model(8, 100.0, comps, [{(2, 64, 64): (1.0, 100.0)}]), [(2, 64, 64)])   # V >= B
     with pytest.raises(KeyError):
         cm.predict(cm.Model(8, 100.0, comps, [{(2, 64, 64): (1.0, 1.0)}]), [(4, 64, 64)])     # not in the table
+
+
+# ------------------------------------------------------------ dependent chains (Sec. 2.1 patterns)
+def test_dependent_chains_hand_worked_fixture(golden_dir):
+    fx = json.load(open(os.path.join(golden_dir, "cost_model_worked.json")))
+    for case in fx["dependent_cases"]:
+        model, cfgs = _model(fx["lambda"], fx["bw_peak"], case["comps"], case["comms"])
+        p = cm.predict(model, cfgs, case["comp_after_comm"], case["comm_after_comp"])
+        assert p.y == case["y"] and p.g == case["g"], case["name"]
+        assert (p.X, p.Y, p.Z) == (case["X"], case["Y"], case["Z"]), case["name"]
+
+
+def test_dependencies_that_bind_nothing_change_nothing_and_real_ones_never_shorten_the_makespan():
+    import numpy as np
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        N, M = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+        lam, bw = 64, 1000.0
+        comps = [cm.Comp(int(rng.integers(1, 400)), int(rng.integers(1, 3)), float(rng.uniform(1, 200)), float(rng.uniform(0, 5))) for _ in range(M)]
+        tables = [{(int(rng.choice([1, 4, 16])), 64, 1024): (float(rng.uniform(1, 300)), float(rng.uniform(0, 900)))} for _ in range(N)]
+        model = cm.Model(lam, bw, comps, tables)
+        cfgs = [next(iter(t)) for t in tables]
+        free = cm.predict(model, cfgs)
+        none = cm.predict(model, cfgs, [-1] * M, [-1] * N)
+        assert (none.y, none.g, none.X, none.Y, none.Z) == (free.y, free.g, free.X, free.Y, free.Z)
+        cac = [int(rng.integers(-1, min(i + 1, N))) for i in range(M)]          # comp i may wait for comm <= i
+        cap = [int(rng.integers(-1, min(j, M))) if j > 0 else -1 for j in range(N)]   # comm j may wait for comp < j
+        dep = cm.predict(model, cfgs, cac, cap)
+        assert dep.X == free.X                                   # x_j are table values
+        assert dep.Z >= max(dep.X, dep.Y) - 1e-9                 # waiting only adds idle time
+        assert dep.Z >= min(free.Z, dep.Z)                       # and every wave count is still Eq. 5's
+        for i, comp in enumerate(comps):
+            assert sum(dep.g[i]) >= math.ceil(comp.mu / (lam * comp.tb))
+
+
+def test_dependency_cycle_is_rejected():
+    model = cm.Model(8, 100.0, [cm.Comp(10, 1, 1.0, 0.5)], [{(2, 64, 64): (5.0, 1.0)}])
+    with pytest.raises(ValueError):
+        cm.predict(model, [(2, 64, 64)], [0], [0])       # each waits for the other
