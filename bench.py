@@ -40,7 +40,7 @@ def _up(x):
     return torch.from_numpy(x.view(np.int16) if x.dtype == np.uint16 else x).cuda()
 
 
-def build_workload(name: str):
+def build_workload(name: str, dependent: bool = False):
     """Device buffers + launch descriptors of one of the five synthetic overlap groups."""
     import torch
     from paper_2602_20656_amd import binding as lg, inputs
@@ -95,14 +95,16 @@ def build_workload(name: str):
     A = _up(inputs.normal_bf16(2, (M, K)))
     keep.append(A)
     for i in range(w.ncomp):
-        if name == "fsdp_chain":
-            # GEMM i multiplies by the weight gathered one pair earlier (pair 0 uses its own, pre-filled)
-            B = _up(inputs.normal_bf16(3 + i, (N, K), 0.02))
+        if name == "fsdp_chain" and dependent and i > 0:
+            B = weights[i - 1]          # prefetch: all-gather i-1 assembles the weight of GEMM i while GEMM i-1 runs
+        elif name == "fsdp_chain":
+            B = _up(inputs.normal_bf16(3 + i, (N, K), 0.02))   # literal Eq. 1: no cross-stream dependency
         else:
             B = _up(inputs.normal_bf16(3, (N, K), 0.02 if name != "tiny" else 1.0))
         Cm = torch.zeros((M, N), dtype=torch.int16, device="cuda")
         keep += [B, Cm]
-        comps.append(lg.GemmDesc(A, B, Cm, M, N, K, True, lg.LAGOM_BF16))
+        comps.append(lg.GemmDesc(A, B, Cm, M, N, K, True, lg.LAGOM_BF16,
+                                 after_comm_id=i - 1 if (name == "fsdp_chain" and dependent and i > 0) else -1))
     return w, launches, comps, ncomm, keep
 
 
@@ -183,6 +185,8 @@ def main():
     ap.add_argument("--workload", default="dp_bucket", choices=["tiny", "dp_bucket", "tp_layer", "fsdp_chain", "compute_bound"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep-iters", type=int, default=5)
+    ap.add_argument("--dependent", action="store_true",
+                    help="fsdp_chain only: GEMM i (i > 0) consumes the weight gathered by communication i-1 and waits for it")
     ap.add_argument("--dump", default=None, help="write the sweep table and tuner traces to this JSON file")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -196,7 +200,8 @@ def main():
     torch.cuda.set_device(0)
     s_comm, s_comp = torch.cuda.Stream(), torch.cuda.Stream()
 
-    w, launches, comps, ncomm, keep = build_workload(args.workload)
+    dependent = args.dependent and args.workload == "fsdp_chain"
+    w, launches, comps, ncomm, keep = build_workload(args.workload, dependent)
     nbytes = comm_bytes(launches)
     M, N, K = w.gemm
     flops = 2.0 * M * N * K
@@ -214,7 +219,8 @@ def main():
     g0 = -(-geo.mu // (LAMBDA * geo.tb))
     theta = max(0.0, y_alone / g0 - LAMBDA * geo.tb * geo.d_bytes / bw)
     tables = [{p.cfg: (p.comm_corun_us / ncomm, min(p.v_corun, 0.99 * bw)) for p in sweep} for _ in range(ncomm)]
-    model = lg.Model(LAMBDA, bw, [lg.CompModel(geo.mu, geo.tb, geo.d_bytes, theta) for _ in comps], tables)
+    model = lg.Model(LAMBDA, bw, [lg.CompModel(geo.mu, geo.tb, geo.d_bytes, theta) for _ in comps], tables,
+                     comp_after_comm=[i - 1 for i in range(len(comps))] if dependent else None)
 
     # ---- the search: Alg. 1/2 with measured profiles, and with the model as ProfileTime
     nt_grid = list(w.nt_grid) if len(w.nt_grid) > 1 else [256]
@@ -272,7 +278,7 @@ def main():
         "ms_per_step": wall_ms / args.steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": args.workload, "comm": f"{w.comm.op} {w.comm.dtype} S={w.comm.nsrc} count={w.comm.count} "
+        "config": {"workload": args.workload + ("+dependent" if dependent else ""), "comm": f"{w.comm.op} {w.comm.dtype} S={w.comm.nsrc} count={w.comm.count} "
                    f"launches={len(launches)} comms={ncomm}", "gemm": f"{M}x{N}x{K} bf16 x{len(comps)}",
                    "default_cfg": list(DEFAULT_CFG), "tuned_cfgs": [list(c) for c in tuned.cfgs]},
         "z_tuned_us": t_tuned.Z_us, "z_default_us": t_default.Z_us,
@@ -282,7 +288,7 @@ def main():
         "z_best_swept_us": best_sweep.z_corun_us, "best_swept_cfg": list(best_sweep.cfg),
         "z_model_tuned_us": t_model.Z_us if t_model else None,
         "model_tuned_cfgs": [list(c) for c in tuned_model.cfgs] if tuned_model else None,
-        "model_predicted_z_us": tuned_model.Z if tuned_model else None,
+        "model_predicted_z_us": lg.lagom_cost_model(model, tuned_model.cfgs).Z_us if tuned_model else None,
         "tune_profile_calls": tuned.calls, "tune_seconds": tune_s, "sweep_points": len(points), "sweep_seconds": sweep_s,
         "gemm_alone_us": gemm_us, "gemm_mfma_util": tflops / BF16_PEAK_TFLOPS,
         "gemm_slowdown_default": t_default.Y_us / t_gemm.Y_us, "gemm_slowdown_tuned": t_tuned.Y_us / t_gemm.Y_us,
