@@ -80,6 +80,21 @@ def build_workload(name: str, dependent: bool = False):
             keep += [shards, full]
             weights.append(full)
             launches.append(lg.CommLaunch(lg.LAGOM_GATHER_COPY, dt, shards, [full], w.comm.count, j))
+    elif name == "ep_alltoall":
+        ncomm, P, m, rank = 1, w.comm.nsrc, w.comm.count, 3
+        send = [_up(gen(w.seeds[p], P * m)) for p in range(P)]          # every peer's send buffer: P blocks of m
+        recv = _up(np.zeros(P * m, np_dt))
+        keep += [send, recv]
+        launches.append(lg.CommLaunch(lg.LAGOM_GATHER_COPY, dt, [b.data_ptr() + rank * m * 2 for b in send], [recv], m, 0))
+    elif name == "rs_ag_pair":
+        ncomm = 2
+        grads = [_up(gen(w.seeds[p], w.comm.count)) for p in range(8)]
+        shard = _up(np.zeros(w.comm.count, np_dt))
+        shards = [_up(gen(w.seeds[8 + p], 2097152)) for p in range(8)]
+        full = _up(np.zeros(8 * 2097152, np_dt))
+        keep += [grads, shard, shards, full]
+        launches.append(lg.CommLaunch(lg.LAGOM_REDUCE_COPY, dt, grads, [shard], w.comm.count, 0))
+        launches.append(lg.CommLaunch(lg.LAGOM_GATHER_COPY, dt, shards, [full], 2097152, 1))
     else:
         ncomm = 1
         reps = 1
@@ -182,7 +197,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="dp_bucket", choices=["tiny", "dp_bucket", "tp_layer", "fsdp_chain", "compute_bound"])
+    ap.add_argument("--workload", default="dp_bucket", choices=["tiny", "dp_bucket", "tp_layer", "fsdp_chain", "compute_bound", "ep_alltoall", "rs_ag_pair"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep-iters", type=int, default=5)
     ap.add_argument("--dependent", action="store_true",
@@ -218,7 +233,9 @@ def main():
     y_alone = sweep[0].comp_alone_us / len(comps)
     g0 = -(-geo.mu // (LAMBDA * geo.tb))
     theta = max(0.0, y_alone / g0 - LAMBDA * geo.tb * geo.d_bytes / bw)
-    tables = [{p.cfg: (p.comm_corun_us / ncomm, min(p.v_corun, 0.99 * bw)) for p in sweep} for _ in range(ncomm)]
+    # the sweep times the communication stream as a whole; a communication's x is its share of the bytes
+    share = [sum(b for b, l in zip(nbytes, launches) if l.comm_id == j) / sum(nbytes) for j in range(ncomm)]
+    tables = [{p.cfg: (p.comm_corun_us * share[j], min(p.v_corun, 0.99 * bw)) for p in sweep} for j in range(ncomm)]
     model = lg.Model(LAMBDA, bw, [lg.CompModel(geo.mu, geo.tb, geo.d_bytes, theta) for _ in comps], tables,
                      comp_after_comm=[i - 1 for i in range(len(comps))] if dependent else None)
 

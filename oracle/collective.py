@@ -73,10 +73,11 @@ def reduce_copy(srcs, dtype: str, ndst: int = 1):
         raise ValueError("need at least one source and one destination")
     n = len(srcs[0])
     acc = _widen(srcs[0], dtype).astype(np.float32, copy=True)
-    for s in srcs[1:]:
-        if len(s) != n:
-            raise ValueError("sources differ in length")
-        acc = (acc + _widen(s, dtype)).astype(np.float32)  # one fp32 add per source, in order
+    with np.errstate(over="ignore", invalid="ignore"):   # Inf and NaN inputs are legal data
+        for s in srcs[1:]:
+            if len(s) != n:
+                raise ValueError("sources differ in length")
+            acc = (acc + _widen(s, dtype)).astype(np.float32)  # one fp32 add per source, in order
     out = _narrow(acc, dtype)
     return [out.copy() for _ in range(ndst)]
 
@@ -156,6 +157,27 @@ def all_gather(shards):
     """Every rank ends with the concatenation of all shards."""
     full = gather_copy(shards)[0]
     return [full.copy() for _ in shards]
+
+
+def all_to_all(send_buffers):
+    """Every rank sends block s of its buffer to rank s (Sec. 2.1, expert parallelism).
+
+    ``send_buffers[r]`` holds P equal blocks; rank r's receive buffer is the concatenation over
+    senders s of block r of ``send_buffers[s]``.  On rank r this is a gather-copy whose source s
+    starts at block r of peer s's buffer, which is how the kernel is driven.
+    """
+    P = len(send_buffers)
+    n = len(send_buffers[0])
+    if n % P:
+        raise ValueError("buffer length must divide by the number of ranks")
+    m = n // P
+    out = []
+    for r in range(P):
+        recv = np.empty(n, dtype=np.asarray(send_buffers[0]).dtype)
+        for s_ in range(P):
+            recv[s_ * m:(s_ + 1) * m] = send_buffers[s_][r * m:(r + 1) * m]
+        out.append(recv)
+    return out
 
 
 def ring_all_reduce(buckets, dtype: str):

@@ -107,4 +107,12 @@ WORKLOADS = {
     # back-to-back 16 MiB fp32 two-buffer reduce-copies against one 8192^3 GEMM
     "compute_bound": Workload("compute_bound", CommShape("reduce_copy", "f32", 2, 1, 4194304, launches=3), 1,
                               (8192, 8192, 8192), 1, _NC, _C, (128, 256, 512, 1024), (40, 41)),
+    # expert parallelism: one rank's share of an all-to-all of 8 x 4096 tokens x 2048 bf16 (a gather-copy whose
+    # sources start at this rank's block of every peer's send buffer) against one expert GEMM
+    "ep_alltoall": Workload("ep_alltoall", CommShape("gather_copy", "bf16", 8, 1, 1048576), 1,
+                            (4096, 8192, 2048), 1, _NC, _C, (256,), tuple(range(50, 58))),
+    # two communications of different kinds in one overlap (reduce-scatter share, then all-gather) against
+    # three GEMMs: which one the search raises first is decided by the metric H
+    "rs_ag_pair": Workload("rs_ag_pair", CommShape("reduce_copy", "bf16", 8, 1, 4194304), 2,
+                           (8192, 4096, 4096), 3, _NC, _C, (256,), tuple(range(60, 76)), scale=0.02),
 }

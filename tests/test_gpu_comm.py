@@ -172,3 +172,21 @@ def test_full_size_workload_launches_sampled():
     for cfg in [(512, 512, 16 << 10), (256, 1024, 32 << 10), (1024, 512, 64 << 10)]:
         got = _run(lg.LAGOM_REDUCE_COPY, "f32", f, 1, cfg, n)[0]
         assert same_bits(got, oc.reduce_copy(f, oc.F32)[0]), cfg
+
+
+@pytest.mark.parametrize("dtype,P,m", [("bf16", 8, 4096 * 24), ("f32", 4, 1004)])
+def test_all_to_all_emulated_on_one_gpu(dtype, P, m):
+    """Expert-parallel exchange: rank r's local step is a gather-copy whose source s starts at block r of peer s."""
+    send = _sources(dtype, P, P * m, 500)
+    want = oc.all_to_all(send)
+    dt = lg.LAGOM_BF16 if dtype == "bf16" else lg.LAGOM_F32
+    esz = 2 if dtype == "bf16" else 4
+    d_send = [dev(b) for b in send]
+    d_recv = [torch.zeros_like(d_send[0]) for _ in range(P)]
+    st = torch.cuda.current_stream()
+    for r in range(P):
+        srcs = [d_send[s].data_ptr() + r * m * esz for s in range(P)]
+        lg.lagom_comm_kernel(lg.LAGOM_GATHER_COPY, dt, srcs, [d_recv[r]], m, (4, 256, 32768), st)
+    torch.cuda.synchronize()
+    for r in range(P):
+        assert same_bits(host(d_recv[r], send[0].dtype), want[r]), r

@@ -208,3 +208,20 @@ def test_c_loops_match_numpy_oracle(threads):
     assert out.tolist() == [1.0, 0.0]
     srcs = [np.array([v], dtype=np.uint16) for v in (0x3F80, 0x3B80, 0x3B80)]
     assert cloops.reduce_copy(srcs, "bf16")[0].tolist() == [0x3F81]
+
+
+def test_all_to_all_is_a_block_transpose_and_an_involution():
+    P, m = 4, 37
+    send = [np.arange(r * 1000, r * 1000 + P * m, dtype=np.float32) for r in range(P)]
+    recv = oc.all_to_all(send)
+    grid = np.stack([b.reshape(P, m) for b in send])              # [sender, block, i]
+    want = grid.transpose(1, 0, 2)                                # [receiver, sender, i]
+    for r in range(P):
+        assert np.array_equal(recv[r], want[r].reshape(-1))
+        assert recv[r][2 * m + 5] == send[2][r * m + 5]           # element 5 of what rank 2 sent to rank r
+    back = oc.all_to_all(recv)                                    # exchanging twice returns every buffer
+    for r in range(P):
+        assert np.array_equal(back[r], send[r])
+    # per rank it is a gather-copy whose sources start at that rank's block of every peer
+    for r in range(P):
+        assert np.array_equal(oc.gather_copy([b[r * m:(r + 1) * m] for b in send])[0], recv[r])
