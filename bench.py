@@ -128,7 +128,7 @@ def comm_bytes(launches):
     return [lg.lagom_comm_bytes(l.op, l.dtype, len(l.srcs), len(l.dsts), l.count) for l in launches]
 
 
-def standalone_comm_roofline(st1, st2, iters):
+def standalone_comm_roofline(st1, st2, iters, final_iters=20):
     """Best standalone reduce-copy bandwidth over an extended NC set, on buffers rotated through
     more than the 256 MB last-level cache so that HBM has to serve them.  Two shapes of the
     workloads are tried: the two-source fp32 reduce of 16 MiB buffers and the eight-source bf16
@@ -137,8 +137,9 @@ def standalone_comm_roofline(st1, st2, iters):
     from paper_2602_20656_amd import binding as lg
     shapes = [("reduce_copy f32 S=2 D=1 count=4194304", lg.LAGOM_F32, torch.float32, 2, 4194304, 12),
               ("reduce_copy bf16 S=8 D=1 count=4194304", lg.LAGOM_BF16, torch.bfloat16, 8, 4194304, 8)]
-    best = None
-    for name, dt, tdt, nsrc, count, nrot in shapes:
+    best, best_shape = None, None
+    for shape in shapes:
+        name, dt, tdt, nsrc, count, nrot = shape
         bufs = [[torch.empty(count, dtype=torch.float32, device="cuda").uniform_(-1, 1).to(tdt) for _ in range(nsrc + 1)]
                 for _ in range(nrot)]
         launches = [lg.CommLaunch(lg.LAGOM_REDUCE_COPY, dt, b[:nsrc], [b[nsrc]], count, 0) for b in bufs]
@@ -150,12 +151,23 @@ def standalone_comm_roofline(st1, st2, iters):
                     us = t.X_us / nrot
                     gbps = per_launch / us / 1e3
                     if best is None or gbps > best["achieved"]:
+                        best_shape = shape
                         best = {"bound": "hbm", "kernel": "reduce_copy_kernel", "workload": name, "achieved": gbps,
                                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS,
                                 "traffic": MEASURED_TRAFFIC_BYTES.get(name),
                                 "us_per_launch": us, "bytes_per_launch": per_launch, "cfg": [nc, nt, chunk],
                                 "rotation_mib": nrot * per_launch >> 20}
         del bufs, launches
+    # the figure that is reported: the winning configuration once more, final_iters passes of nrot launches each
+    # (these are the last dispatches of that kernel in a trace of this run)
+    name, dt, tdt, nsrc, count, nrot = best_shape
+    bufs = [[torch.empty(count, dtype=torch.float32, device="cuda").uniform_(-1, 1).to(tdt) for _ in range(nsrc + 1)]
+            for _ in range(nrot)]
+    launches = [lg.CommLaunch(lg.LAGOM_REDUCE_COPY, dt, b[:nsrc], [b[nsrc]], count, 0) for b in bufs]
+    t = lg.lagom_overlap_run(launches, [tuple(best["cfg"])], [], st1, st2, 2, final_iters, lg.LAGOM_ALONE_COMM)
+    us = t.X_us / nrot
+    best.update({"achieved": best["bytes_per_launch"] / us / 1e3, "frac": best["bytes_per_launch"] / us / 1e3 / HBM_PEAK_GBPS,
+                 "us_per_launch": us, "launches_timed": nrot * final_iters})
     return best
 
 
