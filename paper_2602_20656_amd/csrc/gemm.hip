@@ -22,7 +22,8 @@
 //     bank line; this swizzle makes the 16 lanes of a ds_read_b128 phase hit 16 distinct
 //     16-byte bank groups (measured: no bank-conflict cycles, against +50 % with r & 7).
 //   * Operand fragments are double buffered in registers: the reads for k-slice kk+1 are issued
-//     between the MFMAs of slice kk.
+//     between the first MFMAs of slice kk, in the order slice kk+1 consumes them; the steady-state
+//     loop is branch-free (the last two K-steps, which load nothing or only B, are peeled).
 //   * The MFMA is issued with the B fragment as first operand, so a lane ends up holding four
 //     consecutive columns of one row of C; bf16 results are packed (v_cvt_pk_bf16_f32), staged
 //     through LDS and written to HBM as full 16-byte vectors, 256 contiguous bytes per row.
@@ -30,6 +31,7 @@
 // bounds checks and zero fill, then stored to LDS; single buffered.  Slower; used for ragged
 // K and for B stored [K,N].
 #include <hip/hip_runtime.h>
+#include <type_traits>
 #include "common.h"
 
 namespace {
@@ -280,12 +282,17 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
 #pragma unroll
     for (int r = 0; r < 8; ++r) read_frag(slot_ptr(0), slot_ptr(1), 0, r, 0);
 
+    // One K-step.  MORE1 / MORE2: tiles kt+1 / kt+2 exist (compile-time, so that the steady-state loop has
+    // no branches; the last two steps are peeled).  The eight fragment reads of k-slice kk+1 are issued in
+    // the first two MFMA groups of slice kk, in the order the next slice's MFMAs need them, so that the
+    // wait in front of a slice finds them long since arrived.
+    constexpr int kReadOrder[8] = {0, 4, 5, 6, 7, 1, 2, 3};   // A0, B0..B3, A1..A3
     int s_a = 0;   // slot of A(kt); B(kt), A(kt+1), B(kt+1), A(kt+2) follow at +1..+4 modulo 5
-    for (int64_t kt = 0; kt < ksteps; ++kt) {
+    auto step = [&](int64_t kt, auto more1_c, auto more2_c) {
+        constexpr bool more1 = decltype(more1_c)::value, more2 = decltype(more2_c)::value;
         const int s_b = (s_a + 1) % LDS_SLOTS, s_a1 = (s_a + 2) % LDS_SLOTS, s_b1 = (s_a + 3) % LDS_SLOTS, s_a2 = (s_a + 4) % LDS_SLOTS;
         const u32x4* sa = slot_ptr(s_a);
         const u32x4* sb = slot_ptr(s_b);
-        const bool more1 = kt + 1 < ksteps, more2 = kt + 2 < ksteps;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
 #pragma unroll
@@ -293,9 +300,9 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
                 const int q = kk * 4 + g;
                 if (q < 8) { if (more1) load_b(s_b1, kt + 1, q); }        // slot freed by B(kt-1)
                 else { if (more2) load_a(s_a2, kt + 2, q - 8); }          // slot freed by A(kt-1)
-                if (kk < 3) {
-                    read_frag(sa, sb, kk + 1, g * 2, (kk + 1) & 1);
-                    read_frag(sa, sb, kk + 1, g * 2 + 1, (kk + 1) & 1);
+                if (kk < 3 && g < 2) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) read_frag(sa, sb, kk + 1, kReadOrder[g * 4 + e], (kk + 1) & 1);
                 }
 #pragma unroll
                 for (int j = 0; j < 4; ++j)   // B fragment first: the lane's 16 results are C[row lane%32][4 x 4 consecutive columns]
@@ -310,11 +317,15 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
         __builtin_amdgcn_s_barrier();
         if (more1) {
 #pragma unroll
-            for (int r = 0; r < 8; ++r) read_frag(slot_ptr(s_a1), slot_ptr(s_b1), 0, r, 0);
+            for (int e = 0; e < 8; ++e) read_frag(slot_ptr(s_a1), slot_ptr(s_b1), 0, kReadOrder[e], 0);
         }
         __builtin_amdgcn_sched_barrier(0);
         s_a = s_a1;
-    }
+    };
+    int64_t kt = 0;
+    for (; kt + 2 < ksteps; ++kt) step(kt, std::true_type{}, std::true_type{});
+    if (kt + 1 < ksteps) { step(kt, std::true_type{}, std::false_type{}); ++kt; }
+    if (kt < ksteps) step(kt, std::false_type{}, std::false_type{});
 
     // acc[i][j][v]: row i*32 + lane%32, column j*32 + 8*(v/4) + 4*(lane/32) + v%4 of the wavefront's 128 x 128 block
     const int r_in = lane & 31, c_half = 4 * (lane >> 5);
