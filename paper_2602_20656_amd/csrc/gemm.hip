@@ -11,8 +11,8 @@
 // Fast kernel (B stored [N,K], K a multiple of 64):
 //   * A and B tiles go from global memory straight into LDS (global_load_lds_dwordx4).  LDS
 //     holds five 32 KiB slots used as a ring A0,B0,A1,B1,A2,...: while step kt multiplies the
-//     tiles in two slots, B(kt+1) is loaded during its first half and A(kt+2) during its second
-//     half, so every load has at least half a step to land before it is needed and 1.5 tiles
+//     tiles in two slots, the loads of B(kt+1), A(kt+2) and B(kt+2) are in flight, issued so that
+//     every load has at least half a step to land before it is needed and 1.5 tiles
 //     are in flight on average (one CU's load path delivers 65 GB/s with one tile in flight and
 //     90 GB/s with two; 77 GB/s are needed at full MFMA rate).  The 16 load instructions of a
 //     wavefront per step are spread one per group of four MFMAs: issued as a burst they stall
@@ -259,7 +259,7 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
     auto load_b = [&](int slot, int64_t kt, int d) { load_to_lds16(gb + b_off[d] + kt * BK, slot_ptr(slot) + (d * 4 + wave) * 64); };
 
     const int64_t ksteps = K / BK;
-    // prologue: A0 -> slot 0, B0 -> slot 1, A1 -> slot 2
+    // prologue: A0 -> slot 0, B0 -> slot 1, A1 -> slot 2, first half of B1 -> slot 3
 #pragma unroll
     for (int d = 0; d < 8; ++d) load_a(0, 0, d);
 #pragma unroll
@@ -267,7 +267,9 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
     if (ksteps > 1) {
 #pragma unroll
         for (int d = 0; d < 8; ++d) load_a(2, 1, d);
-        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");   // loads complete in issue order: A0 and B0 are in
+#pragma unroll
+        for (int d = 0; d < 4; ++d) load_b(3, 1, d);
+        asm volatile("s_waitcnt vmcnt(12)" ::: "memory");   // loads complete in issue order: A0 and B0 are in
     } else {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
@@ -282,10 +284,16 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
 #pragma unroll
     for (int r = 0; r < 8; ++r) read_frag(slot_ptr(0), slot_ptr(1), 0, r, 0);
 
-    // One K-step.  MORE1 / MORE2: tiles kt+1 / kt+2 exist (compile-time, so that the steady-state loop has
-    // no branches; the last two steps are peeled).  The eight fragment reads of k-slice kk+1 are issued in
-    // the first two MFMA groups of slice kk, in the order the next slice's MFMAs need them, so that the
-    // wait in front of a slice finds them long since arrived.
+    // One K-step (16 groups of 4 MFMAs, four per k-slice).  MORE1 / MORE2: tiles kt+1 / kt+2 exist
+    // (compile-time, so that the steady-state loop has no branches; the last two steps are peeled).
+    //   loads   groups 0-3: second half of B(kt+1); groups 4-11: A(kt+2) into the fifth slot;
+    //           groups 12-15: first half of B(kt+2) into the slot A(kt) has just left.
+    //   reads   the eight fragments of k-slice kk+1 are read in the first two groups of slice kk, in the
+    //           order slice kk+1 consumes them.
+    //   barrier in front of the last k-slice: by then this wavefront holds every fragment of tile kt in
+    //           registers, tile kt+1 has landed (the 8 youngest loads, A(kt+2), may still fly), so after
+    //           the barrier tile kt's slots are free and the first fragments of tile kt+1 are read under
+    //           the last 16 MFMAs instead of after them.
     constexpr int kReadOrder[8] = {0, 4, 5, 6, 7, 1, 2, 3};   // A0, B0..B3, A1..A3
     int s_a = 0;   // slot of A(kt); B(kt), A(kt+1), B(kt+1), A(kt+2) follow at +1..+4 modulo 5
     auto step = [&](int64_t kt, auto more1_c, auto more2_c) {
@@ -295,14 +303,27 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
         const u32x4* sb = slot_ptr(s_b);
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
+            if (kk == 3) {
+                if (more2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+                else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+            }
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int q = kk * 4 + g;
-                if (q < 8) { if (more1) load_b(s_b1, kt + 1, q); }        // slot freed by B(kt-1)
-                else { if (more2) load_a(s_a2, kt + 2, q - 8); }          // slot freed by A(kt-1)
-                if (kk < 3 && g < 2) {
+                if (q < 4) { if (more1) load_b(s_b1, kt + 1, 4 + q); }
+                else if (q < 12) { if (more2) load_a(s_a2, kt + 2, q - 4); }
+                else { if (more2) load_b(s_a, kt + 2, q - 12); }
+                if (g < 2) {
+                    if (kk < 3) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) read_frag(sa, sb, kk + 1, kReadOrder[g * 4 + e], (kk + 1) & 1);
+                        for (int e = 0; e < 4; ++e) read_frag(sa, sb, kk + 1, kReadOrder[g * 4 + e], (kk + 1) & 1);
+                    } else if (more1) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) read_frag(slot_ptr(s_a1), slot_ptr(s_b1), 0, kReadOrder[g * 4 + e], 0);
+                    }
                 }
 #pragma unroll
                 for (int j = 0; j < 4; ++j)   // B fragment first: the lane's 16 results are C[row lane%32][4 x 4 consecutive columns]
@@ -310,22 +331,13 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
                 __builtin_amdgcn_sched_barrier(0);   // keep this load / read / MFMA grouping
             }
         }
-        // tile kt+1 has landed (this wavefront's part; the 8 youngest loads, A(kt+2), may still fly)
-        // and after the barrier everyone is done reading tile kt
-        if (more2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-        if (more1) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) read_frag(slot_ptr(s_a1), slot_ptr(s_b1), 0, kReadOrder[e], 0);
-        }
-        __builtin_amdgcn_sched_barrier(0);
         s_a = s_a1;
     };
     int64_t kt = 0;
     for (; kt + 2 < ksteps; ++kt) step(kt, std::true_type{}, std::true_type{});
     if (kt + 1 < ksteps) { step(kt, std::true_type{}, std::false_type{}); ++kt; }
     if (kt < ksteps) step(kt, std::false_type{}, std::false_type{});
+    __builtin_amdgcn_s_barrier();   // every wavefront is past its last LDS read before the slots are reused below
 
     // acc[i][j][v]: row i*32 + lane%32, column j*32 + 8*(v/4) + 4*(lane/32) + v%4 of the wavefront's 128 x 128 block
     const int r_in = lane & 31, c_half = 4 * (lane >> 5);

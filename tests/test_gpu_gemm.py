@@ -32,7 +32,7 @@ def _gemm(a_bits, b_bits, b_is_nk, out):
 
 
 @pytest.mark.parametrize("M,N,K", [(512, 512, 512), (1, 1, 8), (300, 200, 136), (700, 520, 264), (256, 256, 64),
-                                   (257, 255, 72), (33, 1000, 4096), (130, 77, 128), (513, 260, 192)])
+                                   (257, 255, 72), (33, 1000, 4096), (130, 77, 128), (513, 260, 192), (700, 300, 320), (1000, 520, 256), (300, 300, 64)])
 @pytest.mark.parametrize("b_is_nk", [True, False])
 @pytest.mark.parametrize("out", ["bf16", "f32"])
 def test_gemm_small_shapes(M, N, K, b_is_nk, out):
