@@ -253,7 +253,15 @@ def main():
 
     # ---- the search: Alg. 1/2 with measured profiles, and with the model as ProfileTime
     nt_grid = list(w.nt_grid) if len(w.nt_grid) > 1 else [256]
-    spaces = [lg.Space(list(w.nc_grid), nt_grid, list(w.chunk_grid)) for _ in range(ncomm)]
+    # The ladder's chunk grid is cut where a chunk would exceed (bytes one launch moves per source) / NC_max:
+    # beyond that point part of the channels of every launch have no chunk to move (chunk g goes to channel
+    # g mod NC), so a higher level could only be slower.  The profiler still sweeps the full grid.
+    spaces = []
+    for j in range(ncomm):
+        esz = 4 if w.comm.dtype == "f32" else 2
+        per_src = min(l.count * esz * (len(l.srcs) if l.op == lg.LAGOM_GATHER_COPY else 1) for l in launches if l.comm_id == j)
+        cut = [c for c in w.chunk_grid if c * max(w.nc_grid) <= per_src] or [min(w.chunk_grid)]
+        spaces.append(lg.Space(list(w.nc_grid), nt_grid, cut))
     ladder_ok = all(tuple(c) in tables[0] for c in
                     [(spaces[0].nc[min(l, len(spaces[0].nc) - 1)], spaces[0].nt[min(l, len(spaces[0].nt) - 1)],
                       spaces[0].chunk[min(l, len(spaces[0].chunk) - 1)]) for l in range(max(len(spaces[0].nc), len(spaces[0].nt), len(spaces[0].chunk)))])
@@ -309,7 +317,8 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload + ("+dependent" if dependent else ""), "comm": f"{w.comm.op} {w.comm.dtype} S={w.comm.nsrc} count={w.comm.count} "
                    f"launches={len(launches)} comms={ncomm}", "gemm": f"{M}x{N}x{K} bf16 x{len(comps)}",
-                   "default_cfg": list(DEFAULT_CFG), "tuned_cfgs": [list(c) for c in tuned.cfgs]},
+                   "default_cfg": list(DEFAULT_CFG), "tuned_cfgs": [list(c) for c in tuned.cfgs],
+                   "ladder_chunk_grids": [list(sp.chunk) for sp in spaces]},
         "z_tuned_us": t_tuned.Z_us, "z_default_us": t_default.Z_us,
         "x_tuned_us": t_tuned.X_us, "y_tuned_us": t_tuned.Y_us, "x_default_us": t_default.X_us, "y_default_us": t_default.Y_us,
         "z_comm_optimal_us": t_commopt.Z_us, "comm_optimal_cfg": list(comm_opt.cfg),
