@@ -144,7 +144,13 @@ __global__ void __launch_bounds__(MAXNT) reduce_copy_kernel(const CommArgs p) {
             Acc<DT> acc;
             acc.init(ld16<STREAM>(p.src[0] + off));
             const int ns = S > 0 ? S : p.nsrc;
-            for (int s = 1; s < ns; ++s) acc.add(ld16<STREAM>(p.src[s] + off));
+            int s = 1;
+            for (; s + 3 < ns; s += 4) {          // four loads in flight, added in source order
+                const u32x4 x0 = ld16<STREAM>(p.src[s] + off), x1 = ld16<STREAM>(p.src[s + 1] + off);
+                const u32x4 x2 = ld16<STREAM>(p.src[s + 2] + off), x3 = ld16<STREAM>(p.src[s + 3] + off);
+                acc.add(x0); acc.add(x1); acc.add(x2); acc.add(x3);
+            }
+            for (; s < ns; ++s) acc.add(ld16<STREAM>(p.src[s] + off));
             const u32x4 o = acc.result();
             for (int d = 0; d < p.ndst; ++d) st16(p.dst[d] + off, o);
         }

@@ -190,3 +190,18 @@ def test_all_to_all_emulated_on_one_gpu(dtype, P, m):
     torch.cuda.synchronize()
     for r in range(P):
         assert same_bits(host(d_recv[r], send[0].dtype), want[r]), r
+
+
+def test_limits_of_the_argument_ranges():
+    """Most sources and destinations the ABI allows, the largest channel count, the smallest chunk and block."""
+    count = 40000 + 3
+    for dtype in ("f32", "bf16"):
+        srcs = _sources(dtype, 16, count, 700)
+        want = oc.reduce_copy(srcs, dtype, 4)
+        for cfg in [(65535, 64, 16), (1, 1024, 4 << 20), (300, 192, 48)]:
+            got = _run(lg.LAGOM_REDUCE_COPY, dtype, srcs, 4, cfg, count)
+            for g, w in zip(got, want):
+                assert same_bits(g, w), (dtype, cfg)
+        shards = _sources(dtype, 16, 1001, 800)
+        for g in _run(lg.LAGOM_GATHER_COPY, dtype, shards, 4, (65535, 64, 16), 16 * 1001):
+            assert same_bits(g, np.concatenate(shards))
