@@ -251,6 +251,13 @@ def main():
     model = lg.Model(LAMBDA, bw, [lg.CompModel(geo.mu, geo.tb, geo.d_bytes, theta) for _ in comps], tables,
                      comp_after_comm=[i - 1 for i in range(len(comps))] if dependent else None)
 
+    # ---- how well Eq. 4-6 reproduce the sweep they were filled from: predicted Y against measured Y, per point
+    errs = []
+    for pt in sweep:
+        pred = lg.lagom_cost_model(model, [pt.cfg] * ncomm)
+        errs.append(abs(pred.Y_us - pt.comp_corun_us) / pt.comp_corun_us)
+    model_y_mape, model_y_max = float(np.mean(errs)), float(np.max(errs))
+
     # ---- the search: Alg. 1/2 with measured profiles, and with the model as ProfileTime
     nt_grid = list(w.nt_grid) if len(w.nt_grid) > 1 else [256]
     # The ladder's chunk grid is cut where a chunk would exceed (bytes one launch moves per source) / NC_max:
@@ -327,6 +334,7 @@ def main():
         "z_model_tuned_us": t_model.Z_us if t_model else None,
         "model_tuned_cfgs": [list(c) for c in tuned_model.cfgs] if tuned_model else None,
         "model_predicted_z_us": lg.lagom_cost_model(model, tuned_model.cfgs).Z_us if tuned_model else None,
+        "model_y_mean_abs_rel_err": model_y_mape, "model_y_max_abs_rel_err": model_y_max,
         "tune_profile_calls": tuned.calls, "tune_seconds": tune_s, "sweep_points": len(points), "sweep_seconds": sweep_s,
         "gemm_alone_us": gemm_us, "gemm_mfma_util": tflops / BF16_PEAK_TFLOPS,
         "gemm_slowdown_default": t_default.Y_us / t_gemm.Y_us, "gemm_slowdown_tuned": t_tuned.Y_us / t_gemm.Y_us,
