@@ -1,35 +1,39 @@
 // lagom_gemm: C[M,N] = A[M,K] . B, bf16 inputs, fp32 accumulation on the gfx950 matrix
-// cores (v_mfma_f32_32x32x16_bf16), the computation whose slow-down the overlap model
-// describes (Sec. 3.2, Fig. 3).
+// cores, the computation whose slow-down the overlap model describes (Sec. 3.2, Fig. 3).
 //
 // Tiling (both kernels): one workgroup of 256 threads (4 wavefronts, 2 x 2) owns a 256 x 256
-// tile of C and walks K in steps of 64; each wavefront owns 128 x 128 = 4 x 4 MFMA tiles of
-// 32 x 32, i.e. 256 fp32 accumulators per lane (the whole AGPR file), so one workgroup is
-// resident per compute unit.  Workgroup ids are remapped so that the workgroups of one XCD
-// (ids equal modulo 8) cover a compact block of tiles and share A/B panels in that XCD's L2.
+// tile of C and walks K in steps of 64; each wavefront owns a 128 x 128 block, i.e. 256 fp32
+// accumulators per lane (the whole AGPR file), so one workgroup is resident per compute unit.
+// Workgroup ids are remapped so that the workgroups of one XCD (ids equal modulo 8) cover a
+// compact block of tiles and share A/B panels in that XCD's L2.
 //
-// Fast kernel (B stored [N,K], K a multiple of 64):
-//   * A and B tiles go from global memory straight into LDS (global_load_lds_dwordx4).  LDS
-//     holds five 32 KiB slots used as a ring A0,B0,A1,B1,A2,...: while step kt multiplies the
-//     tiles in two slots, the loads of B(kt+1), A(kt+2) and B(kt+2) are in flight, issued so that
-//     every load has at least half a step to land before it is needed and 1.5 tiles
-//     are in flight on average (one CU's load path delivers 65 GB/s with one tile in flight and
-//     90 GB/s with two; 77 GB/s are needed at full MFMA rate).  The 16 load instructions of a
-//     wavefront per step are spread one per group of four MFMAs: issued as a burst they stall
-//     the wavefront on the address queue for most of the load time and starve the matrix core.
+// Fast kernel (B stored [N,K], K a multiple of 64, K <= 2^22):
+//   * v_mfma_f32_16x16x32_bf16, 8 x 8 MFMA tiles per wavefront.  Under random operands the chip
+//     is power limited, and this shape costs less energy per flop than 32x32x16: a register-only
+//     loop sustains 86 % of the 2.5 PFLOP/s peak at 2.14 GHz with it against 77 % at 1.89 GHz.
+//     The MFMAs are inline asm with the accumulators pinned to AGPRs (with the builtin the
+//     register allocator copies the 64 accumulator quads around on every iteration).
+//   * A and B tiles go from global memory straight into LDS (global_load_lds_dwordx4, scalar base
+//     + 32-bit lane offset).  LDS holds five 32 KiB slots used as a ring A0,B0,A1,B1,A2,...: while
+//     step kt multiplies the tiles in two slots, the loads of B(kt+1), A(kt+2) and B(kt+2) are in
+//     flight, issued so that every load has at least half a step to land before it is needed.
+//   * One side instruction per MFMA: a 16x16x32 MFMA keeps the matrix core busy for 16 cycles and
+//     takes 4 to issue, so one load, M0 write or ds_read issued right behind it costs nothing,
+//     whereas several in a row leave the matrix core idle (measured: 2720 -> 2370 cycles per
+//     K-step against 2048 of pure MFMA time).
 //   * LDS rows are 128 bytes (64 bf16 = eight 16-byte groups); group g of row r is stored at
 //     position g ^ ((r >> 1) & 7).  LDS on gfx950 has 64 banks of 4 bytes, so two rows share a
 //     bank line; this swizzle makes the 16 lanes of a ds_read_b128 phase hit 16 distinct
-//     16-byte bank groups (measured: no bank-conflict cycles, against +50 % with r & 7).
-//   * Operand fragments are double buffered in registers: the reads for k-slice kk+1 are issued
-//     between the first MFMAs of slice kk, in the order slice kk+1 consumes them; the steady-state
-//     loop is branch-free (the last two K-steps, which load nothing or only B, are peeled).
+//     16-byte bank groups.
+//   * Operand fragments are double buffered in registers (two 32-wide k-slices of 8 + 8
+//     fragments); the steady-state loop is branch-free (the last two K-steps, which load nothing
+//     or only B, are peeled).
 //   * The MFMA is issued with the B fragment as first operand, so a lane ends up holding four
-//     consecutive columns of one row of C; bf16 results are packed (v_cvt_pk_bf16_f32), staged
-//     through LDS and written to HBM as full 16-byte vectors, 256 contiguous bytes per row.
-// General kernel (any K multiple of 8, either B layout): tiles are fetched into registers with
-// bounds checks and zero fill, then stored to LDS; single buffered.  Slower; used for ragged
-// K and for B stored [K,N].
+//     consecutive columns of one row of C; results are staged through LDS and written to HBM as
+//     16-byte vectors, whole rows of the wavefront's block contiguous.
+// General kernel (any K multiple of 8, either B layout, v_mfma_f32_32x32x16_bf16): tiles are
+// fetched into registers with bounds checks and zero fill, then stored to LDS; single buffered.
+// Slower; used for ragged K and for B stored [K,N].
 #include <hip/hip_runtime.h>
 #include <type_traits>
 #include "common.h"
@@ -208,17 +212,17 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 constexpr int LDS_SLOTS = 5;                             // ring of operand tiles: A0 B0 A1 B1 A2 ...
-constexpr int FAST_LDS_BYTES = LDS_SLOTS * BM * BK * 2;  // 160 KiB: all of a compute unit's LDS
+constexpr int SLOT_BYTES = BM * BK * 2;                  // 32 KiB: one operand tile
+constexpr int FAST_LDS_BYTES = LDS_SLOTS * SLOT_BYTES;   // 160 KiB: all of a compute unit's LDS
 constexpr int TILE_SLOTS = BM * 8;                       // 16-byte slots of one operand tile
+constexpr int64_t FAST_MAX_K = int64_t(1) << 22;         // 256 rows x K x 2 bytes must fit a 32-bit lane offset
 
 __device__ __forceinline__ int swz64(int row, int cg) { return row * 8 + (cg ^ ((row >> 1) & 7)); }
 
-// 16 bytes per lane from global memory straight into LDS: the wavefront writes 64 consecutive
-// 16-byte slots starting at `lds` (which must be wave-uniform).
-__device__ __forceinline__ void load_to_lds16(const void* g, void* lds) {
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
-                                     (__attribute__((address_space(3))) void*)lds, 16, 0, 0);
-}
+// One 16x16x32 MFMA, accumulator pinned to the AGPR file.  Written as inline asm: with the builtin the
+// register allocator rotates the 64 accumulator quads through copies on every loop iteration.
+#define LAGOM_MFMA_16x16x32(ACC, SRC_A, SRC_B) \
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(ACC) : "v"(SRC_A), "v"(SRC_B))
 
 template <bool OUT_BF16>
 __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p) {
@@ -232,103 +236,129 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
     const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
     const int64_t M = p.M, N = p.N, K = p.K;
 
-    f32x16 acc[4][4];
+    f32x4 acc[8][8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < 8; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+            for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.0f;
 
     // Load instruction d (0..7) of an operand tile fills its 16-byte slots [(d*4+wave)*64, +64):
     // lane -> row (d*4+wave)*8 + lane/8, stored group lane%8, i.e. source group (lane%8) ^ ((row>>1)&7).
     // (row>>1)&7 does not depend on d because rows of successive d differ by 32.
+    // Addresses are a wave-uniform 64-bit base (first row of the tile, advanced along K) plus a 32-bit
+    // byte offset per lane; rows past the edge re-read the last row.
     const int srow = wave * 8 + (lane >> 3);
     const int scg = (lane & 7) ^ ((srow >> 1) & 7);
-    const uint16_t* ga = p.A + scg * 8;
-    const uint16_t* gb = p.B + scg * 8;
-    int64_t a_off[8], b_off[8];   // element offsets of the 8 source rows; rows past the edge re-read the last row
+    const char* base_a = reinterpret_cast<const char*>(p.A + m0 * K);
+    const char* base_b = reinterpret_cast<const char*>(p.B + n0 * K);
+    uint32_t a_off[8], b_off[8];
 #pragma unroll
     for (int d = 0; d < 8; ++d) {
-        const int64_t ra = m0 + srow + 32 * d, rb = n0 + srow + 32 * d;
-        a_off[d] = (ra < M ? ra : M - 1) * K;
-        b_off[d] = (rb < N ? rb : N - 1) * K;
+        const int64_t r = srow + 32 * d, last_a = M - 1 - m0, last_b = N - 1 - n0;
+        a_off[d] = (uint32_t)(((r < last_a ? r : last_a) * K + scg * 8) * 2);
+        b_off[d] = (uint32_t)(((r < last_b ? r : last_b) * K + scg * 8) * 2);
     }
+    // LDS byte address of this wavefront's 1 KiB window of load 0 in slot 0
+    const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) char*)smem + wave * 1024;
+    // 16 bytes per lane from global memory straight into LDS: M0 holds the LDS address of lane 0.
+    auto load_now = [&](const char* sbase, uint32_t voff, int slot, int d) {
+        const uint32_t la = lds0 + slot * SLOT_BYTES + d * 4096;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(la), "v"(voff), "s"(sbase) : "memory");
+    };
+    // main-loop form in two halves, one MFMA apart (which also is the wait state M0 needs before the load)
+    auto set_m0 = [&](uint32_t slot_base, int d) { asm volatile("s_add_i32 m0, %0, %1" ::"s"(slot_base), "n"(d * 4096) : "memory"); };
+    auto load_m0 = [&](const char* sbase, uint32_t voff) { asm volatile("global_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase) : "memory"); };
     auto slot_ptr = [&](int slot) -> u32x4* { return smem + slot * TILE_SLOTS; };
-    auto load_a = [&](int slot, int64_t kt, int d) { load_to_lds16(ga + a_off[d] + kt * BK, slot_ptr(slot) + (d * 4 + wave) * 64); };
-    auto load_b = [&](int slot, int64_t kt, int d) { load_to_lds16(gb + b_off[d] + kt * BK, slot_ptr(slot) + (d * 4 + wave) * 64); };
 
     const int64_t ksteps = K / BK;
     // prologue: A0 -> slot 0, B0 -> slot 1, A1 -> slot 2, first half of B1 -> slot 3
 #pragma unroll
-    for (int d = 0; d < 8; ++d) load_a(0, 0, d);
+    for (int d = 0; d < 8; ++d) load_now(base_a, a_off[d], 0, d);
 #pragma unroll
-    for (int d = 0; d < 8; ++d) load_b(1, 0, d);
+    for (int d = 0; d < 8; ++d) load_now(base_b, b_off[d], 1, d);
     if (ksteps > 1) {
 #pragma unroll
-        for (int d = 0; d < 8; ++d) load_a(2, 1, d);
+        for (int d = 0; d < 8; ++d) load_now(base_a + BK * 2, a_off[d], 2, d);
 #pragma unroll
-        for (int d = 0; d < 4; ++d) load_b(3, 1, d);
+        for (int d = 0; d < 4; ++d) load_now(base_b + BK * 2, b_off[d], 3, d);
         asm volatile("s_waitcnt vmcnt(12)" ::: "memory");   // loads complete in issue order: A0 and B0 are in
     } else {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
     __builtin_amdgcn_s_barrier();
 
-    const int arow = wm * 128 + (lane & 31), brow = wn * 128 + (lane & 31), khalf = lane >> 5;
-    bf16x8 fa[2][4], fb[2][4];
-    auto read_frag = [&](const u32x4* sa, const u32x4* sb, int kk, int r, int slot) {   // r: A0..A3, B0..B3
-        if (r < 4) fa[slot][r] = __builtin_bit_cast(bf16x8, sa[swz64(arow + r * 32, kk * 2 + khalf)]);
-        else fb[slot][r - 4] = __builtin_bit_cast(bf16x8, sb[swz64(brow + (r - 4) * 32, kk * 2 + khalf)]);
+    // Fragment r of a 32-wide k-slice: lane -> row 16*r + lane%16, 16-byte group 4*slice + lane/16.
+    const int arow = wm * 128 + (lane & 15), brow = wn * 128 + (lane & 15), kq = lane >> 4;
+    bf16x8 fa[2][8], fb[2][8];
+    auto read_frag = [&](const u32x4* sa, const u32x4* sb, int ks, int r, int buf) {   // r: 0..7 = A0..A7, 8..15 = B0..B7
+        if (r < 8) fa[buf][r] = __builtin_bit_cast(bf16x8, sa[swz64(arow + r * 16, ks * 4 + kq)]);
+        else fb[buf][r - 8] = __builtin_bit_cast(bf16x8, sb[swz64(brow + (r - 8) * 16, ks * 4 + kq)]);
     };
 #pragma unroll
-    for (int r = 0; r < 8; ++r) read_frag(slot_ptr(0), slot_ptr(1), 0, r, 0);
+    for (int r = 0; r < 16; ++r) read_frag(slot_ptr(0), slot_ptr(1), 0, r, 0);
 
-    // One K-step (16 groups of 4 MFMAs, four per k-slice).  MORE1 / MORE2: tiles kt+1 / kt+2 exist
-    // (compile-time, so that the steady-state loop has no branches; the last two steps are peeled).
-    //   loads   groups 0-3: second half of B(kt+1); groups 4-11: A(kt+2) into the fifth slot;
-    //           groups 12-15: first half of B(kt+2) into the slot A(kt) has just left.
-    //   reads   the eight fragments of k-slice kk+1 are read in the first two groups of slice kk, in the
-    //           order slice kk+1 consumes them.
-    //   barrier in front of the last k-slice: by then this wavefront holds every fragment of tile kt in
-    //           registers, tile kt+1 has landed (the 8 youngest loads, A(kt+2), may still fly), so after
-    //           the barrier tile kt's slots are free and the first fragments of tile kt+1 are read under
-    //           the last 16 MFMAs instead of after them.
-    constexpr int kReadOrder[8] = {0, 4, 5, 6, 7, 1, 2, 3};   // A0, B0..B3, A1..A3
+    // One K-step = 2 k-slices x 8 groups x 8 MFMAs (group g: A fragment g against the 8 B fragments).
+    // MORE1 / MORE2: tiles kt+1 / kt+2 exist (compile-time, so that the steady-state loop has no
+    // branches; the last two K-steps are peeled).  Every MFMA is followed by at most one other
+    // instruction, which issues while the matrix core works on that MFMA:
+    //   loads   one per group, M0 after the group's first MFMA and the load after its second:
+    //           groups 0-3 second half of B(kt+1); 4-11 A(kt+2) into the fifth slot; 12-15 first half
+    //           of B(kt+2) into the slot A(kt) has just left.
+    //   reads   slice 0: two fragments of slice 1 per group; slice 1, groups 4-7: four fragments per
+    //           group of slice 0 of tile kt+1, in the order the next step consumes them.
+    //   barrier in front of group 12: by then this wavefront holds every fragment of tile kt in
+    //           registers and tile kt+1 has landed (the 8 youngest loads, A(kt+2), may still fly), so
+    //           after the barrier tile kt's slots are free and tile kt+1 may be read.
+    constexpr int kReadOrder[16] = {0, 8, 9, 10, 11, 12, 13, 14, 15, 1, 2, 3, 4, 5, 6, 7};   // A0, B0..B7, A1..A7
     int s_a = 0;   // slot of A(kt); B(kt), A(kt+1), B(kt+1), A(kt+2) follow at +1..+4 modulo 5
     auto step = [&](int64_t kt, auto more1_c, auto more2_c) {
         constexpr bool more1 = decltype(more1_c)::value, more2 = decltype(more2_c)::value;
         const int s_b = (s_a + 1) % LDS_SLOTS, s_a1 = (s_a + 2) % LDS_SLOTS, s_b1 = (s_a + 3) % LDS_SLOTS, s_a2 = (s_a + 4) % LDS_SLOTS;
         const u32x4* sa = slot_ptr(s_a);
         const u32x4* sb = slot_ptr(s_b);
+        const u32x4* sa1 = slot_ptr(s_a1);
+        const u32x4* sb1 = slot_ptr(s_b1);
+        const uint32_t l_b1 = lds0 + s_b1 * SLOT_BYTES, l_a2 = lds0 + s_a2 * SLOT_BYTES, l_a = lds0 + s_a * SLOT_BYTES;
+        const char* g_b1 = base_b + (kt + 1) * (BK * 2);
+        const char* g_a2 = base_a + (kt + 2) * (BK * 2);
+        const char* g_b2 = base_b + (kt + 2) * (BK * 2);
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            if (kk == 3) {
-                if (more2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-                else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-                __builtin_amdgcn_s_barrier();
-                __builtin_amdgcn_sched_barrier(0);
-            }
+        for (int ks = 0; ks < 2; ++ks) {
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int q = kk * 4 + g;
-                if (q < 4) { if (more1) load_b(s_b1, kt + 1, 4 + q); }
-                else if (q < 12) { if (more2) load_a(s_a2, kt + 2, q - 4); }
-                else { if (more2) load_b(s_a, kt + 2, q - 12); }
-                if (g < 2) {
-                    if (kk < 3) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) read_frag(sa, sb, kk + 1, kReadOrder[g * 4 + e], (kk + 1) & 1);
-                    } else if (more1) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) read_frag(slot_ptr(s_a1), slot_ptr(s_b1), 0, kReadOrder[g * 4 + e], 0);
-                    }
+            for (int g = 0; g < 8; ++g) {
+                const int q = ks * 8 + g;
+                if (q == 12) {
+                    if (more2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+                    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                    __builtin_amdgcn_s_barrier();
+                    __builtin_amdgcn_sched_barrier(0);
                 }
 #pragma unroll
-                for (int j = 0; j < 4; ++j)   // B fragment first: the lane's 16 results are C[row lane%32][4 x 4 consecutive columns]
-                    acc[g][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk & 1][j], fa[kk & 1][g], acc[g][j], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);   // keep this load / read / MFMA grouping
+                for (int j = 0; j < 8; ++j) {
+                    // B fragment first: the lane's 4 results are C[row lane%16][4 consecutive columns]
+                    LAGOM_MFMA_16x16x32(acc[g][j], fb[ks][j], fa[ks][g]);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (j == 0) {
+                        if (q < 4) { if (more1) set_m0(l_b1, 4 + q); }
+                        else if (q < 12) { if (more2) set_m0(l_a2, q - 4); }
+                        else { if (more2) set_m0(l_a, q - 12); }
+                    }
+                    if (j == 1) {
+                        if (q < 4) { if (more1) load_m0(g_b1, b_off[4 + q]); }
+                        else if (q < 12) { if (more2) load_m0(g_a2, a_off[q - 4]); }
+                        else { if (more2) load_m0(g_b2, b_off[q - 12]); }
+                    }
+                    if (ks == 0) {
+                        if (j == 3) read_frag(sa, sb, 1, kReadOrder[2 * g], 1);
+                        if (j == 5) read_frag(sa, sb, 1, kReadOrder[2 * g + 1], 1);
+                    } else if (more1 && g >= 4) {
+                        if (j & 1) read_frag(sa1, sb1, 0, kReadOrder[(g - 4) * 4 + (j >> 1)], 0);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
         }
         s_a = s_a1;
@@ -337,58 +367,77 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
     for (; kt + 2 < ksteps; ++kt) step(kt, std::true_type{}, std::true_type{});
     if (kt + 1 < ksteps) { step(kt, std::true_type{}, std::false_type{}); ++kt; }
     if (kt < ksteps) step(kt, std::false_type{}, std::false_type{});
+    // The compiler does not see an MFMA inside the asm statements and therefore adds none of the wait
+    // states an accumulator read needs after one: give the last results their cycles here, and make
+    // every later use of an accumulator depend on a statement that follows these cycles.
+    asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) asm volatile("" : "+a"(acc[i][j]));
     __builtin_amdgcn_s_barrier();   // every wavefront is past its last LDS read before the slots are reused below
 
-    // acc[i][j][v]: row i*32 + lane%32, column j*32 + 8*(v/4) + 4*(lane/32) + v%4 of the wavefront's 128 x 128 block
-    const int r_in = lane & 31, c_half = 4 * (lane >> 5);
-    if (OUT_BF16 && (N & 7) == 0) {
-        // stage the block as bf16 rows of 256 bytes (sixteen 16-byte groups, group c stored at c ^ (row & 15))
-        char* st = reinterpret_cast<char*>(smem) + wave * (128 * 256);
+    // Epilogue.  acc[i][j][v] is row 16*i + lane%16, column 16*j + 4*(lane/16) + v of the wavefront's
+    // 128 x 128 block.  The block is staged in the wavefront's own 32 KiB of LDS as rows of ROW_BYTES
+    // (16-byte group c of row r stored at c ^ (r & 15)) and written out as 16-byte vectors, whole rows
+    // of the block contiguous: all 128 rows at once for bf16, 64 rows per pass for fp32.  A wavefront
+    // reads back only what it wrote itself, and LDS serves one wavefront's accesses in order, so the
+    // passes need no waits between them beyond the data dependencies.
+    constexpr int ESZ = OUT_BF16 ? 2 : 4;
+    constexpr int PASSES = OUT_BF16 ? 1 : 2;
+    constexpr int ROW_BYTES = 128 * ESZ, GROUPS = ROW_BYTES / 16, ROWS_PER_READ = 64 / GROUPS, VEC = 16 / ESZ;
+    const int r_in = lane & 15, c_q = 4 * (lane >> 4);
+    char* st = reinterpret_cast<char*>(smem) + wave * SLOT_BYTES;
+    const bool interior = m0 + BM <= M && n0 + BN <= N;
+    const bool vector_ok = (N % VEC) == 0;
+    const int rd_row = lane / GROUPS, rd_cv = lane % GROUPS;
+    const int64_t gcol = n0 + wn * 128 + rd_cv * VEC;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+    for (int pass = 0; pass < PASSES; ++pass) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+        for (int ii = 0; ii < 8 / PASSES; ++ii)
 #pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const int r = i * 32 + r_in;
-                    const int c = j * 32 + 8 * b + c_half;          // first of four consecutive columns
-                    const bf16x2 lo = __builtin_convertvector(f32x2{acc[i][j][4 * b], acc[i][j][4 * b + 1]}, bf16x2);
-                    const bf16x2 hi = __builtin_convertvector(f32x2{acc[i][j][4 * b + 2], acc[i][j][4 * b + 3]}, bf16x2);
+            for (int j = 0; j < 8; ++j) {
+                const int i = pass * (8 / PASSES) + ii;
+                const int r = ii * 16 + r_in;
+                const int cb = (j * 16 + c_q) * ESZ;          // byte offset of the first of four consecutive columns
+                char* dst = st + r * ROW_BYTES + (((cb >> 4) ^ (r & 15)) << 4) + (cb & 15);
+                if (OUT_BF16) {
+                    const bf16x2 lo = __builtin_convertvector(f32x2{acc[i][j][0], acc[i][j][1]}, bf16x2);
+                    const bf16x2 hi = __builtin_convertvector(f32x2{acc[i][j][2], acc[i][j][3]}, bf16x2);
                     uint2 v;
                     v.x = __builtin_bit_cast(uint32_t, lo);
                     v.y = __builtin_bit_cast(uint32_t, hi);
-                    *reinterpret_cast<uint2*>(st + r * 256 + (((c >> 3) ^ (r & 15)) << 4) + ((c & 7) << 1)) = v;
+                    *reinterpret_cast<uint2*>(dst) = v;
+                } else {
+                    *reinterpret_cast<f32x4*>(dst) = acc[i][j];
                 }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // own writes only: a wavefront reads back its own block
-#pragma unroll 4
-        for (int t = 0; t < 32; ++t) {
-            const int r = (lane >> 4) + 4 * t, cv = lane & 15;
-            const u32x4 val = *reinterpret_cast<const u32x4*>(st + r * 256 + ((cv ^ (r & 15)) << 4));
-            const int64_t grow = m0 + wm * 128 + r, gcol = n0 + wn * 128 + cv * 8;
-            if (grow < M && gcol < N) *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(p.C) + grow * N + gcol) = val;
+            }
+        const int64_t row0 = m0 + wm * 128 + pass * (128 / PASSES) + rd_row;
+#pragma unroll
+        for (int tb = 0; tb < 4; ++tb) {   // eight reads in flight, then eight stores
+            u32x4 val[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int r = rd_row + ROWS_PER_READ * (tb * 8 + e);
+                val[e] = *reinterpret_cast<const u32x4*>(st + r * ROW_BYTES + ((rd_cv ^ (r & 15)) << 4));
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int64_t grow = row0 + ROWS_PER_READ * (tb * 8 + e);
+                char* out = reinterpret_cast<char*>(p.C) + (grow * N + gcol) * ESZ;
+                if (vector_ok) {
+                    if (interior || (grow < M && gcol < N)) *reinterpret_cast<u32x4*>(out) = val[e];
+                } else if (grow < M) {
+#pragma unroll
+                    for (int k = 0; k < VEC; ++k)
+                        if (gcol + k < N) {
+                            if (OUT_BF16) reinterpret_cast<uint16_t*>(out)[k] = (uint16_t)(val[e][k >> 1] >> (16 * (k & 1)));
+                            else reinterpret_cast<uint32_t*>(out)[k] = val[e][k];
+                        }
+                }
+            }
         }
-    } else {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const int64_t row = m0 + wm * 128 + i * 32 + r_in;
-                    const int64_t col = n0 + wn * 128 + j * 32 + 8 * b + c_half;
-                    if (row >= M) continue;
-                    if (!OUT_BF16 && (N & 3) == 0 && col + 4 <= N) {
-                        *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(p.C) + row * N + col) =
-                            f32x4{acc[i][j][4 * b], acc[i][j][4 * b + 1], acc[i][j][4 * b + 2], acc[i][j][4 * b + 3]};
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (col + e < N) {
-                                if (OUT_BF16) reinterpret_cast<uint16_t*>(p.C)[row * N + col + e] = (uint16_t)bf16_round_bits(acc[i][j][4 * b + e]);
-                                else reinterpret_cast<float*>(p.C)[row * N + col + e] = acc[i][j][4 * b + e];
-                            }
-                    }
-                }
     }
 }
 
@@ -436,7 +485,7 @@ extern "C" int lagom_gemm(const void* A, const void* B, void* C, int64_t M, int6
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const dim3 grid((unsigned)tiles), block(THREADS);
     const bool bf = out_dt == LAGOM_BF16;
-    if (b_is_nk && K % BK == 0) {
+    if (b_is_nk && K % BK == 0 && K <= FAST_MAX_K) {
         if (int rc = bf ? launch_fast<true>(a, grid, st) : launch_fast<false>(a, grid, st)) return rc;
     } else if (b_is_nk) {
         if (bf) hipLaunchKernelGGL((gemm_bf16_general_kernel<true, true>), grid, block, 0, st, a);
