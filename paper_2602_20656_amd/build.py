@@ -48,6 +48,14 @@ def build(verbose: bool = True) -> str:
     return LIB
 
 
+def device_assembly(src: str, out_dir: str) -> str:
+    """Device-side gfx950 assembly of one kernel source, with the flags of the library build."""
+    out = os.path.join(out_dir, os.path.basename(src) + ".gfx950.s")
+    cmd = [HIPCC] + COMMON + DEVICE + ["--offload-device-only", "-S", os.path.join(CSRC, src), "-o", out]
+    subprocess.run(cmd, check=True, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    return out
+
+
 if __name__ == "__main__":
     build()
     sys.exit(0)

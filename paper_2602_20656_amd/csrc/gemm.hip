@@ -269,6 +269,7 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
     };
     // main-loop form in two halves, one MFMA apart (which also is the wait state M0 needs before the load)
     auto set_m0 = [&](uint32_t slot_base, int d) { asm volatile("s_add_i32 m0, %0, %1" ::"s"(slot_base), "n"(d * 4096) : "memory"); };
+    // (no immediate offset: the hardware would add it to the LDS address as well)
     auto load_m0 = [&](const char* sbase, uint32_t voff) { asm volatile("global_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase) : "memory"); };
     auto slot_ptr = [&](int slot) -> u32x4* { return smem + slot * TILE_SLOTS; };
 
@@ -303,7 +304,7 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
     // MORE1 / MORE2: tiles kt+1 / kt+2 exist (compile-time, so that the steady-state loop has no
     // branches; the last two K-steps are peeled).  Every MFMA is followed by at most one other
     // instruction, which issues while the matrix core works on that MFMA:
-    //   loads   one per group, M0 after the group's first MFMA and the load after its second:
+    //   loads   one per group, M0 after the group's first MFMA and the load after its third:
     //           groups 0-3 second half of B(kt+1); 4-11 A(kt+2) into the fifth slot; 12-15 first half
     //           of B(kt+2) into the slot A(kt) has just left.
     //   reads   slice 0: two fragments of slice 1 per group; slice 1, groups 4-7: four fragments per
@@ -312,18 +313,22 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
     //           registers and tile kt+1 has landed (the 8 youngest loads, A(kt+2), may still fly), so
     //           after the barrier tile kt's slots are free and tile kt+1 may be read.
     constexpr int kReadOrder[16] = {0, 8, 9, 10, 11, 12, 13, 14, 15, 1, 2, 3, 4, 5, 6, 7};   // A0, B0..B7, A1..A7
-    int s_a = 0;   // slot of A(kt); B(kt), A(kt+1), B(kt+1), A(kt+2) follow at +1..+4 modulo 5
-    auto step = [&](int64_t kt, auto more1_c, auto more2_c) {
+    // Byte offsets of the slots of A(kt), B(kt), A(kt+1), B(kt+1), A(kt+2).  Advancing by one K-step moves
+    // every role two slots along a ring of five, which is a pure rotation of these five values.
+    uint32_t o_a = 0, o_b = SLOT_BYTES, o_a1 = 2 * SLOT_BYTES, o_b1 = 3 * SLOT_BYTES, o_a2 = 4 * SLOT_BYTES;
+    const char* g_a = base_a + 2 * (BK * 2);   // &A[m0][(kt+2)*64]
+    const char* g_b = base_b + BK * 2;         // &B[n0][(kt+1)*64]; tile kt+2 of B is reached through b_off_next
+    uint32_t b_off_next[4];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) b_off_next[d] = b_off[d] + BK * 2;
+    const char* smem_bytes = reinterpret_cast<const char*>(smem);
+    auto step = [&](auto more1_c, auto more2_c) {
         constexpr bool more1 = decltype(more1_c)::value, more2 = decltype(more2_c)::value;
-        const int s_b = (s_a + 1) % LDS_SLOTS, s_a1 = (s_a + 2) % LDS_SLOTS, s_b1 = (s_a + 3) % LDS_SLOTS, s_a2 = (s_a + 4) % LDS_SLOTS;
-        const u32x4* sa = slot_ptr(s_a);
-        const u32x4* sb = slot_ptr(s_b);
-        const u32x4* sa1 = slot_ptr(s_a1);
-        const u32x4* sb1 = slot_ptr(s_b1);
-        const uint32_t l_b1 = lds0 + s_b1 * SLOT_BYTES, l_a2 = lds0 + s_a2 * SLOT_BYTES, l_a = lds0 + s_a * SLOT_BYTES;
-        const char* g_b1 = base_b + (kt + 1) * (BK * 2);
-        const char* g_a2 = base_a + (kt + 2) * (BK * 2);
-        const char* g_b2 = base_b + (kt + 2) * (BK * 2);
+        const u32x4* sa = reinterpret_cast<const u32x4*>(smem_bytes + o_a);
+        const u32x4* sb = reinterpret_cast<const u32x4*>(smem_bytes + o_b);
+        const u32x4* sa1 = reinterpret_cast<const u32x4*>(smem_bytes + o_a1);
+        const u32x4* sb1 = reinterpret_cast<const u32x4*>(smem_bytes + o_b1);
+        const uint32_t l_b1 = lds0 + o_b1, l_a2 = lds0 + o_a2, l_a = lds0 + o_a;
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
 #pragma unroll
@@ -346,10 +351,10 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
                         else if (q < 12) { if (more2) set_m0(l_a2, q - 4); }
                         else { if (more2) set_m0(l_a, q - 12); }
                     }
-                    if (j == 1) {
-                        if (q < 4) { if (more1) load_m0(g_b1, b_off[4 + q]); }
-                        else if (q < 12) { if (more2) load_m0(g_a2, a_off[q - 4]); }
-                        else { if (more2) load_m0(g_b2, b_off[q - 12]); }
+                    if (j == 2) {
+                        if (q < 4) { if (more1) load_m0(g_b, b_off[4 + q]); }
+                        else if (q < 12) { if (more2) load_m0(g_a, a_off[q - 4]); }
+                        else { if (more2) load_m0(g_b, b_off_next[q - 12]); }
                     }
                     if (ks == 0) {
                         if (j == 3) read_frag(sa, sb, 1, kReadOrder[2 * g], 1);
@@ -361,12 +366,16 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
                 }
             }
         }
-        s_a = s_a1;
+        const uint32_t t_a = o_a, t_b = o_b;
+        o_a = o_a1; o_b = o_b1; o_a1 = o_a2; o_b1 = t_a; o_a2 = t_b;
+        g_a += BK * 2;
+        g_b += BK * 2;
     };
-    int64_t kt = 0;
-    for (; kt + 2 < ksteps; ++kt) step(kt, std::true_type{}, std::true_type{});
-    if (kt + 1 < ksteps) { step(kt, std::true_type{}, std::false_type{}); ++kt; }
-    if (kt < ksteps) step(kt, std::false_type{}, std::false_type{});
+    int kt = 0;
+    const int nk = (int)ksteps;
+    for (; kt + 2 < nk; ++kt) step(std::true_type{}, std::true_type{});
+    if (kt + 1 < nk) { step(std::true_type{}, std::false_type{}); ++kt; }
+    if (kt < nk) step(std::false_type{}, std::false_type{});
     // The compiler does not see an MFMA inside the asm statements and therefore adds none of the wait
     // states an accumulator read needs after one: give the last results their cycles here, and make
     // every later use of an accumulator depend on a statement that follows these cycles.
