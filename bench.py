@@ -26,9 +26,9 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 BF16_PEAK_TFLOPS = 2500.0       # MI355X dense bf16 MFMA, published
 LAMBDA = 256                    # compute units
 # Bytes past L2 per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by the same counters' reading of a plain
-# 64 MiB copy (factors 1.9985 and 0.9990); figures and commands: profiles/bench_dp_bucket_hbm_counters.md
+# 64 MiB copy (factors 1.9984 and 0.9992); figures and commands: profiles/bench_dp_bucket_hbm_counters.md
 MEASURED_TRAFFIC_BYTES = {
-    "gemm 4096x4096x4096": int(225.1 * (1 << 20)),
+    "gemm 4096x4096x4096": int(224.2 * (1 << 20)),
     "reduce_copy bf16 S=8 D=1 count=4194304": int(72.0 * (1 << 20)),
     "reduce_copy f32 S=2 D=1 count=4194304": int(48.0 * (1 << 20)),
 }
