@@ -436,7 +436,7 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
                 const int64_t grow = row0 + ROWS_PER_READ * (tb * 8 + e);
                 char* out = reinterpret_cast<char*>(p.C) + (grow * N + gcol) * ESZ;
                 if (vector_ok) {
-                    if (interior || (grow < M && gcol < N)) *reinterpret_cast<u32x4*>(out) = val[e];
+                    if (interior || (grow < M && gcol < N)) __builtin_nontemporal_store(val[e], reinterpret_cast<u32x4*>(out));
                 } else if (grow < M) {
 #pragma unroll
                     for (int k = 0; k < VEC; ++k)
