@@ -227,6 +227,9 @@ __device__ __forceinline__ int swz64(int row, int cg) { return row * 8 + (cg ^ (
 template <bool OUT_BF16>
 __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p) {
     extern __shared__ u32x4 smem[];   // LDS_SLOTS operand tiles of 2048 16-byte slots
+    // Wavefronts of a communication kernel may share this wavefront's SIMD (this kernel leaves them
+    // registers): let the instruction arbiter prefer the GEMM.
+    __builtin_amdgcn_s_setprio(3);
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
