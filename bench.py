@@ -244,19 +244,30 @@ def main():
     bw = HBM_PEAK_GBPS * 1e3                                     # bytes per microsecond
     y_alone = sweep[0].comp_alone_us / len(comps)
     g0 = -(-geo.mu // (LAMBDA * geo.tb))
-    theta = max(0.0, y_alone / g0 - LAMBDA * geo.tb * geo.d_bytes / bw)
     # the sweep times the communication stream as a whole; a communication's x is its share of the bytes
     share = [sum(b for b, l in zip(nbytes, launches) if l.comm_id == j) / sum(nbytes) for j in range(ncomm)]
     tables = [{p.cfg: (p.comm_corun_us * share[j], min(p.v_corun, 0.99 * bw)) for p in sweep} for j in range(ncomm)]
-    model = lg.Model(LAMBDA, bw, [lg.CompModel(geo.mu, geo.tb, geo.d_bytes, theta) for _ in comps], tables,
-                     comp_after_comm=[i - 1 for i in range(len(comps))] if dependent else None)
+    dep_arg = [i - 1 for i in range(len(comps))] if dependent else None
 
-    # ---- how well Eq. 4-6 reproduce the sweep they were filled from: predicted Y against measured Y, per point
-    errs = []
-    for pt in sweep:
-        pred = lg.lagom_cost_model(model, [pt.cfg] * ncomm)
-        errs.append(abs(pred.Y_us - pt.comp_corun_us) / pt.comp_corun_us)
-    model_y_mape, model_y_max = float(np.mean(errs)), float(np.max(errs))
+    def make_model(d_bytes, sigma):
+        theta = max(0.0, y_alone / g0 - LAMBDA * geo.tb * d_bytes / bw)
+        return lg.Model(LAMBDA, bw, [lg.CompModel(geo.mu, geo.tb, d_bytes, theta) for _ in comps], tables,
+                        comp_after_comm=dep_arg, corun_share=sigma), theta
+
+    def y_errors(mdl):   # predicted Y against the measured Y of every sweep point the model was filled from
+        e = [abs(lg.lagom_cost_model(mdl, [pt.cfg] * ncomm).Y_us - pt.comp_corun_us) / pt.comp_corun_us for pt in sweep]
+        return float(np.mean(e)), float(np.max(e))
+
+    # (1) the model as printed: D = all bytes a workgroup reads and writes, a channel takes a compute unit (Eq. 5)
+    model_printed, theta_printed = make_model(geo.d_bytes, 0.0)
+    printed_mape, printed_max = y_errors(model_printed)
+    # (2) calibrated to this part: D = the bytes that leave the XCD's L2, and the share sigma of a channel's
+    #     compute unit that stays with the GEMM (its wavefronts run beside the GEMM's) fitted to the sweep
+    fits = []
+    for sigma in [i / 8 for i in range(9)]:
+        mdl, th = make_model(geo.d_bytes_past_l2, sigma)
+        fits.append((y_errors(mdl), sigma, mdl, th))
+    (model_y_mape, model_y_max), sigma_fit, model, theta = min(fits, key=lambda f: f[0][0])
 
     # ---- the search: Alg. 1/2 with measured profiles, and with the model as ProfileTime
     nt_grid = list(w.nt_grid) if len(w.nt_grid) > 1 else [256]
@@ -276,6 +287,7 @@ def main():
     tuned = lg.lagom_tune(spaces, lg.OverlapProfile(launches, comps, s_comm, s_comp, 1, args.sweep_iters), lg.LAGOM_PRIORITY)
     tune_s = time.perf_counter() - t0
     tuned_model = lg.lagom_tune(spaces, model, lg.LAGOM_PRIORITY) if ladder_ok else None
+    tuned_printed = lg.lagom_tune(spaces, model_printed, lg.LAGOM_PRIORITY) if ladder_ok else None
     # the communication-bound reference (Eq. 2): per-communication coordinate descent on x_j alone
     comm_cd = lg.lagom_tune(spaces, lg.OverlapProfile(launches, comps, s_comm, s_comp, 1, args.sweep_iters), lg.LAGOM_COMM_OPTIMAL)
 
@@ -294,6 +306,8 @@ def main():
     t_commcd = lg.lagom_overlap_run(launches, comm_cd.cfgs, comps, s_comm, s_comp, args.warmup, args.steps, lg.LAGOM_CORUN)
     t_model = (lg.lagom_overlap_run(launches, tuned_model.cfgs, comps, s_comm, s_comp, args.warmup, args.steps, lg.LAGOM_CORUN)
                if tuned_model else None)
+    t_printed = (lg.lagom_overlap_run(launches, tuned_printed.cfgs, comps, s_comm, s_comp, args.warmup, args.steps, lg.LAGOM_CORUN)
+                 if tuned_printed else None)
 
     # ---- roofline of the dominant kernel (the GEMM), measured live with HIP events on its own stream
     t_gemm = lg.lagom_overlap_run(launches, default_cfgs, comps, s_comm, s_comp, args.warmup, args.steps, lg.LAGOM_ALONE_COMP)
@@ -335,6 +349,11 @@ def main():
         "model_tuned_cfgs": [list(c) for c in tuned_model.cfgs] if tuned_model else None,
         "model_predicted_z_us": lg.lagom_cost_model(model, tuned_model.cfgs).Z_us if tuned_model else None,
         "model_y_mean_abs_rel_err": model_y_mape, "model_y_max_abs_rel_err": model_y_max,
+        "model_corun_share": sigma_fit, "model_d_bytes": geo.d_bytes_past_l2, "model_theta_us": theta,
+        "printed_model_y_mean_abs_rel_err": printed_mape, "printed_model_y_max_abs_rel_err": printed_max,
+        "printed_model_d_bytes": geo.d_bytes, "printed_model_theta_us": theta_printed,
+        "z_printed_model_tuned_us": t_printed.Z_us if t_printed else None,
+        "printed_model_predicted_z_us": lg.lagom_cost_model(model_printed, tuned_printed.cfgs).Z_us if tuned_printed else None,
         "tune_profile_calls": tuned.calls, "tune_seconds": tune_s, "sweep_points": len(points), "sweep_seconds": sweep_s,
         "gemm_alone_us": gemm_us, "gemm_mfma_util": tflops / BF16_PEAK_TFLOPS,
         "gemm_slowdown_default": t_default.Y_us / t_gemm.Y_us, "gemm_slowdown_tuned": t_tuned.Y_us / t_gemm.Y_us,

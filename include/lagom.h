@@ -96,6 +96,10 @@ typedef struct {
     int32_t tb;
     double  d_bytes;
     int32_t tile_m, tile_n, tile_k, threads;
+    double  d_bytes_past_l2;    /* estimate of the bytes of d_bytes that leave an XCD's L2: the kernel's
+                                   tile order gives the n (up to 32) workgroups an XCD runs at a time a
+                                   block of r x c tiles that share r A panels and c B panels, so a
+                                   workgroup's share is (r*tile_m + c*tile_n)*K*2/n + tile_m*tile_n*out_size */
 } lagom_gemm_geometry;
 int lagom_gemm_describe(int64_t M, int64_t N, int64_t K, lagom_dtype out_dt, lagom_gemm_geometry* out);
 
@@ -214,6 +218,12 @@ typedef struct {
                                         computation i starts, or -1                              */
     const int32_t* comm_after_comp;  /* host [ncomm]: computation that must have ended before
                                         communication j starts, or -1                            */
+    /* Not in the paper; 0 gives Eq. 5-6 exactly.  Fraction sigma in [0, 1] of a compute unit that
+     * stays available to the computation while a channel runs on it: the workgroups in flight
+     * become floor((lambda - NC*(1 - sigma)) * TB) in Eq. 5 and Eq. 6.  On this part a channel's
+     * wavefronts fit beside the GEMM's on the same compute unit (sigma near 1): the channel then
+     * costs the computation bandwidth (V), not compute units.                                  */
+    double corun_share;
 } lagom_model;
 typedef struct {
     double X_us, Y_us, Z_us;
@@ -224,7 +234,8 @@ typedef struct {
 } lagom_pred;
 
 /* Errors: LAGOM_EINVAL for a null pointer, ncomm != model ncomm, a configuration that
- * is not in its table, NC < 1 or NC >= lambda, V < 0 or V >= B, x < 0, mu < 0, TB < 1. */
+ * is not in its table, NC < 1 or NC >= lambda, V < 0 or V >= B, x < 0, mu < 0, TB < 1,
+ * corun_share outside [0, 1]. */
 int lagom_cost_model(const lagom_model* m, const lagom_cfg* cfgs, int ncomm, lagom_pred* out);
 
 /* ---------------------------------------------------------------------------------

@@ -29,10 +29,17 @@ Readings taken where the text leaves a choice:
   stepping is unchanged, and the makespan is the later of the two stream ends (without
   dependencies that is max(X, Y) again).
 
+* Not in the paper (an adaptation to a part where a communication workgroup can run beside
+  the computation's workgroups on one compute unit): Model.corun_share = sigma in [0, 1] is the
+  fraction of a compute unit that stays available to the computation while a channel runs on
+  it.  The workgroups in flight of Eq. 5 and Eq. 6 become floor((lambda - NC*(1-sigma)) * TB);
+  sigma = 0 (the default) is the paper's model, sigma = 1 leaves only the bandwidth term V.
+
 Units: time in microseconds, bandwidth in bytes per microsecond, D_i in bytes.
 """
 from __future__ import annotations
 
+import math
 from dataclasses import dataclass, field
 from typing import Dict, List, Sequence, Tuple
 
@@ -54,6 +61,7 @@ class Model:
     comps: List[Comp]
     # one table per communication: cfg -> (x microseconds, V bytes/microsecond)
     tables: List[Dict[Cfg, Tuple[float, float]]] = field(default_factory=list)
+    corun_share: float = 0.0       # sigma; 0 = Eq. 5-6 as printed
 
 
 @dataclass
@@ -66,19 +74,28 @@ class Prediction:
     Z: float
 
 
-def wave_count(mu: int, lam: int, nc: int, tb: int) -> int:
+def workgroups_in_flight(lam: int, nc: int, tb: int, share: float = 0.0) -> int:
+    """The divisor of Eq. 5, (lambda - NC) * TB; with a co-run share sigma, floor((lambda - NC*(1-sigma)) * TB)."""
+    if not 0.0 <= share <= 1.0:
+        raise ValueError("co-run share outside [0, 1]")
+    if share == 0.0:
+        return (lam - nc) * tb
+    return int(math.floor((float(lam) - float(nc) * (1.0 - share)) * float(tb)))
+
+
+def wave_count(mu: int, lam: int, nc: int, tb: int, share: float = 0.0) -> int:
     """Eq. 5."""
-    cap = (lam - nc) * tb
+    cap = workgroups_in_flight(lam, nc, tb, share)
     if cap <= 0:
         raise ValueError("communication leaves no compute unit free")
     return -(-mu // cap)
 
 
-def wave_time(theta: float, lam: int, nc: int, tb: int, d_bytes: float, bw_peak: float, v: float) -> float:
+def wave_time(theta: float, lam: int, nc: int, tb: int, d_bytes: float, bw_peak: float, v: float, share: float = 0.0) -> float:
     """Eq. 6."""
     if not v < bw_peak:
         raise ValueError("communication bandwidth reaches the peak")
-    cap = (lam - nc) * tb
+    cap = workgroups_in_flight(lam, nc, tb, share)
     return theta + (cap * d_bytes) / (bw_peak - v)
 
 
@@ -127,8 +144,8 @@ def predict(model: Model, cfgs: Sequence[Cfg], comp_after_comm=None, comm_after_
                     slot = j
                     break
             if slot < N:
-                cap = (model.lam - nc[slot]) * comp.tb
-                f[slot] = wave_time(comp.theta, model.lam, nc[slot], comp.tb, comp.d_bytes, model.bw_peak, v[slot])
+                cap = workgroups_in_flight(model.lam, nc[slot], comp.tb, model.corun_share)
+                f[slot] = wave_time(comp.theta, model.lam, nc[slot], comp.tb, comp.d_bytes, model.bw_peak, v[slot], model.corun_share)
             else:
                 cap = model.lam * comp.tb
                 f[slot] = wave_time(comp.theta, model.lam, 0, comp.tb, comp.d_bytes, model.bw_peak, 0.0)
@@ -196,8 +213,8 @@ def _predict_dependent(model: Model, cfgs: Sequence[Cfg], comp_after_comm, comm_
                             slot = j
                             break
                     if slot < N:
-                        cap = (model.lam - nc[slot]) * comp.tb
-                        f[slot] = wave_time(comp.theta, model.lam, nc[slot], comp.tb, comp.d_bytes, model.bw_peak, v[slot])
+                        cap = workgroups_in_flight(model.lam, nc[slot], comp.tb, model.corun_share)
+                        f[slot] = wave_time(comp.theta, model.lam, nc[slot], comp.tb, comp.d_bytes, model.bw_peak, v[slot], model.corun_share)
                     else:
                         cap = model.lam * comp.tb
                         f[slot] = wave_time(comp.theta, model.lam, 0, comp.tb, comp.d_bytes, model.bw_peak, 0.0)

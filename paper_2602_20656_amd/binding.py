@@ -44,7 +44,8 @@ class lagom_cfg(C.Structure):
 
 class lagom_gemm_geometry(C.Structure):
     _fields_ = [("mu", C.c_int64), ("tb", C.c_int32), ("d_bytes", C.c_double),
-                ("tile_m", C.c_int32), ("tile_n", C.c_int32), ("tile_k", C.c_int32), ("threads", C.c_int32)]
+                ("tile_m", C.c_int32), ("tile_n", C.c_int32), ("tile_k", C.c_int32), ("threads", C.c_int32),
+                ("d_bytes_past_l2", C.c_double)]
 
 
 class lagom_comm_desc(C.Structure):
@@ -84,7 +85,8 @@ class lagom_comp_model(C.Structure):
 class lagom_model(C.Structure):
     _fields_ = [("lambda_", C.c_int32), ("bw_peak", C.c_double), ("comps", C.POINTER(lagom_comp_model)),
                 ("ncomp", C.c_int32), ("tables", C.POINTER(lagom_comm_table)), ("ncomm", C.c_int32),
-                ("comp_after_comm", C.POINTER(C.c_int32)), ("comm_after_comp", C.POINTER(C.c_int32))]
+                ("comp_after_comm", C.POINTER(C.c_int32)), ("comm_after_comp", C.POINTER(C.c_int32)),
+                ("corun_share", C.c_double)]
 
 
 class lagom_pred(C.Structure):
@@ -314,6 +316,7 @@ class Model:
     tables: List[dict] = field(default_factory=list)  # per communication: (nc, nt, chunk) -> (x_us, v)
     comp_after_comm: Optional[Sequence[int]] = None   # per computation: communication it waits for, or -1
     comm_after_comp: Optional[Sequence[int]] = None   # per communication: computation it waits for, or -1
+    corun_share: float = 0.0                          # 0 = Eq. 5-6 as printed; see lagom_model in lagom.h
 
 
 @dataclass
@@ -345,7 +348,8 @@ class _CModel:
         self.c = lagom_model(int(m.lam), float(m.bw_peak), C.cast(self.comps, C.POINTER(lagom_comp_model)), len(m.comps),
                              C.cast(self.tables, C.POINTER(lagom_comm_table)), len(m.tables),
                              C.cast(self.cac, C.POINTER(C.c_int32)) if self.cac is not None else null,
-                             C.cast(self.cap, C.POINTER(C.c_int32)) if self.cap is not None else null)
+                             C.cast(self.cap, C.POINTER(C.c_int32)) if self.cap is not None else null,
+                             float(m.corun_share))
 
 
 def lagom_cost_model(model: Model, cfgs: Sequence[CfgLike]) -> Pred:

@@ -22,6 +22,15 @@ int lookup(const lagom_comm_table& t, const lagom_cfg& c, int j, CommPoint* out)
                        j, c.nc, c.nt, (long long)c.chunk_bytes);
 }
 
+// Workgroups in flight under a communication of NC channels (Eq. 5's divisor): (lambda - NC) * TB, or
+// with a share sigma of every channel's compute unit left to the computation
+// floor((lambda - NC * (1 - sigma)) * TB).
+inline int64_t in_flight(int lambda, int nc, int tb, double sigma) {
+    if (sigma == 0.0) return (int64_t)(lambda - nc) * tb;
+    const double avail = (double)lambda - (double)nc * (1.0 - sigma);
+    return (int64_t)std::floor(avail * (double)tb);
+}
+
 // Eq. 6 with cap = (lambda - NC) * TB workgroups in flight.
 inline double wave_time(double theta, int64_t cap, double d_bytes, double bw_peak, double v) {
     return theta + ((double)cap * d_bytes) / (bw_peak - v);
@@ -36,6 +45,7 @@ extern "C" int lagom_cost_model(const lagom_model* m, const lagom_cfg* cfgs, int
     if (m->ncomp < 0 || (m->ncomp > 0 && !m->comps) || (ncomm > 0 && !m->tables))
         return lagom::fail(LAGOM_EINVAL, "bad model arrays");
     if (m->lambda < 1 || !(m->bw_peak > 0.0)) return lagom::fail(LAGOM_EINVAL, "lambda and peak bandwidth must be positive");
+    if (!(m->corun_share >= 0.0 && m->corun_share <= 1.0)) return lagom::fail(LAGOM_EINVAL, "corun_share must lie in [0, 1]");
 
     const int N = ncomm;
     std::vector<CommPoint> c(N);
@@ -75,7 +85,7 @@ extern "C" int lagom_cost_model(const lagom_model* m, const lagom_cfg* cfgs, int
                     if (t < T[j + 1]) { slot = j; break; }
                 int64_t cap;
                 if (slot < N) {
-                    cap = (int64_t)(m->lambda - c[slot].nc) * cp.tb;
+                    cap = in_flight(m->lambda, c[slot].nc, cp.tb, m->corun_share);
                     f[slot] = wave_time(cp.theta_us, cap, cp.d_bytes, m->bw_peak, c[slot].v);
                 } else {
                     cap = (int64_t)m->lambda * cp.tb;
@@ -143,7 +153,7 @@ extern "C" int lagom_cost_model(const lagom_model* m, const lagom_cfg* cfgs, int
                             if (c_known[j] && cs[j] <= t && t < ce[j]) { slot = j; break; }
                         int64_t cap;
                         if (slot < N) {
-                            cap = (int64_t)(m->lambda - c[slot].nc) * cp.tb;
+                            cap = in_flight(m->lambda, c[slot].nc, cp.tb, m->corun_share);
                             f[slot] = wave_time(cp.theta_us, cap, cp.d_bytes, m->bw_peak, c[slot].v);
                         } else {
                             cap = (int64_t)m->lambda * cp.tb;

@@ -483,6 +483,22 @@ extern "C" int lagom_gemm_describe(int64_t M, int64_t N, int64_t K, lagom_dtype 
     out->tb = 1;   // 256 accumulators per lane fill the AGPR file: one workgroup per compute unit
     out->d_bytes = (double)(BM + BN) * (double)K * 2.0 + (double)BM * BN * lagom::elem_size(out_dt);
     out->tile_m = BM; out->tile_n = BN; out->tile_k = BK; out->threads = THREADS;
+    // the block of tiles an XCD works on at a time under tile_of() (32 compute units per XCD): n tiles in
+    // r tile-rows and c tile-columns need r A panels and c B panels between them
+    const int64_t total = tm * tn;
+    int64_t n, rows, cols;
+    if (total % 8 == 0) {
+        n = total / 8 < 32 ? total / 8 : 32;
+        rows = tm < 8 ? tm : 8;
+        if (rows > n) rows = n;
+        cols = (n + rows - 1) / rows;
+    } else {   // ids are not remapped: an XCD holds every eighth tile of the column-of-8 order
+        n = (total + 7) / 8 < 32 ? (total + 7) / 8 : 32;
+        rows = 1;
+        cols = n;
+    }
+    out->d_bytes_past_l2 = ((double)rows * BM + (double)cols * BN) * (double)K * 2.0 / (double)n +
+                           (double)BM * BN * lagom::elem_size(out_dt);
     return LAGOM_OK;
 }
 

@@ -43,7 +43,7 @@ int main() {
         for (int i = 0; i < M; ++i) cac[i] = (int)(rng() % (std::min(i + 1, N) + 1)) - 1;
         for (int j = 0; j < N; ++j) cap[j] = j == 0 ? -1 : (int)(rng() % (std::min(j, M) + 1)) - 1;
         const bool dep = rep & 1;
-        lagom_model m{256, 8.0e6, comps.data(), M, tab.t.data(), N, dep ? cac.data() : nullptr, dep ? cap.data() : nullptr};
+        lagom_model m{256, 8.0e6, comps.data(), M, tab.t.data(), N, dep ? cac.data() : nullptr, dep ? cap.data() : nullptr, (rep % 3 == 0) ? 0.0 : 0.125 * (double)(rep % 9)};
         std::vector<lagom_cfg> cfgs(N);
         for (auto& c : cfgs) c = lagom_cfg{nc[rng() % nc.size()], nt[rng() % nt.size()], ch[rng() % ch.size()]};
         std::vector<double> x(N), y(M);

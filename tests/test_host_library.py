@@ -35,6 +35,13 @@ def test_host_only_helpers():
     assert g.mu == (8192 // g.tile_m) * (8192 // g.tile_n) and g.tb >= 1
     assert g.d_bytes == (g.tile_m + g.tile_n) * 8192 * 2 + g.tile_m * g.tile_n * 2
     assert lg.lagom_gemm_describe(100, 300, 64).mu == math.ceil(100 / g.tile_m) * math.ceil(300 / g.tile_n)
+    # bytes past an XCD's L2: the 32 tiles an XCD holds at a time form an 8 x 4 block -> A panels shared by 4, B by 8
+    for M, N, K in [(4096, 4096, 4096), (8192, 4096, 4096), (8192, 8192, 8192)]:
+        assert lg.lagom_gemm_describe(M, N, K).d_bytes_past_l2 == (8 * 256 + 4 * 256) * K * 2 / 32 + 256 * 256 * 2
+    small = lg.lagom_gemm_describe(512, 512, 512)          # 4 tiles: nothing is shared
+    assert small.d_bytes_past_l2 == small.d_bytes
+    # 16 x 14 tiles: 28 per XCD at a time, 8 tile-rows x 4 tile-columns (the last one half full)
+    assert lg.lagom_gemm_describe(4096, 3584, 8192).d_bytes_past_l2 == (8 * 256 + 4 * 256) * 8192 * 2 / 28 + 256 * 256 * 2
 
 
 def test_argument_errors_are_reported_before_any_gpu_work():
@@ -90,6 +97,28 @@ def test_cost_model_equals_oracle_bit_for_bit():
         po, pl = ocm.predict(mo, cfgs), lg.lagom_cost_model(ml, cfgs)
         assert pl.x_us == po.x and pl.y_us == po.y and pl.g == po.g
         assert (pl.X_us, pl.Y_us, pl.Z_us) == (po.X, po.Y, po.Z)
+
+
+def test_cost_model_with_a_corun_share_equals_oracle_bit_for_bit(golden_dir):
+    rng = np.random.default_rng(12)
+    for _ in range(300):
+        N, M = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+        mo, ml, cfgs = _random_model(rng, N, M)
+        mo.corun_share = ml.corun_share = float(rng.choice([0.0, 0.125, 0.3, 0.5, 0.77, 1.0, rng.uniform(0, 1)]))
+        po, pl = ocm.predict(mo, cfgs), lg.lagom_cost_model(ml, cfgs)
+        assert pl.x_us == po.x and pl.y_us == po.y and pl.g == po.g
+        assert (pl.X_us, pl.Y_us, pl.Z_us) == (po.X, po.Y, po.Z)
+    fx = json.load(open(os.path.join(golden_dir, "cost_model_worked.json")))
+    for case in fx["corun_share_cases"]:
+        tables = [{(c["nc"], 256, 65536): (c["x"], c["v"])} for c in case["comms"]]
+        model = lg.Model(fx["lambda"], fx["bw_peak"], [lg.CompModel(c["mu"], c["tb"], c["d_bytes"], c["theta"]) for c in case["comps"]],
+                         tables, corun_share=case["corun_share"])
+        p = lg.lagom_cost_model(model, [(c["nc"], 256, 65536) for c in case["comms"]])
+        assert p.y_us == case["y"] and p.g == case["g"] and (p.X_us, p.Y_us, p.Z_us) == (case["X"], case["Y"], case["Z"])
+    for bad in (-0.1, 1.5, float("nan")):
+        with pytest.raises(lg.LagomError) as e:
+            lg.lagom_cost_model(lg.Model(8, 100.0, [lg.CompModel(10, 1, 1.0, 1.0)], [{(2, 64, 64): (1.0, 1.0)}], corun_share=bad), [(2, 64, 64)])
+        assert e.value.code == lg.LAGOM_EINVAL
 
 
 def test_cost_model_on_the_hand_worked_fixture(golden_dir):

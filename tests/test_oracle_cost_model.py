@@ -132,3 +132,38 @@ def test_dependency_cycle_is_rejected():
     model = cm.Model(8, 100.0, [cm.Comp(10, 1, 1.0, 0.5)], [{(2, 64, 64): (5.0, 1.0)}])
     with pytest.raises(ValueError):
         cm.predict(model, [(2, 64, 64)], [0], [0])       # each waits for the other
+
+
+# ------------------------------------------------------------------ co-run share (not in the paper)
+def test_corun_share_hand_worked_fixture(golden_dir):
+    fx = json.load(open(os.path.join(golden_dir, "cost_model_worked.json")))
+    for case in fx["corun_share_cases"]:
+        model, cfgs = _model(fx["lambda"], fx["bw_peak"], case["comps"], case["comms"])
+        model.corun_share = case["corun_share"]
+        p = cm.predict(model, cfgs)
+        assert p.y == case["y"] and p.g == case["g"], case["name"]
+        assert (p.X, p.Y, p.Z) == (case["X"], case["Y"], case["Z"]), case["name"]
+
+
+def test_corun_share_zero_is_the_printed_model_and_one_removes_the_channel_count():
+    lam, bw = 256, 8.0e6
+    for nc, v, mu, tb in itertools.product([1, 8, 32, 200], [0.0, 1.0e6, 7.9e6], [1, 255, 1024, 5000], [1, 2]):
+        comp = cm.Comp(mu, tb, 3.0e6, 12.5)
+        table = {(nc, 256, 4096): (1e12, v)}
+        printed = cm.predict(cm.Model(lam, bw, [comp], [table]), [(nc, 256, 4096)])
+        zero = cm.predict(cm.Model(lam, bw, [comp], [table], corun_share=0.0), [(nc, 256, 4096)])
+        assert (zero.y, zero.g) == (printed.y, printed.g)
+        one = cm.predict(cm.Model(lam, bw, [comp], [table], corun_share=1.0), [(nc, 256, 4096)])
+        g = math.ceil(mu / (lam * tb))                                      # Eq. 5 with no compute unit taken
+        f = 12.5 + lam * tb * 3.0e6 / (bw - v)                              # Eq. 6, bandwidth term only
+        assert one.g[0][0] == g and one.y[0] == pytest.approx(f * g, rel=1e-15)
+        assert cm.workgroups_in_flight(lam, nc, tb, 1.0) == lam * tb
+        # in between, the workgroups in flight grow with the share and stay within the two ends
+        caps = [cm.workgroups_in_flight(lam, nc, tb, s / 8) for s in range(9)]
+        assert caps == sorted(caps) and caps[0] == (lam - nc) * tb and caps[-1] == lam * tb
+
+
+def test_corun_share_out_of_range_is_rejected():
+    for bad in (-0.1, 1.5, float("nan")):
+        with pytest.raises(ValueError):
+            cm.predict(cm.Model(8, 100.0, [cm.Comp(10, 1, 1.0, 1.0)], [{(2, 64, 64): (1.0, 1.0)}], corun_share=bad), [(2, 64, 64)])
