@@ -168,8 +168,8 @@ int lagom_overlap_run(const lagom_comm_desc* launches, int nlaunch,
  */
 typedef struct {
     lagom_cfg cfg;
-    double comm_alone_us, comm_corun_us;     /* X                                       */
-    double comp_alone_us, comp_corun_us;     /* Y                                       */
+    double comm_alone_us, comm_corun_us;     /* X = sum of the x_j (Eq. 1)              */
+    double comp_alone_us, comp_corun_us;     /* Y = sum of the y_i (waits not included) */
     double z_corun_us;
     double v_alone, v_corun;                 /* algorithmic bytes / X, bytes per us     */
 } lagom_sweep_point;
@@ -307,7 +307,8 @@ int lagom_tune(const lagom_tune_space* spaces, int ncomm, lagom_profile_fn profi
 /* Ready-made callbacks for lagom_tune. */
 /* user = const lagom_model*: x_j from the tables, Y from lagom_cost_model.             */
 int lagom_model_profile(void* user, const lagom_cfg* cfgs, int ncomm, double* x_us, double* Y_us);
-/* user = const lagom_overlap_ctx*: one measured co-run of the group (ProfileTime).     */
+/* user = const lagom_overlap_ctx*: one measured co-run of the group (ProfileTime); x_j per
+ * communication and Y = sum of the per-GEMM times y_i, as in Eq. 1.                      */
 typedef struct {
     const lagom_comm_desc* launches; int32_t nlaunch;
     const lagom_gemm_desc* comps;    int32_t ncomp;

@@ -224,10 +224,16 @@ extern "C" int lagom_contention_sweep(const lagom_comm_desc* launches, int nlaun
         bytes += (double)b;
     }
     std::vector<lagom_cfg> cfgs(ncfg, points[0]);
+    // X and Y of a sweep point are the sums of the per-operator times (Eq. 1), so that a wait for the
+    // other stream is not counted as communication or computation time
+    std::vector<double> xj(ncfg), yi(ncomp);
     lagom_timing t{};
+    t.x_us = xj.data();
+    t.y_us = yi.data();
+    auto sum = [](const std::vector<double>& v) { double s = 0.0; for (double e : v) s = s + e; return s; };
     if (int rc = lagom_overlap_run(launches, nlaunch, cfgs.data(), ncfg, comps, ncomp, comm_stream, comp_stream,
                                    warmup, iters, LAGOM_ALONE_COMP, &t)) return rc;
-    const double comp_alone = t.Y_us;
+    const double comp_alone = sum(yi);
     for (int p = 0; p < npoints; ++p) {
         std::fill(cfgs.begin(), cfgs.end(), points[p]);
         lagom_sweep_point& o = out[p];
@@ -235,11 +241,11 @@ extern "C" int lagom_contention_sweep(const lagom_comm_desc* launches, int nlaun
         o.comp_alone_us = comp_alone;
         if (int rc = lagom_overlap_run(launches, nlaunch, cfgs.data(), ncfg, comps, ncomp, comm_stream, comp_stream,
                                        warmup, iters, LAGOM_ALONE_COMM, &t)) return rc;
-        o.comm_alone_us = t.X_us;
+        o.comm_alone_us = sum(xj);
         if (int rc = lagom_overlap_run(launches, nlaunch, cfgs.data(), ncfg, comps, ncomp, comm_stream, comp_stream,
                                        warmup, iters, LAGOM_CORUN, &t)) return rc;
-        o.comm_corun_us = t.X_us;
-        o.comp_corun_us = t.Y_us;
+        o.comm_corun_us = sum(xj);
+        o.comp_corun_us = sum(yi);
         o.z_corun_us = t.Z_us;
         o.v_alone = o.comm_alone_us > 0.0 ? bytes / o.comm_alone_us : 0.0;
         o.v_corun = o.comm_corun_us > 0.0 ? bytes / o.comm_corun_us : 0.0;
@@ -250,11 +256,16 @@ extern "C" int lagom_contention_sweep(const lagom_comm_desc* launches, int nlaun
 extern "C" int lagom_overlap_profile(void* user, const lagom_cfg* cfgs, int ncomm, double* x_us, double* Y_us) {
     if (!user || !cfgs || !x_us || !Y_us) return lagom::fail(LAGOM_EINVAL, "null argument");
     const lagom_overlap_ctx* c = static_cast<const lagom_overlap_ctx*>(user);
+    if (c->ncomp < 0 || c->ncomp > LAGOM_MAX_LAUNCHES) return lagom::fail(LAGOM_EINVAL, "ncomp=%d out of range", c->ncomp);
+    std::vector<double> yi((size_t)c->ncomp);
     lagom_timing t{};
     t.x_us = x_us;
+    t.y_us = yi.data();
     int rc = lagom_overlap_run(c->launches, c->nlaunch, cfgs, ncomm, c->comps, c->ncomp, c->comm_stream, c->comp_stream,
                                c->warmup, c->iters, LAGOM_CORUN, &t);
     if (rc) return rc;
-    *Y_us = t.Y_us;
+    double Y = 0.0;   // Eq. 1: Y is the sum of the y_i (a GEMM's wait for a communication is not computation time)
+    for (double y : yi) Y = Y + y;
+    *Y_us = Y;
     return LAGOM_OK;
 }
