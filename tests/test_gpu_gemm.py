@@ -48,6 +48,16 @@ def test_gemm_small_shapes(M, N, K, b_is_nk, out):
         assert e_fro < 1e-5, e_fro
 
 
+@pytest.mark.parametrize("K", [1 << 22, (1 << 22) + 64])
+def test_gemm_longest_k_of_the_fast_kernel_and_the_first_beyond_it(K):
+    """K = 2^22 is the last K the LDS-direct kernel takes (32-bit lane offsets); the next multiple of 64 goes to the general one."""
+    a = inputs.normal_bf16(2, (2, K)); b = inputs.normal_bf16(3, (3, K), 0.02)
+    ref = og.gemm_f64(a, b, True)
+    for out in ("bf16", "f32"):
+        e_max, e_fro = og.rel_errors(_gemm(a, b, True, out), ref)
+        assert e_max <= GATE and e_fro <= GATE, (K, out, e_max, e_fro)
+
+
 def test_gemm_integer_inputs_are_exact():
     rng = np.random.default_rng(5)
     ai = rng.integers(-4, 5, size=(260, 320)); bi = rng.integers(-4, 5, size=(270, 320))

@@ -102,6 +102,15 @@ def test_cross_stream_dependencies_are_honoured():
     assert same_bits(host(d_sum, np.uint16), want_sum), "the reduce-copy did not wait for the GEMM"
     # the chain is serial: gather -> GEMM -> reduce, so the makespan holds all three
     assert t.Z_us >= 0.98 * (t.x_us[0] + t.y_us[0] + t.x_us[1])
+    # the profiler and the measured ProfileTime report sums of the operators' own times (Eq. 1): the GEMM's wait for
+    # the gather is in the computation stream's span (Y_us of the run) but not in Y of a sweep point or of a profile
+    pt = lg.lagom_contention_sweep(launches, 2, comps, [cfgs[0]], s1, s2, 1, 3)[0]
+    assert pt.comp_corun_us == pytest.approx(t.y_us[0], rel=0.5)
+    two = [lg.GemmDesc(dA, dW, dC, M, N, K, True, lg.LAGOM_BF16), lg.GemmDesc(dA, dW, dC, M, N, K, True, lg.LAGOM_BF16, after_comm_id=0)]
+    t2 = lg.lagom_overlap_run(launches[:1], cfgs[:1], two, s1, s2, 1, 3, lg.LAGOM_CORUN)
+    assert t2.Y_us > 1.15 * (t2.y_us[0] + t2.y_us[1])           # the span holds the second GEMM's wait for the slow gather
+    pt2 = lg.lagom_contention_sweep(launches[:1], 1, two, [cfgs[0]], s1, s2, 1, 3)[0]
+    assert pt2.comp_corun_us < 0.92 * t2.Y_us and pt2.comp_corun_us == pytest.approx(t2.y_us[0] + t2.y_us[1], rel=0.3)
     # a cycle is refused and leaves nothing queued
     cyc_l = [lg.CommLaunch(lg.LAGOM_GATHER_COPY, lg.LAGOM_BF16, d_sh, [dW], N * K // 8, 0, after_comp=0)]
     with pytest.raises(lg.LagomError) as e:
