@@ -225,7 +225,7 @@ def main():
     from paper_2602_20656_amd import binding as lg
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
-    s_comm, s_comp = torch.cuda.Stream(), torch.cuda.Stream()
+    s_comm, s_comp = lg.overlapping_streams()
 
     dependent = args.dependent and args.workload == "fsdp_chain"
     w, launches, comps, ncomm, keep = build_workload(args.workload, dependent)

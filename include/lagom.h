@@ -160,6 +160,14 @@ int lagom_overlap_run(const lagom_comm_desc* launches, int nlaunch,
                       void* comm_stream, void* comp_stream,
                       int warmup, int iters, int mode, lagom_timing* out);
 
+/* Whether kernels enqueued on the two streams can run at the same time.  HIP multiplexes streams
+ * onto a few hardware queues (4 per process by default); two streams that share a queue run their
+ * kernels in submission order, and an overlap measured on them is a serial run.  Probes with two
+ * bounded delay kernels (0.3 ms; 3 ms more before it answers 0) and synchronises both streams.  *overlap = 1 or 0; 0 for
+ * stream_a == stream_b.  lagom_overlap_run(LAGOM_CORUN) makes this check itself and returns
+ * LAGOM_EINVAL for a pair that does not overlap.  Errors: LAGOM_EINVAL (null output), LAGOM_EHIP. */
+int lagom_streams_overlap(void* stream_a, void* stream_b, int* overlap);
+
 /* ---------------------------------------------------------------------------------
  * lagom_contention_sweep -- the contention profiler (the experiment of Fig. 3,
  * Sec. 3.2): for every configuration of a list, applied to all communications of

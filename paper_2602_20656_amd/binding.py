@@ -28,7 +28,7 @@ LAGOM_MAX_SRCS, LAGOM_MAX_DSTS, LAGOM_MAX_LAUNCHES, LAGOM_MAX_COMMS = 16, 4, 256
 
 EXPORTS = ["lagom_strerror", "lagom_last_error", "lagom_comm_kernel", "lagom_gemm", "lagom_gemm_describe",
            "lagom_overlap_run", "lagom_contention_sweep", "lagom_comm_bytes", "lagom_cost_model", "lagom_tune",
-           "lagom_model_profile", "lagom_overlap_profile"]
+           "lagom_model_profile", "lagom_overlap_profile", "lagom_streams_overlap"]
 
 
 class LagomError(RuntimeError):
@@ -144,6 +144,7 @@ def lib() -> C.CDLL:
         L.lagom_contention_sweep.argtypes = [C.POINTER(lagom_comm_desc), C.c_int, C.c_int, C.POINTER(lagom_gemm_desc), C.c_int,
                                              C.POINTER(lagom_cfg), C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int,
                                              C.POINTER(lagom_sweep_point)]
+        L.lagom_streams_overlap.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int)]
         L.lagom_comm_bytes.restype = C.c_int64
         L.lagom_comm_bytes.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int64]
         L.lagom_cost_model.argtypes = [C.POINTER(lagom_model), C.POINTER(lagom_cfg), C.c_int, C.POINTER(lagom_pred)]
@@ -263,6 +264,25 @@ class _Group:
         for i, g in enumerate(comps):
             self.G[i] = lagom_gemm_desc(_ptr(g.A), _ptr(g.B), _ptr(g.C), int(g.M), int(g.N), int(g.K),
                                         1 if g.b_is_nk else 0, int(g.out_dtype), int(g.after_comm_id))
+
+
+def lagom_streams_overlap(stream_a, stream_b) -> bool:
+    out = C.c_int(0)
+    _check(lib().lagom_streams_overlap(C.c_void_p(_stream(stream_a)), C.c_void_p(_stream(stream_b)), C.byref(out)))
+    return bool(out.value)
+
+
+def overlapping_streams(tries: int = 8):
+    """Two torch streams (default priority) on which kernels run at the same time: new streams are drawn
+    until lagom_streams_overlap accepts a pair."""
+    import torch
+    pool = [torch.cuda.Stream()]
+    for _ in range(tries):
+        pool.append(torch.cuda.Stream())
+        for a in pool[:-1]:
+            if lagom_streams_overlap(a, pool[-1]):
+                return a, pool[-1]
+    raise LagomError(LAGOM_EHIP, "no pair of streams on which kernels overlap (is GPU_MAX_HW_QUEUES 1?)")
 
 
 def lagom_overlap_run(launches: Sequence[CommLaunch], cfgs: Sequence[CfgLike], comps: Sequence[GemmDesc],

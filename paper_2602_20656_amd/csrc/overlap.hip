@@ -88,6 +88,39 @@ int validate(const lagom_comm_desc* L, int nlaunch, const lagom_cfg* cfgs, int n
 
 }  // namespace
 
+// Two bounded delay kernels, a long one on stream a and, behind a common event, a short one on
+// stream b: on separate hardware queues the short one ends before the long one does, on a shared
+// queue it cannot start until the long one has ended.  The long kernel has to outlast the host's
+// submission of the short one; a verdict of "shared" is therefore confirmed with a ten times longer one.
+extern "C" int lagom_streams_overlap(void* stream_a, void* stream_b, int* overlap) {
+    if (!overlap) return lagom::fail(LAGOM_EINVAL, "null output");
+    hipStream_t sa = static_cast<hipStream_t>(stream_a), sb = static_cast<hipStream_t>(stream_b);
+    *overlap = 0;
+    if (sa == sb) return LAGOM_OK;
+    int dev = 0, clock_khz = 100000;
+    HIP_TRY(hipGetDevice(&dev));
+    if (hipDeviceGetAttribute(&clock_khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || clock_khz <= 0) clock_khz = 100000;
+    Events E;
+    if (int rc = E.make(3)) return rc;
+    for (const double long_us : {300.0, 3000.0}) {
+        HIP_TRY(hipEventRecord(E.ev[0], sa));
+        HIP_TRY(hipStreamWaitEvent(sb, E.ev[0], 0));
+        hipLaunchKernelGGL(gate_delay_kernel, dim3(1), dim3(64), 0, sa, (long long)(long_us * clock_khz / 1000.0), 1 << 14);
+        HIP_TRY(hipGetLastError());
+        HIP_TRY(hipEventRecord(E.ev[1], sa));
+        hipLaunchKernelGGL(gate_delay_kernel, dim3(1), dim3(64), 0, sb, (long long)(1.0 * clock_khz / 1000.0), 1 << 14);
+        HIP_TRY(hipGetLastError());
+        HIP_TRY(hipEventRecord(E.ev[2], sb));
+        HIP_TRY(hipStreamSynchronize(sa));
+        HIP_TRY(hipStreamSynchronize(sb));
+        float ta = 0.f, tb = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ta, E.ev[0], E.ev[1]));
+        HIP_TRY(hipEventElapsedTime(&tb, E.ev[0], E.ev[2]));
+        if (tb < ta) { *overlap = 1; break; }
+    }
+    return LAGOM_OK;
+}
+
 extern "C" int lagom_overlap_run(const lagom_comm_desc* launches, int nlaunch, const lagom_cfg* cfgs, int ncfg,
                                  const lagom_gemm_desc* comps, int ncomp, void* comm_stream, void* comp_stream,
                                  int warmup, int iters, int mode, lagom_timing* out) {
@@ -97,6 +130,13 @@ extern "C" int lagom_overlap_run(const lagom_comm_desc* launches, int nlaunch, c
     const bool run_comm = mode != LAGOM_ALONE_COMP, run_comp = mode != LAGOM_ALONE_COMM;
     hipStream_t sa = static_cast<hipStream_t>(comm_stream), sb = static_cast<hipStream_t>(comp_stream);
     if (run_comm && run_comp && sa == sb) return lagom::fail(LAGOM_EINVAL, "co-run needs two distinct streams");
+    if (run_comm && run_comp) {
+        int overlap = 0;
+        if (int rc = lagom_streams_overlap(sa, sb, &overlap)) return rc;
+        if (!overlap)
+            return lagom::fail(LAGOM_EINVAL, "kernels on the two streams do not run at the same time (HIP maps streams onto a few "
+                                             "hardware queues and these two share one): pick another pair, see lagom_streams_overlap");
+    }
 
     // launches of one communication form a group; every group and every GEMM gets a start and an end event
     std::vector<int> group_first, group_last, group_id, group_of(ncfg > 0 ? ncfg : 1, -1);

@@ -16,7 +16,8 @@ def tiny():
     A, B = inputs.normal_bf16(2, (512, 512)), inputs.normal_bf16(3, (512, 512))
     d = dict(a=a, b=b, A=A, B=B, da=dev(a), db=dev(b), dout=dev(np.zeros(1 << 20, np.float32)),
              dA=dev(A), dB=dev(B), dC=dev(np.zeros((512, 512), np.uint16)),
-             s1=torch.cuda.Stream(), s2=torch.cuda.Stream())
+             s1=None, s2=None)
+    d["s1"], d["s2"] = lg.overlapping_streams()
     d["launches"] = [lg.CommLaunch(lg.LAGOM_REDUCE_COPY, lg.LAGOM_F32, [d["da"], d["db"]], [d["dout"]], 1 << 20, 0)]
     d["comps"] = [lg.GemmDesc(d["dA"], d["dB"], d["dC"], 512, 512, 512)]
     return d
@@ -34,6 +35,20 @@ def test_corun_keeps_both_results_correct_and_times_are_consistent(tiny):
     for mode, which in [(lg.LAGOM_ALONE_COMM, "X_us"), (lg.LAGOM_ALONE_COMP, "Y_us")]:
         r = lg.lagom_overlap_run(tiny["launches"], [(4, 256, 128 << 10)], tiny["comps"], tiny["s1"], tiny["s2"], 1, 5, mode)
         assert getattr(r, which) > 0
+
+
+def test_streams_that_share_a_hardware_queue_are_detected_and_refused(tiny):
+    assert lg.lagom_streams_overlap(tiny["s1"], tiny["s2"]) and not lg.lagom_streams_overlap(tiny["s1"], tiny["s1"])
+    pool = [torch.cuda.Stream() for _ in range(8)]        # HIP has 4 hardware queues per process by default
+    shared = [(a, b) for i, a in enumerate(pool) for b in pool[i + 1:] if not lg.lagom_streams_overlap(a, b)]
+    if not shared:
+        pytest.skip("every pair of eight streams overlapped")
+    a, b = shared[0]
+    with pytest.raises(lg.LagomError) as e:
+        lg.lagom_overlap_run(tiny["launches"], [(4, 256, 65536)], tiny["comps"], a, b, 0, 1, lg.LAGOM_CORUN)
+    assert e.value.code == lg.LAGOM_EINVAL and "hardware queue" in str(e.value)
+    # the alone modes use one stream only and take any pair
+    assert lg.lagom_overlap_run(tiny["launches"], [(4, 256, 65536)], tiny["comps"], a, b, 0, 1, lg.LAGOM_ALONE_COMM).X_us > 0
 
 
 def test_runner_rejects_bad_groups(tiny):
@@ -85,7 +100,7 @@ def test_cross_stream_dependencies_are_honoured():
     dW = dev(np.zeros(N * K, np.uint16))                       # zeros until the gather has run
     dA, dC = dev(A), dev(np.zeros(M * N, np.uint16))
     d_other, d_sum = dev(other), dev(np.zeros(M * N, np.uint16))
-    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    s1, s2 = lg.overlapping_streams()
     launches = [lg.CommLaunch(lg.LAGOM_GATHER_COPY, lg.LAGOM_BF16, d_sh, [dW], N * K // 8, 0),
                 lg.CommLaunch(lg.LAGOM_REDUCE_COPY, lg.LAGOM_BF16, [dC, d_other], [d_sum], M * N, 1, after_comp=0)]
     comps = [lg.GemmDesc(dA, dW, dC, M, N, K, True, lg.LAGOM_BF16, after_comm_id=0)]
@@ -106,11 +121,14 @@ def test_cross_stream_dependencies_are_honoured():
     # the gather is in the computation stream's span (Y_us of the run) but not in Y of a sweep point or of a profile
     pt = lg.lagom_contention_sweep(launches, 2, comps, [cfgs[0]], s1, s2, 1, 3)[0]
     assert pt.comp_corun_us == pytest.approx(t.y_us[0], rel=0.5)
+    big = [dev(inputs.normal_bf16(400 + p, 1 << 19)) for p in range(8)]          # 8 MiB through one 64-thread channel: ~1 ms
+    d_big = dev(np.zeros(8 << 19, np.uint16))
+    slow = [lg.CommLaunch(lg.LAGOM_GATHER_COPY, lg.LAGOM_BF16, big, [d_big], 1 << 19, 0)]
     two = [lg.GemmDesc(dA, dW, dC, M, N, K, True, lg.LAGOM_BF16), lg.GemmDesc(dA, dW, dC, M, N, K, True, lg.LAGOM_BF16, after_comm_id=0)]
-    t2 = lg.lagom_overlap_run(launches[:1], cfgs[:1], two, s1, s2, 1, 3, lg.LAGOM_CORUN)
-    assert t2.Y_us > 1.15 * (t2.y_us[0] + t2.y_us[1])           # the span holds the second GEMM's wait for the slow gather
-    pt2 = lg.lagom_contention_sweep(launches[:1], 1, two, [cfgs[0]], s1, s2, 1, 3)[0]
-    assert pt2.comp_corun_us < 0.92 * t2.Y_us and pt2.comp_corun_us == pytest.approx(t2.y_us[0] + t2.y_us[1], rel=0.3)
+    t2 = lg.lagom_overlap_run(slow, cfgs[:1], two, s1, s2, 1, 3, lg.LAGOM_CORUN)
+    assert t2.Y_us > 5 * (t2.y_us[0] + t2.y_us[1])              # the span holds the second GEMM's wait for the slow gather
+    pt2 = lg.lagom_contention_sweep(slow, 1, two, [cfgs[0]], s1, s2, 1, 3)[0]
+    assert pt2.comp_corun_us < 0.5 * t2.Y_us and pt2.comp_corun_us == pytest.approx(t2.y_us[0] + t2.y_us[1], rel=0.5)
     # a cycle is refused and leaves nothing queued
     cyc_l = [lg.CommLaunch(lg.LAGOM_GATHER_COPY, lg.LAGOM_BF16, d_sh, [dW], N * K // 8, 0, after_comp=0)]
     with pytest.raises(lg.LagomError) as e:
