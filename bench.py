@@ -291,6 +291,30 @@ def main():
     # the communication-bound reference (Eq. 2): per-communication coordinate descent on x_j alone
     comm_cd = lg.lagom_tune(spaces, lg.OverlapProfile(launches, comps, s_comm, s_comp, 1, args.sweep_iters), lg.LAGOM_COMM_OPTIMAL)
 
+    # ---- the first three pairs of the chain: priority search against exhaustive search over the same ladder
+    #      (216 level vectors), with measured profiles and with the calibrated model as ProfileTime
+    first3 = None
+    if args.workload == "fsdp_chain" and ncomm >= 3 and ladder_ok:
+        l3 = [l for l in launches if l.comm_id < 3]
+        c3 = comps[:3]
+        sp3 = [lg.Space(sp.nc[:6], sp.nt, sp.chunk[:6]) for sp in spaces[:3]]
+        prof3 = lg.OverlapProfile(l3, c3, s_comm, s_comp, 1, args.sweep_iters)
+        model3 = lg.Model(model.lam, model.bw_peak, model.comps[:3], model.tables[:3],
+                          comp_after_comm=dep_arg[:3] if dep_arg else None, corun_share=model.corun_share)
+        t0 = time.perf_counter()
+        pr_meas, ex_meas = lg.lagom_tune(sp3, prof3, lg.LAGOM_PRIORITY), lg.lagom_tune(sp3, prof3, lg.LAGOM_EXHAUSTIVE)
+        first3_s = time.perf_counter() - t0
+        pr_mod, ex_mod = lg.lagom_tune(sp3, model3, lg.LAGOM_PRIORITY), lg.lagom_tune(sp3, model3, lg.LAGOM_EXHAUSTIVE)
+        run3 = lambda cfgs: lg.lagom_overlap_run(l3, cfgs, c3, s_comm, s_comp, args.warmup, args.steps, lg.LAGOM_CORUN).Z_us
+        first3 = {"ladder_levels": [max(len(sp.nc), len(sp.nt), len(sp.chunk)) for sp in sp3],
+                  "measured": {"priority_cfgs": [list(c) for c in pr_meas.cfgs], "priority_calls": pr_meas.calls,
+                               "exhaustive_cfgs": [list(c) for c in ex_meas.cfgs], "exhaustive_calls": ex_meas.calls,
+                               "z_priority_us": run3(pr_meas.cfgs), "z_exhaustive_us": run3(ex_meas.cfgs), "seconds": first3_s},
+                  "model": {"priority_cfgs": [list(c) for c in pr_mod.cfgs], "priority_calls": pr_mod.calls,
+                            "exhaustive_cfgs": [list(c) for c in ex_mod.cfgs], "exhaustive_calls": ex_mod.calls,
+                            "z_priority_model_us": pr_mod.Z, "z_exhaustive_model_us": ex_mod.Z,
+                            "z_priority_us": run3(pr_mod.cfgs), "z_exhaustive_us": run3(ex_mod.cfgs)}}
+
     # ---- timed region: W warm-up steps, then exactly K steps with the tuned parameters
     default_cfgs = [DEFAULT_CFG] * ncomm
     lg.lagom_overlap_run(launches, tuned.cfgs, comps, s_comm, s_comp, args.warmup, 1, lg.LAGOM_CORUN)
@@ -361,6 +385,8 @@ def main():
         "comm_hbm_gbps": roofline_comm["achieved"],
         "roofline": roofline, "roofline_comm": roofline_comm,
     }
+    if first3 is not None:
+        out["first_three_pairs_priority_vs_exhaustive"] = first3
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.workload)
     if args.dump:
