@@ -385,6 +385,14 @@ def main():
         "comm_hbm_gbps": roofline_comm["achieved"],
         "roofline": roofline, "roofline_comm": roofline_comm,
     }
+    # the compute-bound objective: the swept point with the least GEMM slow-down among those whose communication
+    # still finishes inside the GEMM window (X <= Y)
+    hidden = [p for p in sweep if p.comm_corun_us <= p.comp_corun_us]
+    if hidden:
+        p_min = min(hidden, key=lambda p: p.comp_corun_us)
+        out["min_slowdown_with_comm_hidden"] = {"cfg": list(p_min.cfg), "y_us": p_min.comp_corun_us, "x_us": p_min.comm_corun_us,
+                                                "gemm_slowdown": p_min.comp_corun_us / p_min.comp_alone_us,
+                                                "points_with_comm_hidden": len(hidden)}
     if first3 is not None:
         out["first_three_pairs_priority_vs_exhaustive"] = first3
     if not args.no_cpu_baseline:
