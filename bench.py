@@ -86,6 +86,12 @@ def build_workload(name: str, dependent: bool = False):
         recv = _up(np.zeros(P * m, np_dt))
         keep += [send, recv]
         launches.append(lg.CommLaunch(lg.LAGOM_GATHER_COPY, dt, [b.data_ptr() + rank * m * 2 for b in send], [recv], m, 0))
+    elif name == "tp_pipeline":
+        ncomm = w.ncomm
+        peers = [_up(gen(w.seeds[p], w.comm.count)) for p in range(1, 8)]     # the other ranks' partial outputs of this shard
+        shard_out = [_up(np.zeros(w.comm.count, np_dt)) for _ in range(ncomm)]
+        keep += [peers, shard_out]
+        pipeline_outputs = []                                                  # filled with the GEMM outputs below
     elif name == "rs_ag_pair":
         ncomm = 2
         grads = [_up(gen(w.seeds[p], w.comm.count)) for p in range(8)]
@@ -120,7 +126,15 @@ def build_workload(name: str, dependent: bool = False):
         keep += [B, Cm]
         comps.append(lg.GemmDesc(A, B, Cm, M, N, K, True, lg.LAGOM_BF16,
                                  after_comm_id=i - 1 if (name == "fsdp_chain" and dependent and i > 0) else -1))
-    return w, launches, comps, ncomm, keep
+        if name == "tp_pipeline":      # communication i reduces this rank's first eighth of C_i with the peers' partials
+            launches.append(lg.CommLaunch(lg.LAGOM_REDUCE_COPY, dt, [Cm] + peers, [shard_out[i]], w.comm.count, i, after_comp=i))
+    comp_after_comm = [c.after_comm_id for c in comps] if any(c.after_comm_id >= 0 for c in comps) else None
+    comm_after_comp = None
+    if any(l.after_comp >= 0 for l in launches):
+        comm_after_comp = [-1] * ncomm
+        for l in launches:
+            comm_after_comp[l.comm_id] = max(comm_after_comp[l.comm_id], l.after_comp)
+    return w, launches, comps, ncomm, keep, (comp_after_comm, comm_after_comp)
 
 
 def comm_bytes(launches):
@@ -209,7 +223,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="dp_bucket", choices=["tiny", "dp_bucket", "tp_layer", "fsdp_chain", "compute_bound", "ep_alltoall", "rs_ag_pair"])
+    ap.add_argument("--workload", default="dp_bucket", choices=["tiny", "dp_bucket", "tp_layer", "fsdp_chain", "compute_bound", "ep_alltoall", "rs_ag_pair", "tp_pipeline"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep-iters", type=int, default=5)
     ap.add_argument("--dependent", action="store_true",
@@ -228,7 +242,8 @@ def main():
     s_comm, s_comp = lg.overlapping_streams()
 
     dependent = args.dependent and args.workload == "fsdp_chain"
-    w, launches, comps, ncomm, keep = build_workload(args.workload, dependent)
+    w, launches, comps, ncomm, keep, (dep_arg, dep_comm) = build_workload(args.workload, dependent)
+    dependent = dep_arg is not None or dep_comm is not None
     nbytes = comm_bytes(launches)
     M, N, K = w.gemm
     flops = 2.0 * M * N * K
@@ -247,12 +262,11 @@ def main():
     # the sweep times the communication stream as a whole; a communication's x is its share of the bytes
     share = [sum(b for b, l in zip(nbytes, launches) if l.comm_id == j) / sum(nbytes) for j in range(ncomm)]
     tables = [{p.cfg: (p.comm_corun_us * share[j], min(p.v_corun, 0.99 * bw)) for p in sweep} for j in range(ncomm)]
-    dep_arg = [i - 1 for i in range(len(comps))] if dependent else None
 
     def make_model(d_bytes, sigma):
         theta = max(0.0, y_alone / g0 - LAMBDA * geo.tb * d_bytes / bw)
         return lg.Model(LAMBDA, bw, [lg.CompModel(geo.mu, geo.tb, d_bytes, theta) for _ in comps], tables,
-                        comp_after_comm=dep_arg, corun_share=sigma), theta
+                        comp_after_comm=dep_arg, comm_after_comp=dep_comm, corun_share=sigma), theta
 
     def y_errors(mdl):   # predicted Y against the measured Y of every sweep point the model was filled from
         e = [abs(lg.lagom_cost_model(mdl, [pt.cfg] * ncomm).Y_us - pt.comp_corun_us) / pt.comp_corun_us for pt in sweep]

@@ -6,7 +6,7 @@ PyTorch's own float32 -> bfloat16 conversion.  bf16 arrays are returned as
 ``numpy.uint16`` bit patterns so that the same bytes can be fed to the CPU oracle and
 uploaded to the GPU.
 
-The five workloads mirror the shapes of the overlap patterns the paper studies
+The workloads mirror the shapes of the overlap patterns the paper studies
 (Sec. 2.1: DP/TP AllReduce, FSDP AllGather/ReduceScatter; Fig. 3: one collective
 against one FFN GEMM); the paper prints no tensor shapes, so the sizes below are this
 build's stand-ins for its model workloads.
@@ -113,6 +113,10 @@ WORKLOADS = {
                             (4096, 8192, 2048), 1, _NC, _C, (256,), tuple(range(50, 58))),
     # two communications of different kinds in one overlap (reduce-scatter share, then all-gather) against
     # three GEMMs: which one the search raises first is decided by the metric H
+    # tensor parallelism with batch pipelining: four micro-batches, the reduce-scatter share of micro-batch b
+    # (this rank's partial output + seven peers' partials) waits for GEMM b and overlaps GEMM b+1
+    "tp_pipeline": Workload("tp_pipeline", CommShape("reduce_copy", "bf16", 8, 1, 1835008), 4,
+                            (4096, 3584, 8192), 4, _NC, _C, (256,), tuple(range(80, 88))),
     "rs_ag_pair": Workload("rs_ag_pair", CommShape("reduce_copy", "bf16", 8, 1, 4194304), 2,
                            (8192, 4096, 4096), 3, _NC, _C, (256,), tuple(range(60, 76)), scale=0.02),
 }
