@@ -137,3 +137,29 @@ def test_cross_stream_dependencies_are_honoured():
     torch.cuda.synchronize()
     # alone modes ignore dependencies
     assert lg.lagom_overlap_run(cyc_l, cfgs[:1], comps, s1, s2, 0, 2, lg.LAGOM_ALONE_COMP).Y_us > 0
+
+
+def test_full_size_corun_under_heavy_communication_keeps_both_results():
+    """The benchmark's GEMM (4096^3) next to a 32-channel, 1024-thread eight-source reduce-copy that shares its
+    compute units and its memory system: the GEMM's partial waits on its LDS-direct loads must still hold.
+    GEMM: 64 seeded rows x all columns against the oracle; reduce-copy: bit-exact on sampled ranges."""
+    M = N = K = 4096
+    A, B = inputs.normal_bf16(2, (M, K)), inputs.normal_bf16(3, (N, K), 0.02)
+    count = 4194304
+    shards = [inputs.normal_bf16(20 + p, count) for p in range(8)]
+    dA, dB, dC = dev(A), dev(B), dev(np.zeros(M * N, np.uint16))
+    d_sh, d_out = [dev(x) for x in shards], dev(np.zeros(count, np.uint16))
+    s1, s2 = lg.overlapping_streams()
+    launches = [lg.CommLaunch(lg.LAGOM_REDUCE_COPY, lg.LAGOM_BF16, d_sh, [d_out], count, 0)] * 6    # ~6 x 60 us beside ~100 us of GEMM
+    comps = [lg.GemmDesc(dA, dB, dC, M, N, K)] * 2
+    t = lg.lagom_overlap_run(launches, [(32, 1024, 64 << 10)], comps, s1, s2, 1, 3, lg.LAGOM_CORUN)
+    torch.cuda.synchronize()
+    assert t.X_us > 0.5 * t.Y_us, "the communication was too short to overlap the GEMMs"
+    got = oc.bf16_to_f32(host(dC, np.uint16)).reshape(M, N)
+    rows = np.unique(np.random.default_rng(7).integers(0, M, size=64))
+    e_max, e_fro = og.rel_errors(got[rows], og.gemm_f64(A, B, True, rows=rows))
+    assert e_max <= 2e-2 and e_fro <= 2e-2, (e_max, e_fro)
+    out = host(d_out, np.uint16)
+    for lo in (0, 1 << 20, count - 65536):
+        want = oc.reduce_copy([x[lo:lo + 65536] for x in shards], oc.BF16)[0]
+        assert same_bits(out[lo:lo + 65536], want)
