@@ -300,7 +300,9 @@ def main():
     t0 = time.perf_counter()
     tuned = lg.lagom_tune(spaces, lg.OverlapProfile(launches, comps, s_comm, s_comp, 1, args.sweep_iters), lg.LAGOM_PRIORITY)
     tune_s = time.perf_counter() - t0
+    t0 = time.perf_counter()
     tuned_model = lg.lagom_tune(spaces, model, lg.LAGOM_PRIORITY) if ladder_ok else None
+    model_tune_us = (time.perf_counter() - t0) * 1e6      # host only: Alg. 1/2 with the native cost-model callback (binding marshalling included)
     tuned_printed = lg.lagom_tune(spaces, model_printed, lg.LAGOM_PRIORITY) if ladder_ok else None
     # the communication-bound reference (Eq. 2): per-communication coordinate descent on x_j alone
     comm_cd = lg.lagom_tune(spaces, lg.OverlapProfile(launches, comps, s_comm, s_comp, 1, args.sweep_iters), lg.LAGOM_COMM_OPTIMAL)
@@ -392,6 +394,7 @@ def main():
         "printed_model_d_bytes": geo.d_bytes, "printed_model_theta_us": theta_printed,
         "z_printed_model_tuned_us": t_printed.Z_us if t_printed else None,
         "printed_model_predicted_z_us": lg.lagom_cost_model(model_printed, tuned_printed.cfgs).Z_us if tuned_printed else None,
+        "model_tune_us": model_tune_us if tuned_model else None, "model_tune_profile_calls": tuned_model.calls if tuned_model else None,
         "tune_profile_calls": tuned.calls, "tune_seconds": tune_s, "sweep_points": len(points), "sweep_seconds": sweep_s,
         "gemm_alone_us": gemm_us, "gemm_mfma_util": tflops / BF16_PEAK_TFLOPS,
         "gemm_slowdown_default": t_default.Y_us / t_gemm.Y_us, "gemm_slowdown_tuned": t_tuned.Y_us / t_gemm.Y_us,
