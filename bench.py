@@ -340,6 +340,14 @@ def main():
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     t_default = lg.lagom_overlap_run(launches, default_cfgs, comps, s_comm, s_comp, args.warmup, args.steps, lg.LAGOM_CORUN)
+    # the same K steps once more as a training loop would run them: enqueued back to back, streams joined by events only
+    lg.lagom_overlap_steps(launches, tuned.cfgs, comps, s_comm, s_comp, args.warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    chained_tuned_us = lg.lagom_overlap_steps(launches, tuned.cfgs, comps, s_comm, s_comp, args.steps)
+    torch.cuda.synchronize()
+    chained_wall_ms = (time.perf_counter() - t0) * 1e3
+    chained_default_us = lg.lagom_overlap_steps(launches, default_cfgs, comps, s_comm, s_comp, args.steps)
     best_sweep = min(sweep, key=lambda p: p.z_corun_us)
     comm_opt = min(sweep, key=lambda p: p.comm_alone_us)
     t_commopt = lg.lagom_overlap_run(launches, [comm_opt.cfg] * ncomm, comps, s_comm, s_comp, args.warmup, args.steps, lg.LAGOM_CORUN)
@@ -373,7 +381,8 @@ def main():
         "value": t_default.Z_us / t_tuned.Z_us,
         "unit": "x",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": wall_ms / args.steps,
+        "ms_per_step": chained_wall_ms / args.steps,       # K back-to-back steps with the tuned parameters, host clock between synchronisations
+        "gated_wall_ms_per_step": wall_ms / args.steps,    # the same K steps run one by one behind a start gate (what z_tuned_us is the median of)
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload + ("+dependent" if dependent else ""), "comm": f"{w.comm.op} {w.comm.dtype} S={w.comm.nsrc} count={w.comm.count} "
@@ -381,6 +390,8 @@ def main():
                    "default_cfg": list(DEFAULT_CFG), "tuned_cfgs": [list(c) for c in tuned.cfgs],
                    "ladder_chunk_grids": [list(sp.chunk) for sp in spaces]},
         "z_tuned_us": t_tuned.Z_us, "z_default_us": t_default.Z_us,
+        "chained_us_per_step_tuned": chained_tuned_us, "chained_us_per_step_default": chained_default_us,
+        "chained_speedup": chained_default_us / chained_tuned_us,
         "x_tuned_us": t_tuned.X_us, "y_tuned_us": t_tuned.Y_us, "x_default_us": t_default.X_us, "y_default_us": t_default.Y_us,
         "z_comm_optimal_us": t_commopt.Z_us, "comm_optimal_cfg": list(comm_opt.cfg),
         "z_comm_descent_us": t_commcd.Z_us, "comm_descent_cfgs": [list(c) for c in comm_cd.cfgs], "comm_descent_calls": comm_cd.calls,

@@ -160,6 +160,19 @@ int lagom_overlap_run(const lagom_comm_desc* launches, int nlaunch,
                       void* comm_stream, void* comp_stream,
                       int warmup, int iters, int mode, lagom_timing* out);
 
+/* Sustained rate of an overlap group (the executor path of a training loop): `steps` repetitions of
+ * the group of lagom_overlap_run(LAGOM_CORUN) are enqueued back to back; between repetitions the two
+ * streams wait for each other through events, with no host synchronisation and no start gate, so a
+ * repetition starts when the previous one has ended on both streams while the host is already
+ * enqueueing later ones.  *us_per_step = device time from the start of the first repetition to the
+ * end of the last, divided by steps.  Cross-stream dependencies inside the group are honoured as
+ * in lagom_overlap_run.  Synchronises both streams before it returns.
+ * Errors: as lagom_overlap_run (a pair of streams that does not overlap is LAGOM_EINVAL). */
+int lagom_overlap_steps(const lagom_comm_desc* launches, int nlaunch,
+                        const lagom_cfg* cfgs, int ncfg,
+                        const lagom_gemm_desc* comps, int ncomp,
+                        void* comm_stream, void* comp_stream, int steps, double* us_per_step);
+
 /* Whether kernels enqueued on the two streams can run at the same time.  HIP multiplexes streams
  * onto a few hardware queues (4 per process by default); two streams that share a queue run their
  * kernels in submission order, and an overlap measured on them is a serial run.  Probes with two

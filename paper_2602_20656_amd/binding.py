@@ -28,7 +28,7 @@ LAGOM_MAX_SRCS, LAGOM_MAX_DSTS, LAGOM_MAX_LAUNCHES, LAGOM_MAX_COMMS = 16, 4, 256
 
 EXPORTS = ["lagom_strerror", "lagom_last_error", "lagom_comm_kernel", "lagom_gemm", "lagom_gemm_describe",
            "lagom_overlap_run", "lagom_contention_sweep", "lagom_comm_bytes", "lagom_cost_model", "lagom_tune",
-           "lagom_model_profile", "lagom_overlap_profile", "lagom_streams_overlap"]
+           "lagom_model_profile", "lagom_overlap_profile", "lagom_streams_overlap", "lagom_overlap_steps"]
 
 
 class LagomError(RuntimeError):
@@ -145,6 +145,8 @@ def lib() -> C.CDLL:
                                              C.POINTER(lagom_cfg), C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int,
                                              C.POINTER(lagom_sweep_point)]
         L.lagom_streams_overlap.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int)]
+        L.lagom_overlap_steps.argtypes = [C.POINTER(lagom_comm_desc), C.c_int, C.POINTER(lagom_cfg), C.c_int,
+                                          C.POINTER(lagom_gemm_desc), C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.POINTER(C.c_double)]
         L.lagom_comm_bytes.restype = C.c_int64
         L.lagom_comm_bytes.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int64]
         L.lagom_cost_model.argtypes = [C.POINTER(lagom_model), C.POINTER(lagom_cfg), C.c_int, C.POINTER(lagom_pred)]
@@ -295,6 +297,16 @@ def lagom_overlap_run(launches: Sequence[CommLaunch], cfgs: Sequence[CfgLike], c
     _check(lib().lagom_overlap_run(grp.L, grp.nlaunch, _cfg_array(cfgs), ncfg, grp.G, grp.ncomp,
                                    _stream(comm_stream), _stream(comp_stream), warmup, iters, mode, C.byref(t)))
     return Timing(t.X_us, t.Y_us, t.Z_us, list(x)[:ncfg], list(y)[:grp.ncomp])
+
+
+def lagom_overlap_steps(launches: Sequence[CommLaunch], cfgs: Sequence[CfgLike], comps: Sequence[GemmDesc],
+                        comm_stream, comp_stream, steps: int) -> float:
+    """Device microseconds per repetition of the group over `steps` back-to-back repetitions."""
+    grp = _Group(launches, comps)
+    out = C.c_double(0.0)
+    _check(lib().lagom_overlap_steps(grp.L, grp.nlaunch, _cfg_array(cfgs), len(cfgs), grp.G, grp.ncomp,
+                                     _stream(comm_stream), _stream(comp_stream), int(steps), C.byref(out)))
+    return out.value
 
 
 @dataclass

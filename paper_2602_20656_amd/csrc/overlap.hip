@@ -86,6 +86,81 @@ int validate(const lagom_comm_desc* L, int nlaunch, const lagom_cfg* cfgs, int n
     return LAGOM_OK;
 }
 
+// Launches of one communication form a group; groups and computations are what dependencies name.
+struct GroupPlan {
+    std::vector<int> first, last, id, of;   // per group: first / last launch, comm_id; per comm_id: its group
+    int n = 0;
+    void build(const lagom_comm_desc* launches, int nlaunch, int ncfg) {
+        of.assign(ncfg > 0 ? ncfg : 1, -1);
+        for (int i = 0; i < nlaunch; ++i) {
+            if (i == 0 || launches[i].comm_id != launches[i - 1].comm_id) {
+                of[launches[i].comm_id] = (int)first.size();
+                first.push_back(i); last.push_back(i); id.push_back(launches[i].comm_id);
+            } else {
+                last.back() = i;
+            }
+        }
+        n = (int)first.size();
+    }
+};
+
+// Enqueues one repetition of the group: nl launches on sa, nc computations on sb.  The two enqueue
+// orders are merged so that an awaited event has always been recorded first; a dependency cycle
+// drains both streams and is LAGOM_EINVAL.  ga_start / gb_start may be null (no per-operator timing).
+int enqueue_group(const GroupPlan& plan, const lagom_comm_desc* launches, int nl, const lagom_cfg* cfgs,
+                  const lagom_gemm_desc* comps, int nc, bool deps, hipStream_t sa, hipStream_t sb,
+                  hipEvent_t* ga_start, hipEvent_t* ga_end, hipEvent_t* gb_start, hipEvent_t* gb_end) {
+    std::vector<char> group_done(plan.n > 0 ? plan.n : 1, 0), comp_done(nc > 0 ? nc : 1, 0);
+    int li = 0, ci = 0;
+    while (li < nl || ci < nc) {
+        bool progressed = false;
+        if (li < nl) {
+            const lagom_comm_desc& d = launches[li];
+            const int dep = deps ? d.after_comp : -1;
+            if (dep < 0 || comp_done[dep]) {
+                const int g = plan.of[d.comm_id];
+                if (dep >= 0) HIP_TRY(hipStreamWaitEvent(sa, gb_end[dep], 0));
+                if (ga_start && li == plan.first[g]) HIP_TRY(hipEventRecord(ga_start[g], sa));
+                if (int rc = lagom_comm_kernel((lagom_op)d.op, (lagom_dtype)d.dtype, d.srcs, d.nsrc, d.dsts, d.ndst,
+                                               d.count, &cfgs[d.comm_id], sa)) return rc;
+                if (li == plan.last[g]) { HIP_TRY(hipEventRecord(ga_end[g], sa)); group_done[g] = 1; }
+                ++li;
+                progressed = true;
+            }
+        }
+        if (ci < nc) {
+            const lagom_gemm_desc& c = comps[ci];
+            const int dep = deps ? c.after_comm_id : -1;
+            if (dep < 0 || group_done[plan.of[dep]]) {
+                if (dep >= 0) HIP_TRY(hipStreamWaitEvent(sb, ga_end[plan.of[dep]], 0));
+                if (gb_start) HIP_TRY(hipEventRecord(gb_start[ci], sb));
+                if (int rc = lagom_gemm(c.A, c.B, c.C, c.M, c.N, c.K, c.b_is_nk, (lagom_dtype)c.out_dtype, sb)) return rc;
+                HIP_TRY(hipEventRecord(gb_end[ci], sb));
+                comp_done[ci] = 1;
+                ++ci;
+                progressed = true;
+            }
+        }
+        if (!progressed) {
+            // nothing of this repetition may stay queued: drain, then report
+            (void)hipStreamSynchronize(sa);
+            (void)hipStreamSynchronize(sb);
+            return lagom::fail(LAGOM_EINVAL, "the cross-stream dependencies form a cycle (launch %d, computation %d)", li, ci);
+        }
+    }
+    return LAGOM_OK;
+}
+
+int require_overlap(hipStream_t sa, hipStream_t sb) {
+    if (sa == sb) return lagom::fail(LAGOM_EINVAL, "co-run needs two distinct streams");
+    int overlap = 0;
+    if (int rc = lagom_streams_overlap(sa, sb, &overlap)) return rc;
+    if (!overlap)
+        return lagom::fail(LAGOM_EINVAL, "kernels on the two streams do not run at the same time (HIP maps streams onto a few "
+                                         "hardware queues and these two share one): pick another pair, see lagom_streams_overlap");
+    return LAGOM_OK;
+}
+
 }  // namespace
 
 // Two bounded delay kernels, a long one on stream a and, behind a common event, a short one on
@@ -129,27 +204,14 @@ extern "C" int lagom_overlap_run(const lagom_comm_desc* launches, int nlaunch, c
     if (int rc = validate(launches, nlaunch, cfgs, ncfg, comps, ncomp, mode)) return rc;
     const bool run_comm = mode != LAGOM_ALONE_COMP, run_comp = mode != LAGOM_ALONE_COMM;
     hipStream_t sa = static_cast<hipStream_t>(comm_stream), sb = static_cast<hipStream_t>(comp_stream);
-    if (run_comm && run_comp && sa == sb) return lagom::fail(LAGOM_EINVAL, "co-run needs two distinct streams");
-    if (run_comm && run_comp) {
-        int overlap = 0;
-        if (int rc = lagom_streams_overlap(sa, sb, &overlap)) return rc;
-        if (!overlap)
-            return lagom::fail(LAGOM_EINVAL, "kernels on the two streams do not run at the same time (HIP maps streams onto a few "
-                                             "hardware queues and these two share one): pick another pair, see lagom_streams_overlap");
-    }
+    if (run_comm && run_comp)
+        if (int rc = require_overlap(sa, sb)) return rc;
 
-    // launches of one communication form a group; every group and every GEMM gets a start and an end event
-    std::vector<int> group_first, group_last, group_id, group_of(ncfg > 0 ? ncfg : 1, -1);
-    if (run_comm)
-        for (int i = 0; i < nlaunch; ++i) {
-            if (i == 0 || launches[i].comm_id != launches[i - 1].comm_id) {
-                group_of[launches[i].comm_id] = (int)group_first.size();
-                group_first.push_back(i); group_last.push_back(i); group_id.push_back(launches[i].comm_id);
-            } else {
-                group_last.back() = i;
-            }
-        }
-    const int ngroups = (int)group_first.size();
+    // every group of launches and every GEMM gets a start and an end event
+    GroupPlan plan;
+    if (run_comm) plan.build(launches, nlaunch, ncfg);
+    const int ngroups = plan.n;
+    const std::vector<int>& group_id = plan.id;
     const int ncomp_run = run_comp ? ncomp : 0;
     const bool deps = run_comm && run_comp;        // dependencies only matter when both streams run
     Events E;
@@ -172,54 +234,14 @@ extern "C" int lagom_overlap_run(const lagom_comm_desc* launches, int nlaunch, c
     std::vector<std::vector<double>> xs(ncfg), ys(ncomp);
     std::vector<double> Xs, Ys, Zs;
     hipStream_t gate_stream = run_comm ? sa : sb;
-    std::vector<char> group_done(ngroups > 0 ? ngroups : 1), comp_done(ncomp > 0 ? ncomp : 1);
 
     for (int it = 0; it < warmup + iters; ++it) {
         hipLaunchKernelGGL(gate_delay_kernel, dim3(1), dim3(64), 0, gate_stream, ticks, max_iter);
         HIP_TRY(hipGetLastError());
         HIP_TRY(hipEventRecord(gate, gate_stream));
         if (run_comm && run_comp) HIP_TRY(hipStreamWaitEvent(sb, gate, 0));
-        // The two enqueue orders are merged so that an awaited event has always been recorded first.
-        std::fill(group_done.begin(), group_done.end(), 0);
-        std::fill(comp_done.begin(), comp_done.end(), 0);
-        int li = 0, ci = 0;
-        const int nl = run_comm ? nlaunch : 0;
-        while (li < nl || ci < ncomp_run) {
-            bool progressed = false;
-            if (li < nl) {
-                const lagom_comm_desc& d = launches[li];
-                const int dep = deps ? d.after_comp : -1;
-                if (dep < 0 || comp_done[dep]) {
-                    const int g = group_of[d.comm_id];
-                    if (dep >= 0) HIP_TRY(hipStreamWaitEvent(sa, gb_end[dep], 0));
-                    if (li == group_first[g]) HIP_TRY(hipEventRecord(ga_start[g], sa));
-                    if (int rc = lagom_comm_kernel((lagom_op)d.op, (lagom_dtype)d.dtype, d.srcs, d.nsrc, d.dsts, d.ndst,
-                                                   d.count, &cfgs[d.comm_id], sa)) return rc;
-                    if (li == group_last[g]) { HIP_TRY(hipEventRecord(ga_end[g], sa)); group_done[g] = 1; }
-                    ++li;
-                    progressed = true;
-                }
-            }
-            if (ci < ncomp_run) {
-                const lagom_gemm_desc& c = comps[ci];
-                const int dep = deps ? c.after_comm_id : -1;
-                if (dep < 0 || group_done[group_of[dep]]) {
-                    if (dep >= 0) HIP_TRY(hipStreamWaitEvent(sb, ga_end[group_of[dep]], 0));
-                    HIP_TRY(hipEventRecord(gb_start[ci], sb));
-                    if (int rc = lagom_gemm(c.A, c.B, c.C, c.M, c.N, c.K, c.b_is_nk, (lagom_dtype)c.out_dtype, sb)) return rc;
-                    HIP_TRY(hipEventRecord(gb_end[ci], sb));
-                    comp_done[ci] = 1;
-                    ++ci;
-                    progressed = true;
-                }
-            }
-            if (!progressed) {
-                // nothing of this repetition may stay queued behind the gate: drain, then report
-                (void)hipStreamSynchronize(sa);
-                (void)hipStreamSynchronize(sb);
-                return lagom::fail(LAGOM_EINVAL, "the cross-stream dependencies form a cycle (launch %d, computation %d)", li, ci);
-            }
-        }
+        if (int rc = enqueue_group(plan, launches, run_comm ? nlaunch : 0, cfgs, comps, ncomp_run, deps, sa, sb,
+                                   ga_start, ga_end, gb_start, gb_end)) return rc;
         if (run_comm) HIP_TRY(hipStreamSynchronize(sa));
         if (run_comp) HIP_TRY(hipStreamSynchronize(sb));
         if (it < warmup) continue;
@@ -249,6 +271,48 @@ extern "C" int lagom_overlap_run(const lagom_comm_desc* launches, int nlaunch, c
     out->Z_us = median(Zs);
     if (out->x_us) for (int j = 0; j < ncfg; ++j) out->x_us[j] = median(xs[j]);
     if (out->y_us) for (int i = 0; i < ncomp; ++i) out->y_us[i] = median(ys[i]);
+    return LAGOM_OK;
+}
+
+// Sustained rate of the group: repetitions enqueued back to back, joined through events only.
+extern "C" int lagom_overlap_steps(const lagom_comm_desc* launches, int nlaunch, const lagom_cfg* cfgs, int ncfg,
+                                   const lagom_gemm_desc* comps, int ncomp, void* comm_stream, void* comp_stream,
+                                   int steps, double* us_per_step) {
+    if (!us_per_step) return lagom::fail(LAGOM_EINVAL, "null output");
+    if (steps < 1 || steps > 100000) return lagom::fail(LAGOM_EINVAL, "1 <= steps <= 100000 required");
+    if (int rc = validate(launches, nlaunch, cfgs, ncfg, comps, ncomp, LAGOM_CORUN)) return rc;
+    hipStream_t sa = static_cast<hipStream_t>(comm_stream), sb = static_cast<hipStream_t>(comp_stream);
+    if (int rc = require_overlap(sa, sb)) return rc;
+    GroupPlan plan;
+    plan.build(launches, nlaunch, ncfg);
+    Events E;
+    if (int rc = E.make(4 + plan.n + ncomp)) return rc;
+    hipEvent_t t_start = E.ev[0], t_end = E.ev[1], end_a = E.ev[2], end_b = E.ev[3];
+    hipEvent_t* ga_end = E.ev.data() + 4;
+    hipEvent_t* gb_end = ga_end + plan.n;
+
+    int dev = 0, clock_khz = 100000;
+    HIP_TRY(hipGetDevice(&dev));
+    if (hipDeviceGetAttribute(&clock_khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || clock_khz <= 0) clock_khz = 100000;
+    // a head start for the host: the device begins the first repetition while later ones are still being enqueued
+    hipLaunchKernelGGL(gate_delay_kernel, dim3(1), dim3(64), 0, sa, (long long)(200.0 * clock_khz / 1000.0), 1 << 14);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipEventRecord(t_start, sa));
+    HIP_TRY(hipStreamWaitEvent(sb, t_start, 0));
+    for (int it = 0; it < steps; ++it) {
+        // the events are re-recorded every repetition: a wait refers to the record that preceded it
+        if (int rc = enqueue_group(plan, launches, nlaunch, cfgs, comps, ncomp, true, sa, sb, nullptr, ga_end, nullptr, gb_end)) return rc;
+        HIP_TRY(hipEventRecord(end_a, sa));
+        HIP_TRY(hipEventRecord(end_b, sb));
+        HIP_TRY(hipStreamWaitEvent(sa, end_b, 0));   // the next repetition starts when this one has ended on both streams
+        HIP_TRY(hipStreamWaitEvent(sb, end_a, 0));
+    }
+    HIP_TRY(hipEventRecord(t_end, sa));
+    HIP_TRY(hipStreamSynchronize(sa));
+    HIP_TRY(hipStreamSynchronize(sb));
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, t_start, t_end));
+    *us_per_step = (double)ms * 1000.0 / (double)steps;
     return LAGOM_OK;
 }
 

@@ -163,3 +163,21 @@ def test_full_size_corun_under_heavy_communication_keeps_both_results():
     for lo in (0, 1 << 20, count - 65536):
         want = oc.reduce_copy([x[lo:lo + 65536] for x in shards], oc.BF16)[0]
         assert same_bits(out[lo:lo + 65536], want)
+
+
+def test_back_to_back_steps_keep_results_and_cost_about_one_makespan_each(tiny):
+    cfg = [(4, 256, 128 << 10)]
+    t = lg.lagom_overlap_run(tiny["launches"], cfg, tiny["comps"], tiny["s1"], tiny["s2"], 2, 10, lg.LAGOM_CORUN)
+    per_step = lg.lagom_overlap_steps(tiny["launches"], cfg, tiny["comps"], tiny["s1"], tiny["s2"], 50)
+    torch.cuda.synchronize()
+    assert same_bits(host(tiny["dout"], np.float32), oc.reduce_copy([tiny["a"], tiny["b"]], oc.F32)[0])
+    got = oc.bf16_to_f32(host(tiny["dC"], np.uint16))
+    e_max, e_fro = og.rel_errors(got, og.gemm_f64(tiny["A"], tiny["B"], True))
+    assert e_max <= 2e-2 and e_fro <= 2e-2
+    # a repetition starts when the previous one has ended on both streams: no faster than the longer stream alone,
+    # and not much slower than a gated makespan (joins and launch gaps only)
+    assert per_step >= 0.9 * max(t.x_us[0], t.y_us[0]) and per_step <= 3.0 * t.Z_us
+    with pytest.raises(lg.LagomError):
+        lg.lagom_overlap_steps(tiny["launches"], cfg, tiny["comps"], tiny["s1"], tiny["s1"], 5)
+    with pytest.raises(lg.LagomError):
+        lg.lagom_overlap_steps(tiny["launches"], cfg, tiny["comps"], tiny["s1"], tiny["s2"], 0)
