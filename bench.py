@@ -257,7 +257,7 @@ def main():
     # ---- cost model filled from the sweep: x and V per configuration, theta fitted to the standalone GEMM
     geo = lg.lagom_gemm_describe(M, N, K)
     bw = HBM_PEAK_GBPS * 1e3                                     # bytes per microsecond
-    y_alone = sweep[0].comp_alone_us / len(comps)
+    y_alone = float(np.median([p.comp_alone_us for p in sweep])) / len(comps)
     g0 = -(-geo.mu // (LAMBDA * geo.tb))
     # the sweep times the communication stream as a whole; a communication's x is its share of the bytes
     share = [sum(b for b, l in zip(nbytes, launches) if l.comm_id == j) / sum(nbytes) for j in range(ncomm)]

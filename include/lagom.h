@@ -185,7 +185,8 @@ int lagom_streams_overlap(void* stream_a, void* stream_b, int* overlap);
  * lagom_contention_sweep -- the contention profiler (the experiment of Fig. 3,
  * Sec. 3.2): for every configuration of a list, applied to all communications of
  * the group, time the communications alone, the computations alone (once), and both
- * together, and derive the communication's global-memory bandwidth V (Eq. 6).
+ * together, and derive the communication's global-memory bandwidth V (Eq. 6).  The computations
+ * alone are re-timed every eighth point (the clock held under load drifts over a long sweep).
  */
 typedef struct {
     lagom_cfg cfg;
