@@ -348,6 +348,9 @@ def main():
     torch.cuda.synchronize()
     chained_wall_ms = (time.perf_counter() - t0) * 1e3
     chained_default_us = lg.lagom_overlap_steps(launches, default_cfgs, comps, s_comm, s_comp, args.steps)
+    t0 = time.perf_counter()
+    graph_tuned_us = lg.lagom_overlap_steps_graph(launches, tuned.cfgs, comps, s_comm, s_comp, args.steps)
+    graph_wall_ms = (time.perf_counter() - t0) * 1e3      # includes capture, instantiation and one eager repetition
     best_sweep = min(sweep, key=lambda p: p.z_corun_us)
     comm_opt = min(sweep, key=lambda p: p.comm_alone_us)
     t_commopt = lg.lagom_overlap_run(launches, [comm_opt.cfg] * ncomm, comps, s_comm, s_comp, args.warmup, args.steps, lg.LAGOM_CORUN)
@@ -392,6 +395,7 @@ def main():
         "z_tuned_us": t_tuned.Z_us, "z_default_us": t_default.Z_us,
         "chained_us_per_step_tuned": chained_tuned_us, "chained_us_per_step_default": chained_default_us,
         "chained_speedup": chained_default_us / chained_tuned_us,
+        "graph_us_per_step_tuned": graph_tuned_us, "graph_call_wall_ms": graph_wall_ms,
         "x_tuned_us": t_tuned.X_us, "y_tuned_us": t_tuned.Y_us, "x_default_us": t_default.X_us, "y_default_us": t_default.Y_us,
         "z_comm_optimal_us": t_commopt.Z_us, "comm_optimal_cfg": list(comm_opt.cfg),
         "z_comm_descent_us": t_commcd.Z_us, "comm_descent_cfgs": [list(c) for c in comm_cd.cfgs], "comm_descent_calls": comm_cd.calls,

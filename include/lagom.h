@@ -173,6 +173,16 @@ int lagom_overlap_steps(const lagom_comm_desc* launches, int nlaunch,
                         const lagom_gemm_desc* comps, int ncomp,
                         void* comm_stream, void* comp_stream, int steps, double* us_per_step);
 
+/* As lagom_overlap_steps, replayed from a HIP graph: after one eager repetition, one repetition is
+ * captured from both streams (the computation stream forks from and joins the communication stream
+ * through events) and the graph is launched `steps` times on the communication stream.  The host
+ * enqueues one graph launch per step instead of every kernel.  Neither stream may be capturing when
+ * the call is made; both are synchronised before it returns.  Errors: as lagom_overlap_steps. */
+int lagom_overlap_steps_graph(const lagom_comm_desc* launches, int nlaunch,
+                              const lagom_cfg* cfgs, int ncfg,
+                              const lagom_gemm_desc* comps, int ncomp,
+                              void* comm_stream, void* comp_stream, int steps, double* us_per_step);
+
 /* Whether kernels enqueued on the two streams can run at the same time.  HIP multiplexes streams
  * onto a few hardware queues (4 per process by default); two streams that share a queue run their
  * kernels in submission order, and an overlap measured on them is a serial run.  Probes with two

@@ -28,7 +28,7 @@ LAGOM_MAX_SRCS, LAGOM_MAX_DSTS, LAGOM_MAX_LAUNCHES, LAGOM_MAX_COMMS = 16, 4, 256
 
 EXPORTS = ["lagom_strerror", "lagom_last_error", "lagom_comm_kernel", "lagom_gemm", "lagom_gemm_describe",
            "lagom_overlap_run", "lagom_contention_sweep", "lagom_comm_bytes", "lagom_cost_model", "lagom_tune",
-           "lagom_model_profile", "lagom_overlap_profile", "lagom_streams_overlap", "lagom_overlap_steps"]
+           "lagom_model_profile", "lagom_overlap_profile", "lagom_streams_overlap", "lagom_overlap_steps", "lagom_overlap_steps_graph"]
 
 
 class LagomError(RuntimeError):
@@ -147,6 +147,7 @@ def lib() -> C.CDLL:
         L.lagom_streams_overlap.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int)]
         L.lagom_overlap_steps.argtypes = [C.POINTER(lagom_comm_desc), C.c_int, C.POINTER(lagom_cfg), C.c_int,
                                           C.POINTER(lagom_gemm_desc), C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.POINTER(C.c_double)]
+        L.lagom_overlap_steps_graph.argtypes = L.lagom_overlap_steps.argtypes
         L.lagom_comm_bytes.restype = C.c_int64
         L.lagom_comm_bytes.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int64]
         L.lagom_cost_model.argtypes = [C.POINTER(lagom_model), C.POINTER(lagom_cfg), C.c_int, C.POINTER(lagom_pred)]
@@ -302,9 +303,19 @@ def lagom_overlap_run(launches: Sequence[CommLaunch], cfgs: Sequence[CfgLike], c
 def lagom_overlap_steps(launches: Sequence[CommLaunch], cfgs: Sequence[CfgLike], comps: Sequence[GemmDesc],
                         comm_stream, comp_stream, steps: int) -> float:
     """Device microseconds per repetition of the group over `steps` back-to-back repetitions."""
+    return _steps(lib().lagom_overlap_steps, launches, cfgs, comps, comm_stream, comp_stream, steps)
+
+
+def lagom_overlap_steps_graph(launches: Sequence[CommLaunch], cfgs: Sequence[CfgLike], comps: Sequence[GemmDesc],
+                              comm_stream, comp_stream, steps: int) -> float:
+    """The same, one repetition captured into a HIP graph and replayed `steps` times."""
+    return _steps(lib().lagom_overlap_steps_graph, launches, cfgs, comps, comm_stream, comp_stream, steps)
+
+
+def _steps(fn, launches, cfgs, comps, comm_stream, comp_stream, steps) -> float:
     grp = _Group(launches, comps)
     out = C.c_double(0.0)
-    _check(lib().lagom_overlap_steps(grp.L, grp.nlaunch, _cfg_array(cfgs), len(cfgs), grp.G, grp.ncomp,
+    _check(fn(grp.L, grp.nlaunch, _cfg_array(cfgs), len(cfgs), grp.G, grp.ncomp,
                                      _stream(comm_stream), _stream(comp_stream), int(steps), C.byref(out)))
     return out.value
 

@@ -316,6 +316,66 @@ extern "C" int lagom_overlap_steps(const lagom_comm_desc* launches, int nlaunch,
     return LAGOM_OK;
 }
 
+// The same repetitions replayed from a HIP graph: one repetition is captured from both streams (fork and
+// join through events) and launched `steps` times on the communication stream.
+extern "C" int lagom_overlap_steps_graph(const lagom_comm_desc* launches, int nlaunch, const lagom_cfg* cfgs, int ncfg,
+                                         const lagom_gemm_desc* comps, int ncomp, void* comm_stream, void* comp_stream,
+                                         int steps, double* us_per_step) {
+    if (!us_per_step) return lagom::fail(LAGOM_EINVAL, "null output");
+    if (steps < 1 || steps > 100000) return lagom::fail(LAGOM_EINVAL, "1 <= steps <= 100000 required");
+    if (int rc = validate(launches, nlaunch, cfgs, ncfg, comps, ncomp, LAGOM_CORUN)) return rc;
+    hipStream_t sa = static_cast<hipStream_t>(comm_stream), sb = static_cast<hipStream_t>(comp_stream);
+    if (int rc = require_overlap(sa, sb)) return rc;
+    GroupPlan plan;
+    plan.build(launches, nlaunch, ncfg);
+    Events E;
+    if (int rc = E.make(4 + plan.n + ncomp)) return rc;
+    hipEvent_t t_start = E.ev[0], t_end = E.ev[1], fork = E.ev[2], join = E.ev[3];
+    hipEvent_t* ga_end = E.ev.data() + 4;
+    hipEvent_t* gb_end = ga_end + plan.n;
+
+    // One eager repetition first: kernel attributes are set and code objects loaded outside the capture,
+    // and a dependency cycle is reported here, where the streams may still be synchronised.
+    HIP_TRY(hipEventRecord(fork, sa));
+    HIP_TRY(hipStreamWaitEvent(sb, fork, 0));
+    if (int rc = enqueue_group(plan, launches, nlaunch, cfgs, comps, ncomp, true, sa, sb, nullptr, ga_end, nullptr, gb_end)) return rc;
+    HIP_TRY(hipStreamSynchronize(sa));
+    HIP_TRY(hipStreamSynchronize(sb));
+
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+    HIP_TRY(hipStreamBeginCapture(sa, hipStreamCaptureModeThreadLocal));
+    int rc = LAGOM_OK;
+    hipError_t he = hipEventRecord(fork, sa);
+    if (he == hipSuccess) he = hipStreamWaitEvent(sb, fork, 0);
+    if (he == hipSuccess) rc = enqueue_group(plan, launches, nlaunch, cfgs, comps, ncomp, true, sa, sb, nullptr, ga_end, nullptr, gb_end);
+    if (he == hipSuccess && rc == LAGOM_OK) he = hipEventRecord(join, sb);
+    if (he == hipSuccess && rc == LAGOM_OK) he = hipStreamWaitEvent(sa, join, 0);
+    const hipError_t he_end = hipStreamEndCapture(sa, &graph);      // always: the streams must leave capture mode
+    if (rc != LAGOM_OK) { if (graph) (void)hipGraphDestroy(graph); return rc; }
+    if (he != hipSuccess || he_end != hipSuccess || !graph) {
+        if (graph) (void)hipGraphDestroy(graph);
+        return lagom::fail(LAGOM_EHIP, "graph capture of the overlap group: %s", hipGetErrorString(he != hipSuccess ? he : he_end));
+    }
+    he = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    if (he != hipSuccess) {
+        (void)hipGraphDestroy(graph);
+        return lagom::fail(LAGOM_EHIP, "hipGraphInstantiate: %s", hipGetErrorString(he));
+    }
+    he = hipEventRecord(t_start, sa);
+    for (int it = 0; it < steps && he == hipSuccess; ++it) he = hipGraphLaunch(exec, sa);
+    if (he == hipSuccess) he = hipEventRecord(t_end, sa);
+    const hipError_t hs = hipStreamSynchronize(sa);
+    float ms = 0.f;
+    if (he == hipSuccess && hs == hipSuccess) he = hipEventElapsedTime(&ms, t_start, t_end);
+    (void)hipGraphExecDestroy(exec);
+    (void)hipGraphDestroy(graph);
+    if (he != hipSuccess || hs != hipSuccess)
+        return lagom::fail(LAGOM_EHIP, "graph replay of the overlap group: %s", hipGetErrorString(he != hipSuccess ? he : hs));
+    *us_per_step = (double)ms * 1000.0 / (double)steps;
+    return LAGOM_OK;
+}
+
 extern "C" int lagom_contention_sweep(const lagom_comm_desc* launches, int nlaunch, int ncfg,
                                       const lagom_gemm_desc* comps, int ncomp, const lagom_cfg* points, int npoints,
                                       void* comm_stream, void* comp_stream, int warmup, int iters, lagom_sweep_point* out) {

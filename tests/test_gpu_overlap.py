@@ -181,3 +181,33 @@ def test_back_to_back_steps_keep_results_and_cost_about_one_makespan_each(tiny):
         lg.lagom_overlap_steps(tiny["launches"], cfg, tiny["comps"], tiny["s1"], tiny["s1"], 5)
     with pytest.raises(lg.LagomError):
         lg.lagom_overlap_steps(tiny["launches"], cfg, tiny["comps"], tiny["s1"], tiny["s2"], 0)
+
+
+def test_graph_replay_runs_every_repetition_exactly_once(tiny):
+    """An accumulating reduce-copy (destination = first source) counts the repetitions: after the call's one eager
+    repetition and K replays of the captured graph the buffer holds (K + 1) * b exactly.  Several calls, with eager
+    work and synchronisations between them, as a caller would mix them."""
+    n = 1 << 18
+    b = np.random.default_rng(3).integers(-8, 9, size=n).astype(np.float32)
+    d_acc, d_b = dev(np.zeros(n, np.float32)), dev(b)
+    launches = [lg.CommLaunch(lg.LAGOM_REDUCE_COPY, lg.LAGOM_F32, [d_acc, d_b], [d_acc], n, 0)]
+    cfg = [(4, 256, 64 << 10)]
+    total = 0
+    for K in (1, 3, 7):
+        per_step = lg.lagom_overlap_steps_graph(launches, cfg, tiny["comps"], tiny["s1"], tiny["s2"], K)
+        total += K + 1
+        torch.cuda.synchronize()
+        assert per_step > 0
+        assert np.array_equal(host(d_acc, np.float32), total * b), (K, total)
+        got = oc.bf16_to_f32(host(tiny["dC"], np.uint16))
+        e_max, e_fro = og.rel_errors(got, og.gemm_f64(tiny["A"], tiny["B"], True))
+        assert e_max <= 2e-2 and e_fro <= 2e-2
+        # eager work between the graph calls
+        lg.lagom_overlap_run(launches, cfg, tiny["comps"], tiny["s1"], tiny["s2"], 0, 2, lg.LAGOM_CORUN)
+        total += 2
+        torch.cuda.synchronize()
+        assert np.array_equal(host(d_acc, np.float32), total * b)
+    # the eager back-to-back path counts the same way
+    lg.lagom_overlap_steps(launches, cfg, tiny["comps"], tiny["s1"], tiny["s2"], 5)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(d_acc, np.float32), (total + 5) * b)
