@@ -4,6 +4,7 @@ import json
 import math
 import os
 import re
+import subprocess
 
 import numpy as np
 import pytest
@@ -24,6 +25,14 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(L, name), name
     assert set(lg.EXPORTS) == declared
     assert L.lagom_strerror(lg.LAGOM_EALIGN).decode().startswith("device pointer")
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header compiles as C99 with no extensions and no C++."""
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "lagom.h"\nint main(void) { lagom_cfg c = {1, 64, 16}; lagom_model m; (void)m; return c.nc - 1; }\n')
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    "-c", str(src), "-o", str(tmp_path / "use_header.o")], check=True)
 
 
 def test_host_only_helpers():
