@@ -34,6 +34,8 @@ Readings taken where the text leaves a choice:
   fraction of a compute unit that stays available to the computation while a channel runs on
   it.  The workgroups in flight of Eq. 5 and Eq. 6 become floor((lambda - NC*(1-sigma)) * TB);
   sigma = 0 (the default) is the paper's model, sigma = 1 leaves only the bandwidth term V.
+  Every pin of the printed model runs with sigma = 0; the extension has pins of its own (three
+  pencil-worked cases, the closed forms at both ends).
 
 Units: time in microseconds, bandwidth in bytes per microsecond, D_i in bytes.
 """
