@@ -31,9 +31,6 @@
 //   * The MFMA is issued with the B fragment as first operand, so a lane ends up holding four
 //     consecutive columns of one row of C; results are staged through LDS and written to HBM as
 //     16-byte vectors, whole rows of the wavefront's block contiguous.
-//   * Tile width: 256 columns, or 224 (seven instead of eight MFMA tiles per wavefront along N) when
-//     that needs fewer rounds of 256 workgroups x columns per tile: N = 3584 = 16 x 224 gives
-//     16 x 16 = 256 tiles, one per compute unit, instead of 224 tiles that leave 32 units idle.
 // General kernel (any K multiple of 8, either B layout, v_mfma_f32_32x32x16_bf16): tiles are
 // fetched into registers with bounds checks and zero fill, then stored to LDS; single buffered.
 // Slower; used for ragged K and for B stored [K,N].
@@ -227,12 +224,8 @@ __device__ __forceinline__ int swz64(int row, int cg) { return row * 8 + (cg ^ (
 #define LAGOM_MFMA_16x16x32(ACC, SRC_A, SRC_B) \
     asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(ACC) : "v"(SRC_A), "v"(SRC_B))
 
-// NJ: 16-column MFMA tiles per wavefront along N; the workgroup's tile is 256 x (32 * NJ).  NJ = 8 is the
-// 256 x 256 tile; NJ = 7 gives 256 x 224, used when that fills the 256 compute units better (3584 = 16 x 224
-// columns: 16 x 16 = 256 tiles instead of 16 x 14 = 224).
-template <bool OUT_BF16, int NJ>
+template <bool OUT_BF16>
 __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p) {
-    constexpr int TN = 32 * NJ, WN = 16 * NJ;   // tile and wavefront extent along N
     extern __shared__ u32x4 smem[];   // LDS_SLOTS operand tiles of 2048 16-byte slots
     // Wavefronts of a communication kernel may share this wavefront's SIMD (this kernel leaves them
     // registers): let the instruction arbiter prefer the GEMM.
@@ -243,18 +236,18 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
     const int wm = wave >> 1, wn = wave & 1;
     int tm, tn;
     tile_of(blockIdx.x, p.tiles_m, p.tiles_n, &tm, &tn);
-    const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * TN;
+    const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
     const int64_t M = p.M, N = p.N, K = p.K;
 
-    f32x4 acc[8][NJ];
+    f32x4 acc[8][8];
 #pragma unroll
     for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int j = 0; j < NJ; ++j)
+        for (int j = 0; j < 8; ++j)
 #pragma unroll
             for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.0f;
 
-    // Load instruction d (0..7 for A, 0..NJ-1 for B) of an operand tile fills its 16-byte slots [(d*4+wave)*64, +64):
+    // Load instruction d (0..7) of an operand tile fills its 16-byte slots [(d*4+wave)*64, +64):
     // lane -> row (d*4+wave)*8 + lane/8, stored group lane%8, i.e. source group (lane%8) ^ ((row>>1)&7).
     // (row>>1)&7 does not depend on d because rows of successive d differ by 32.
     // Addresses are a wave-uniform 64-bit base (first row of the tile, advanced along K) plus a 32-bit
@@ -263,12 +256,12 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
     const int scg = (lane & 7) ^ ((srow >> 1) & 7);
     const char* base_a = reinterpret_cast<const char*>(p.A + m0 * K);
     const char* base_b = reinterpret_cast<const char*>(p.B + n0 * K);
-    uint32_t a_off[8], b_off[NJ];
+    uint32_t a_off[8], b_off[8];
 #pragma unroll
     for (int d = 0; d < 8; ++d) {
         const int64_t r = srow + 32 * d, last_a = M - 1 - m0, last_b = N - 1 - n0;
         a_off[d] = (uint32_t)(((r < last_a ? r : last_a) * K + scg * 8) * 2);
-        if (d < NJ) b_off[d] = (uint32_t)(((r < last_b ? r : last_b) * K + scg * 8) * 2);
+        b_off[d] = (uint32_t)(((r < last_b ? r : last_b) * K + scg * 8) * 2);
     }
     // LDS byte address of this wavefront's 1 KiB window of load 0 in slot 0
     const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) char*)smem + wave * 1024;
@@ -288,7 +281,7 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
 #pragma unroll
     for (int d = 0; d < 8; ++d) load_now(base_a, a_off[d], 0, d);
 #pragma unroll
-    for (int d = 0; d < NJ; ++d) load_now(base_b, b_off[d], 1, d);
+    for (int d = 0; d < 8; ++d) load_now(base_b, b_off[d], 1, d);
     if (ksteps > 1) {
 #pragma unroll
         for (int d = 0; d < 8; ++d) load_now(base_a + BK * 2, a_off[d], 2, d);
@@ -301,14 +294,14 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
     __builtin_amdgcn_s_barrier();
 
     // Fragment r of a 32-wide k-slice: lane -> row 16*r + lane%16, 16-byte group 4*slice + lane/16.
-    const int arow = wm * 128 + (lane & 15), brow = wn * WN + (lane & 15), kq = lane >> 4;
-    bf16x8 fa[2][8], fb[2][NJ];
-    auto read_frag = [&](const u32x4* sa, const u32x4* sb, int ks, int r, int buf) {   // r: 0..7 = A0..A7, 8.. = B0..B(NJ-1)
+    const int arow = wm * 128 + (lane & 15), brow = wn * 128 + (lane & 15), kq = lane >> 4;
+    bf16x8 fa[2][8], fb[2][8];
+    auto read_frag = [&](const u32x4* sa, const u32x4* sb, int ks, int r, int buf) {   // r: 0..7 = A0..A7, 8..15 = B0..B7
         if (r < 8) fa[buf][r] = __builtin_bit_cast(bf16x8, sa[swz64(arow + r * 16, ks * 4 + kq)]);
         else fb[buf][r - 8] = __builtin_bit_cast(bf16x8, sb[swz64(brow + (r - 8) * 16, ks * 4 + kq)]);
     };
 #pragma unroll
-    for (int r = 0; r < 8 + NJ; ++r) read_frag(slot_ptr(0), slot_ptr(1), 0, r, 0);
+    for (int r = 0; r < 16; ++r) read_frag(slot_ptr(0), slot_ptr(1), 0, r, 0);
 
     // One K-step = 2 k-slices x 8 groups x 8 MFMAs (group g: A fragment g against the 8 B fragments).
     // MORE1 / MORE2: tiles kt+1 / kt+2 exist (compile-time, so that the steady-state loop has no
@@ -322,10 +315,7 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
     //   barrier in front of group 12: by then this wavefront holds every fragment of tile kt in
     //           registers and tile kt+1 has landed (the 8 youngest loads, A(kt+2), may still fly), so
     //           after the barrier tile kt's slots are free and tile kt+1 may be read.
-    // order in which a slice's 8 + NJ fragments are read: A0, B0..B(NJ-1), A1..A7 (entry 15 is unused for NJ = 7)
-    constexpr int kReadOrder[16] = {0, 8, 9, 10, 11, 12, 13, 14, NJ == 8 ? 15 : 1, NJ == 8 ? 1 : 2, NJ == 8 ? 2 : 3, NJ == 8 ? 3 : 4,
-                                    NJ == 8 ? 4 : 5, NJ == 8 ? 5 : 6, NJ == 8 ? 6 : 7, 7};
-    constexpr int kReads = 8 + NJ;
+    constexpr int kReadOrder[16] = {0, 8, 9, 10, 11, 12, 13, 14, 15, 1, 2, 3, 4, 5, 6, 7};   // A0, B0..B7, A1..A7
     // Byte offsets of the slots of A(kt), B(kt), A(kt+1), B(kt+1), A(kt+2).  Advancing by one K-step moves
     // every role two slots along a ring of five, which is a pure rotation of these five values.
     uint32_t o_a = 0, o_b = SLOT_BYTES, o_a1 = 2 * SLOT_BYTES, o_b1 = 3 * SLOT_BYTES, o_a2 = 4 * SLOT_BYTES;
@@ -355,27 +345,25 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
                     __builtin_amdgcn_sched_barrier(0);
                 }
 #pragma unroll
-                for (int j = 0; j < NJ; ++j) {
+                for (int j = 0; j < 8; ++j) {
                     // B fragment first: the lane's 4 results are C[row lane%16][4 consecutive columns]
                     LAGOM_MFMA_16x16x32(acc[g][j], fb[ks][j], fa[ks][g]);
                     __builtin_amdgcn_sched_barrier(0);
                     if (j == 0) {
-                        if (q < 4) { if (more1 && 4 + q < NJ) set_m0(l_b1, 4 + q); }
+                        if (q < 4) { if (more1) set_m0(l_b1, 4 + q); }
                         else if (q < 12) { if (more2) set_m0(l_a2, q - 4); }
                         else { if (more2) set_m0(l_a, q - 12); }
                     }
                     if (j == 2) {
-                        if (q < 4) { if (more1 && 4 + q < NJ) load_m0(g_b, b_off[4 + q < NJ ? 4 + q : 0]); }
+                        if (q < 4) { if (more1) load_m0(g_b, b_off[4 + q]); }
                         else if (q < 12) { if (more2) load_m0(g_a, a_off[q - 4]); }
                         else { if (more2) load_m0(g_b, b_off_next[q - 12]); }
                     }
                     if (ks == 0) {
                         if (j == 3) read_frag(sa, sb, 1, kReadOrder[2 * g], 1);
-                        if (j == 5 && 2 * g + 1 < kReads) read_frag(sa, sb, 1, kReadOrder[2 * g + 1], 1);
+                        if (j == 5) read_frag(sa, sb, 1, kReadOrder[2 * g + 1], 1);
                     } else if (more1 && g >= 4) {
-                        // four read slots per group: behind MFMA 1, 3, 5 and (NJ = 8) 7 or (NJ = 7) 4
-                        constexpr int kSlot[8] = {-1, 0, -1, 1, NJ == 8 ? -1 : 3, 2, -1, 3};
-                        if (kSlot[j] >= 0 && (g - 4) * 4 + kSlot[j] < kReads) read_frag(sa1, sb1, 0, kReadOrder[(g - 4) * 4 + kSlot[j]], 0);
+                        if (j & 1) read_frag(sa1, sb1, 0, kReadOrder[(g - 4) * 4 + (j >> 1)], 0);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -398,11 +386,11 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
 #pragma unroll
     for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) asm volatile("" : "+a"(acc[i][j]));
+        for (int j = 0; j < 8; ++j) asm volatile("" : "+a"(acc[i][j]));
     __builtin_amdgcn_s_barrier();   // every wavefront is past its last LDS read before the slots are reused below
 
     // Epilogue.  acc[i][j][v] is row 16*i + lane%16, column 16*j + 4*(lane/16) + v of the wavefront's
-    // 128 x WN block (rows are staged with the stride of the 128-column case; the last groups stay unused for NJ = 7).  The block is staged in the wavefront's own 32 KiB of LDS as rows of ROW_BYTES
+    // 128 x 128 block.  The block is staged in the wavefront's own 32 KiB of LDS as rows of ROW_BYTES
     // (16-byte group c of row r stored at c ^ (r & 15)) and written out as 16-byte vectors, whole rows
     // of the block contiguous: all 128 rows at once for bf16, 64 rows per pass for fp32.  A wavefront
     // reads back only what it wrote itself, and LDS serves one wavefront's accesses in order, so the
@@ -412,17 +400,16 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
     constexpr int ROW_BYTES = 128 * ESZ, GROUPS = ROW_BYTES / 16, ROWS_PER_READ = 64 / GROUPS, VEC = 16 / ESZ;
     const int r_in = lane & 15, c_q = 4 * (lane >> 4);
     char* st = reinterpret_cast<char*>(smem) + wave * SLOT_BYTES;
-    const bool interior = m0 + BM <= M && n0 + TN <= N;
+    const bool interior = m0 + BM <= M && n0 + BN <= N;
     const bool vector_ok = (N % VEC) == 0;
     const int rd_row = lane / GROUPS, rd_cv = lane % GROUPS;
-    const int64_t gcol = n0 + wn * WN + rd_cv * VEC;
-    const bool col_used = rd_cv * VEC < WN;      // lanes past the wavefront's columns have nothing to store
+    const int64_t gcol = n0 + wn * 128 + rd_cv * VEC;
 #pragma unroll
     for (int pass = 0; pass < PASSES; ++pass) {
 #pragma unroll
         for (int ii = 0; ii < 8 / PASSES; ++ii)
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) {
+            for (int j = 0; j < 8; ++j) {
                 const int i = pass * (8 / PASSES) + ii;
                 const int r = ii * 16 + r_in;
                 const int cb = (j * 16 + c_q) * ESZ;          // byte offset of the first of four consecutive columns
@@ -451,8 +438,7 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
             for (int e = 0; e < 8; ++e) {
                 const int64_t grow = row0 + ROWS_PER_READ * (tb * 8 + e);
                 char* out = reinterpret_cast<char*>(p.C) + (grow * N + gcol) * ESZ;
-                if (!col_used) {
-                } else if (vector_ok) {
+                if (vector_ok) {
                     if (interior || (grow < M && gcol < N)) __builtin_nontemporal_store(val[e], reinterpret_cast<u32x4*>(out));
                 } else if (grow < M) {
 #pragma unroll
@@ -467,29 +453,14 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
     }
 }
 
-template <bool OUT_BF16, int NJ>
+template <bool OUT_BF16>
 int launch_fast(const GemmArgs& a, dim3 grid, hipStream_t st) {
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_nk_kernel<OUT_BF16, NJ>),
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_nk_kernel<OUT_BF16>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, FAST_LDS_BYTES);
     if (attr != hipSuccess) return lagom::fail(LAGOM_EHIP, "gemm: cannot raise the LDS limit: %s", hipGetErrorString(attr));
-    hipLaunchKernelGGL((gemm_bf16_nk_kernel<OUT_BF16, NJ>), grid, dim3(THREADS), FAST_LDS_BYTES, st, a);
+    hipLaunchKernelGGL((gemm_bf16_nk_kernel<OUT_BF16>), grid, dim3(THREADS), FAST_LDS_BYTES, st, a);
     return LAGOM_OK;
 }
-
-constexpr int kComputeUnits = 256;
-
-// Tile extent along N of the fast kernel: 256, or 224 where that costs less.  Cost = rounds of kComputeUnits
-// workgroups x columns per tile (time per tile is proportional to its columns); ties keep 256.
-int fast_tile_n(int64_t M, int64_t N) {
-    const int64_t tm = (M + BM - 1) / BM;
-    auto cost = [&](int64_t tn_cols) {
-        const int64_t tiles = tm * ((N + tn_cols - 1) / tn_cols);
-        return ((tiles + kComputeUnits - 1) / kComputeUnits) * tn_cols;
-    };
-    return cost(224) < cost(256) ? 224 : 256;
-}
-
-bool fast_path(int64_t K, int b_is_nk) { return b_is_nk && K % BK == 0 && K <= FAST_MAX_K; }
 
 }  // namespace
 
@@ -507,13 +478,11 @@ int check_gemm_args(const void* A, const void* B, const void* C, int64_t M, int6
 
 extern "C" int lagom_gemm_describe(int64_t M, int64_t N, int64_t K, lagom_dtype out_dt, lagom_gemm_geometry* out) {
     if (!out || M < 1 || N < 1 || K < 1 || lagom::elem_size(out_dt) == 0) return lagom::fail(LAGOM_EINVAL, "bad argument");
-    // geometry of the kernel lagom_gemm picks for B stored [N,K]
-    const int64_t tile_n = fast_path(K, 1) ? fast_tile_n(M, N) : BN;
-    const int64_t tm = (M + BM - 1) / BM, tn = (N + tile_n - 1) / tile_n;
+    const int64_t tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
     out->mu = tm * tn;
     out->tb = 1;   // 256 accumulators per lane fill the AGPR file: one workgroup per compute unit
-    out->d_bytes = (double)(BM + tile_n) * (double)K * 2.0 + (double)BM * tile_n * lagom::elem_size(out_dt);
-    out->tile_m = BM; out->tile_n = (int32_t)tile_n; out->tile_k = BK; out->threads = THREADS;
+    out->d_bytes = (double)(BM + BN) * (double)K * 2.0 + (double)BM * BN * lagom::elem_size(out_dt);
+    out->tile_m = BM; out->tile_n = BN; out->tile_k = BK; out->threads = THREADS;
     // the block of tiles an XCD works on at a time under tile_of() (32 compute units per XCD): n tiles in
     // r tile-rows and c tile-columns need r A panels and c B panels between them
     const int64_t total = tm * tn;
@@ -528,8 +497,8 @@ extern "C" int lagom_gemm_describe(int64_t M, int64_t N, int64_t K, lagom_dtype 
         rows = 1;
         cols = n;
     }
-    out->d_bytes_past_l2 = ((double)rows * BM + (double)cols * tile_n) * (double)K * 2.0 / (double)n +
-                           (double)BM * tile_n * lagom::elem_size(out_dt);
+    out->d_bytes_past_l2 = ((double)rows * BM + (double)cols * BN) * (double)K * 2.0 / (double)n +
+                           (double)BM * BN * lagom::elem_size(out_dt);
     return LAGOM_OK;
 }
 
@@ -537,20 +506,15 @@ extern "C" int lagom_gemm(const void* A, const void* B, void* C, int64_t M, int6
                           int b_is_nk, lagom_dtype out_dt, void* hip_stream) {
     if (int rc = lagom::check_gemm_args(A, B, C, M, N, K, out_dt)) return rc;
     if (!b_is_nk && (N % 8)) return lagom::fail(LAGOM_EINVAL, "B stored [K,N] needs N to be a multiple of 8");
-    const bool fast = fast_path(K, b_is_nk);
-    const int64_t tile_n = fast ? fast_tile_n(M, N) : BN;
     GemmArgs a{static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(B), C, M, N, K,
-               (int32_t)((M + BM - 1) / BM), (int32_t)((N + tile_n - 1) / tile_n)};
+               (int32_t)((M + BM - 1) / BM), (int32_t)((N + BN - 1) / BN)};
     const int64_t tiles = (int64_t)a.tiles_m * a.tiles_n;
     if (tiles > (1 << 30)) return lagom::fail(LAGOM_EINVAL, "too many tiles");
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const dim3 grid((unsigned)tiles), block(THREADS);
     const bool bf = out_dt == LAGOM_BF16;
-    if (fast) {
-        int rc;
-        if (tile_n == 224) rc = bf ? launch_fast<true, 7>(a, grid, st) : launch_fast<false, 7>(a, grid, st);
-        else rc = bf ? launch_fast<true, 8>(a, grid, st) : launch_fast<false, 8>(a, grid, st);
-        if (rc) return rc;
+    if (b_is_nk && K % BK == 0 && K <= FAST_MAX_K) {
+        if (int rc = bf ? launch_fast<true>(a, grid, st) : launch_fast<false>(a, grid, st)) return rc;
     } else if (b_is_nk) {
         if (bf) hipLaunchKernelGGL((gemm_bf16_general_kernel<true, true>), grid, block, 0, st, a);
         else hipLaunchKernelGGL((gemm_bf16_general_kernel<true, false>), grid, block, 0, st, a);

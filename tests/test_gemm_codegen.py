@@ -11,9 +11,7 @@ import pytest
 
 from paper_2602_20656_amd import build as lb
 
-# (mangled-name fragment, MFMA tiles per wavefront along N): 256-column and 224-column tiles, bf16 and fp32 output
-KERNELS = [("gemm_bf16_nk_kernelILb1ELi8E", 8), ("gemm_bf16_nk_kernelILb0ELi8E", 8),
-           ("gemm_bf16_nk_kernelILb1ELi7E", 7), ("gemm_bf16_nk_kernelILb0ELi7E", 7)]
+KERNELS = ("gemm_bf16_nk_kernelILb1E", "gemm_bf16_nk_kernelILb0E")
 AGPR = re.compile(r"\ba(\[\d+:\d+\]|\d+)\b")
 
 
@@ -39,12 +37,12 @@ def _metadata(text, sym):
     raise AssertionError(sym)
 
 
-@pytest.mark.parametrize("name,nj", KERNELS)
-def test_no_spills_and_all_agprs_for_accumulators(assembly, name, nj):
+@pytest.mark.parametrize("name", KERNELS)
+def test_no_spills_and_all_agprs_for_accumulators(assembly, name):
     sym, _ = _body(assembly, name)
     meta = _metadata(assembly, sym)
     assert meta["vgpr_spill_count"] == "0" and meta["sgpr_spill_count"] == "0", meta
-    assert meta["agpr_count"] == str(32 * nj), meta      # 8 x nj accumulator quads
+    assert meta["agpr_count"] == "256", meta
     assert meta["private_segment_fixed_size"] == "0", meta
 
 
@@ -64,11 +62,11 @@ def _blocks(lines):
     return blocks
 
 
-@pytest.mark.parametrize("name,nj", KERNELS)
-def test_only_mfmas_touch_accumulators_until_the_wait_states(assembly, name, nj):
+@pytest.mark.parametrize("name", KERNELS)
+def test_only_mfmas_touch_accumulators_until_the_wait_states(assembly, name):
     _, lines = _body(assembly, name)
     mfma = [i for i, l in enumerate(lines) if l.startswith("v_mfma_f32_16x16x32_bf16")]
-    assert len(mfma) >= 3 * 16 * nj    # steady-state step and the two peeled steps
+    assert len(mfma) >= 3 * 128        # steady-state step and the two peeled steps
     nop = next(i for i in range(mfma[-1], len(lines)) if lines[i].startswith("s_nop 7"))
     assert lines[nop + 1].startswith("s_nop 7") and lines[nop + 2].startswith("s_nop 7")
     for falls_in, block in _blocks(lines[mfma[0]:nop]):
@@ -83,8 +81,8 @@ def test_only_mfmas_touch_accumulators_until_the_wait_states(assembly, name, nj)
                 assert not has_mfma and not falls_in and l.startswith(("v_accvgpr_mov_b32", "v_accvgpr_write_b32")), l
 
 
-@pytest.mark.parametrize("name,nj", KERNELS)
-def test_steady_state_step_is_branch_free_with_one_side_instruction_per_mfma(assembly, name, nj):
+@pytest.mark.parametrize("name", KERNELS)
+def test_steady_state_step_is_branch_free_with_one_side_instruction_per_mfma(assembly, name):
     _, lines = _body(assembly, name)
     lines = [l for l in lines if l]
     # the loop: from its label to the first backward scalar branch behind the first MFMA
@@ -93,9 +91,9 @@ def test_steady_state_step_is_branch_free_with_one_side_instruction_per_mfma(ass
     label = lines[back].split()[-1] + ":"
     head = max(i for i in range(first) if lines[i].startswith(label))
     body = [l for l in lines[head + 1:back] if not l.endswith(":")]
-    assert sum(l.startswith("v_mfma") for l in body) == 16 * nj
-    assert sum(l.startswith("global_load_lds_dwordx4") for l in body) == 8 + nj
-    assert sum(l.startswith("ds_read_b128") for l in body) == 2 * (8 + nj)
+    assert sum(l.startswith("v_mfma") for l in body) == 128
+    assert sum(l.startswith("global_load_lds_dwordx4") for l in body) == 16
+    assert sum(l.startswith("ds_read_b128") for l in body) == 32
     assert sum(l.startswith("s_barrier") for l in body) == 1
     run, worst, lead = 0, 0, None
     for l in body:      # side instructions between two MFMAs

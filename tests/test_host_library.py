@@ -41,24 +41,16 @@ def test_host_only_helpers():
     assert lg.lagom_comm_bytes(lg.LAGOM_GATHER_COPY, lg.LAGOM_BF16, 8, 1, 2097152) == 64 << 20
     assert lg.lagom_comm_bytes(7, lg.LAGOM_BF16, 8, 1, 1) == -1
     g = lg.lagom_gemm_describe(8192, 8192, 8192)
-    assert (g.tile_m, g.tile_n) == (256, 256)
     assert g.mu == (8192 // g.tile_m) * (8192 // g.tile_n) and g.tb >= 1
     assert g.d_bytes == (g.tile_m + g.tile_n) * 8192 * 2 + g.tile_m * g.tile_n * 2
-    small = lg.lagom_gemm_describe(100, 300, 64)
-    assert small.mu == math.ceil(100 / small.tile_m) * math.ceil(300 / small.tile_n)
-    # bytes past an XCD's L2: the 32 tiles an XCD holds at a time form an 8 x 4 block -> 8 A panels and 4 B panels
+    assert lg.lagom_gemm_describe(100, 300, 64).mu == math.ceil(100 / g.tile_m) * math.ceil(300 / g.tile_n)
+    # bytes past an XCD's L2: the 32 tiles an XCD holds at a time form an 8 x 4 block -> A panels shared by 4, B by 8
     for M, N, K in [(4096, 4096, 4096), (8192, 4096, 4096), (8192, 8192, 8192)]:
         assert lg.lagom_gemm_describe(M, N, K).d_bytes_past_l2 == (8 * 256 + 4 * 256) * K * 2 / 32 + 256 * 256 * 2
-    # the tile is 224 columns wide where that fills the 256 compute units better: 3584 = 16 x 224 gives 16 x 16 = 256
-    # tiles in one round instead of 16 x 14 = 224 tiles of 256 columns; 4096 columns stay with 256
-    tp = lg.lagom_gemm_describe(4096, 3584, 8192)
-    assert (tp.tile_n, tp.mu) == (224, 256)
-    assert tp.d_bytes == (256 + 224) * 8192 * 2 + 256 * 224 * 2
-    assert tp.d_bytes_past_l2 == (8 * 256 + 4 * 224) * 8192 * 2 / 32 + 256 * 224 * 2
-    assert lg.lagom_gemm_describe(4096, 4096, 4096).tile_n == 256 and lg.lagom_gemm_describe(4096, 8192, 2048).tile_n == 256
-    tiny = lg.lagom_gemm_describe(512, 512, 512)          # 2 x 3 tiles of 224 columns: nothing is shared within an XCD
-    assert (tiny.tile_n, tiny.mu) == (224, 6) and tiny.d_bytes_past_l2 == tiny.d_bytes
-    assert lg.lagom_gemm_describe(512, 512, 72).tile_n == 256  # the general kernel (K not a multiple of 64) has one tile shape
+    small = lg.lagom_gemm_describe(512, 512, 512)          # 4 tiles: nothing is shared
+    assert small.d_bytes_past_l2 == small.d_bytes
+    # 16 x 14 tiles: 28 per XCD at a time, 8 tile-rows x 4 tile-columns (the last one half full)
+    assert lg.lagom_gemm_describe(4096, 3584, 8192).d_bytes_past_l2 == (8 * 256 + 4 * 256) * 8192 * 2 / 28 + 256 * 256 * 2
 
 
 def test_argument_errors_are_reported_before_any_gpu_work():
