@@ -61,7 +61,9 @@ const char* lagom_last_error(void);     /* detail of the calling thread's last f
  * numbered shard by shard, the last one of a shard may be short) is moved by
  * workgroup g mod nc.  The result does not depend on cfg.
  *
- *   srcs, dsts : HOST arrays of DEVICE pointers, 16-byte aligned, not overlapping.
+ *   srcs, dsts : HOST arrays of DEVICE pointers, 16-byte aligned.  Buffers must not overlap in part;
+ *                a reduce-copy destination may be exactly one of its sources (in-place
+ *                accumulation: every element is read before the same lane writes it).
  *   nsrc 1..LAGOM_MAX_SRCS, ndst 1..LAGOM_MAX_DSTS, count >= 0 (0 launches nothing).
  *   cfg        : nc >= 1; nt a multiple of 64 in 64..1024; chunk_bytes a positive
  *                multiple of 16.
