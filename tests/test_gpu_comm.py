@@ -205,3 +205,23 @@ def test_limits_of_the_argument_ranges():
         shards = _sources(dtype, 16, 1001, 800)
         for g in _run(lg.LAGOM_GATHER_COPY, dtype, shards, 4, (65535, 64, 16), 16 * 1001):
             assert same_bits(g, np.concatenate(shards))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("which", [0, 2])
+def test_reduce_copy_onto_one_of_its_sources(dtype, which):
+    """In-place accumulation: the destination is exactly source `which`; a second destination gets the same values.
+    Ragged length (a tail shorter than 16 bytes) and a configuration with several chunks per channel."""
+    count = 3 * 65536 + 5
+    srcs = _sources(dtype, 3, count, 900)
+    want = oc.reduce_copy(srcs, oc.F32 if dtype == "f32" else oc.BF16)[0]
+    d = [dev(s) for s in srcs]
+    np_dt = np.float32 if dtype == "f32" else np.uint16
+    other = dev(np.zeros(count, np_dt))
+    lg.lagom_comm_kernel(lg.LAGOM_REDUCE_COPY, lg.LAGOM_F32 if dtype == "f32" else lg.LAGOM_BF16, d, [d[which], other],
+                         count, (3, 128, 16384), torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    assert same_bits(host(d[which], np_dt), want) and same_bits(host(other, np_dt), want)
+    for s in range(3):
+        if s != which:
+            assert same_bits(host(d[s], np_dt), srcs[s]), "a source that is not the destination changed"
