@@ -368,6 +368,22 @@ def main():
                 "unit": "TFLOP/s", "frac": tflops / BF16_PEAK_TFLOPS,
                 "traffic": MEASURED_TRAFFIC_BYTES.get(f"gemm {M}x{N}x{K}"),
                 "us_per_launch": gemm_us, "flop_per_launch": flops}
+    # context only: the vendor BLAS for the same product (torch.matmul), timed the same way -- one event pair per launch
+    vendor_us = None
+    try:
+        tA = torch.randn(M, K, device="cuda").bfloat16()
+        tB = (torch.randn(N, K, device="cuda") * 0.02).bfloat16()
+        with torch.cuda.stream(s_comp):
+            for _ in range(args.warmup):
+                torch.matmul(tA, tB.t())
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+            for e0, e1 in ev:
+                e0.record(); torch.matmul(tA, tB.t()); e1.record()
+        torch.cuda.synchronize()
+        vendor_us = float(np.median([e0.elapsed_time(e1) for e0, e1 in ev])) * 1e3
+        del tA, tB
+    except Exception:        # the reference is optional; the bench line does not depend on it
+        vendor_us = None
     roofline_comm = standalone_comm_roofline(s_comm, s_comp, 5)
     # the workload's own communication, standalone, at its fastest swept point
     t_comm = lg.lagom_overlap_run(launches, [comm_opt.cfg] * ncomm, comps, s_comm, s_comp, args.warmup, args.steps, lg.LAGOM_ALONE_COMM)
@@ -412,6 +428,7 @@ def main():
         "model_tune_us": model_tune_us if tuned_model else None, "model_tune_profile_calls": tuned_model.calls if tuned_model else None,
         "tune_profile_calls": tuned.calls, "tune_seconds": tune_s, "sweep_points": len(points), "sweep_seconds": sweep_s,
         "gemm_alone_us": gemm_us, "gemm_mfma_util": tflops / BF16_PEAK_TFLOPS,
+        "vendor_blas_gemm_us": vendor_us, "vendor_blas_mfma_util": (flops / vendor_us / 1e6 / BF16_PEAK_TFLOPS) if vendor_us else None,
         "gemm_slowdown_default": t_default.Y_us / t_gemm.Y_us, "gemm_slowdown_tuned": t_tuned.Y_us / t_gemm.Y_us,
         "comm_alone_us": t_comm.X_us, "comm_alone_gbps": sum(nbytes) / t_comm.X_us / 1e3,
         "comm_hbm_gbps": roofline_comm["achieved"],
