@@ -125,10 +125,8 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_general_kernel(const GemmAr
             }
         } else {
 #pragma unroll
-            for (int i = 0; i < VEC_PER_THREAD; ++i) {   // B[K,N]: vectors run along N
-                const int id = tid + THREADS * i;
-                const int krow = id >> 5, nv = id & 31;
-                const int64_t gk = k0 + krow, gn = n0 + nv * 8;
+            for (int i = 0; i < VEC_PER_THREAD; ++i) {   // B[K,N]: a thread holds an 8 (k) x 8 (n) block
+                const int64_t gk = k0 + (tid & 7) * 8 + i, gn = n0 + (tid >> 3) * 8;
                 rb[i] = (gk < K && gn < N) ? *reinterpret_cast<const u32x4*>(p.B + gk * N + gn) : zero;
             }
         }
@@ -146,17 +144,18 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_general_kernel(const GemmAr
                 sB[swz(id >> 3, id & 7)] = rb[i];
             }
         } else {
-            uint16_t* sb16 = reinterpret_cast<uint16_t*>(sB);
+            // Transpose the 8 x 8 block in registers: column e of the block becomes one 16-byte group
+            // (8 consecutive k of row n) of the [n][k] tile.  v_perm_b32 picks the low or the high halves
+            // of two rows' words.  The 8 lanes tid & 7 of a row n write its 8 different groups.
+            const int kb = tid & 7, nv = tid >> 3;
 #pragma unroll
-            for (int i = 0; i < VEC_PER_THREAD; ++i) {   // transpose on the way into LDS
-                const int id = tid + THREADS * i;
-                const int krow = id >> 5, nv = id & 31;
+            for (int e = 0; e < 8; ++e) {
+                u32x4 col;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int n = nv * 8 + e;
-                    const uint32_t w = rb[i][e >> 1];
-                    sb16[swz(n, krow >> 3) * 8 + (krow & 7)] = (uint16_t)((e & 1) ? (w >> 16) : (w & 0xffffu));
-                }
+                for (int j = 0; j < 4; ++j)
+                    col[j] = __builtin_amdgcn_perm(rb[2 * j + 1][e >> 1], rb[2 * j][e >> 1],
+                                                   (e & 1) ? 0x07060302u : 0x05040100u);
+                sB[swz(nv * 8 + e, kb)] = col;
             }
         }
     };
