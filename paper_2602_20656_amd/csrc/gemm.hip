@@ -7,7 +7,7 @@
 // Workgroup ids are remapped so that the workgroups of one XCD (ids equal modulo 8) cover a
 // compact block of tiles and share A/B panels in that XCD's L2.
 //
-// Fast kernel (B stored [N,K], K a multiple of 64, K <= 2^22):
+// Fast kernel (K a multiple of 64, K <= 2^22; described for B stored [N,K]):
 //   * v_mfma_f32_16x16x32_bf16, 8 x 8 MFMA tiles per wavefront.  Under random operands the chip
 //     is power limited, and this shape costs less energy per flop than 32x32x16: a register-only
 //     loop sustains 86 % of the 2.5 PFLOP/s peak at 2.14 GHz with it against 77 % at 1.89 GHz.
@@ -31,9 +31,14 @@
 //   * The MFMA is issued with the B fragment as first operand, so a lane ends up holding four
 //     consecutive columns of one row of C; results are staged through LDS and written to HBM as
 //     16-byte vectors, whole rows of the wavefront's block contiguous.
+//   * B stored [K,N] (N a multiple of 8, N <= 2^23) runs the same kernel: the B tile lies in LDS as
+//     in memory, 64 rows (k) of 256 columns, and ds_read_b64_tr_b16 transposes while reading: two
+//     reads give a lane the 8 consecutive k of one column.  48 instead of 32 LDS reads per K-step,
+//     still one per MFMA.
 // General kernel (any K multiple of 8, either B layout, v_mfma_f32_32x32x16_bf16): tiles are
-// fetched into registers with bounds checks and zero fill, then stored to LDS; single buffered.
-// Slower; used for ragged K and for B stored [K,N].
+// fetched into registers with bounds checks and zero fill, then stored to LDS ([K,N]: 8 x 8
+// blocks transposed in registers first); single buffered.  Slower; used for ragged K and beyond
+// the fast kernel's size limits.
 #include <hip/hip_runtime.h>
 #include <type_traits>
 #include "common.h"
@@ -213,18 +218,29 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 constexpr int LDS_SLOTS = 5;                             // ring of operand tiles: A0 B0 A1 B1 A2 ...
 constexpr int SLOT_BYTES = BM * BK * 2;                  // 32 KiB: one operand tile
 constexpr int FAST_LDS_BYTES = LDS_SLOTS * SLOT_BYTES;   // 160 KiB: all of a compute unit's LDS
-constexpr int TILE_SLOTS = BM * 8;                       // 16-byte slots of one operand tile
 constexpr int64_t FAST_MAX_K = int64_t(1) << 22;         // 256 rows x K x 2 bytes must fit a 32-bit lane offset
+constexpr int64_t FAST_MAX_N_KN = int64_t(1) << 23;      // B stored [K,N]: so must 128 rows x N x 2 bytes
 
 __device__ __forceinline__ int swz64(int row, int cg) { return row * 8 + (cg ^ ((row >> 1) & 7)); }
+
+// B stored [K,N]: 16-byte group c of row k of a tile sits at position c ^ kn_swz(k).  A transposing read
+// touches rows 8q + 4h + r (q, r = 0..3) for one h, 32 bytes in each: the swizzle sends those 16 rows to 16
+// different 32-byte windows.
+__device__ __forceinline__ int kn_swz(int k) { return (((k >> 3) & 3) << 3) | ((k & 3) << 1); }
 
 // One 16x16x32 MFMA, accumulator pinned to the AGPR file.  Written as inline asm: with the builtin the
 // register allocator rotates the 64 accumulator quads through copies on every loop iteration.
 #define LAGOM_MFMA_16x16x32(ACC, SRC_A, SRC_B) \
     asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(ACC) : "v"(SRC_A), "v"(SRC_B))
 
-template <bool OUT_BF16>
-__global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p) {
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) char* lds_bytes;
+
+// B_KN = false: B stored [N,K]; true: B stored [K,N], its tiles kept in LDS as 64 rows (k) of 256 columns
+// and transposed by the LDS reads.
+template <bool B_KN, bool OUT_BF16>
+__device__ __forceinline__ void fast_gemm_body(const GemmArgs& p) {
     extern __shared__ u32x4 smem[];   // LDS_SLOTS operand tiles of 2048 16-byte slots
     // Wavefronts of a communication kernel may share this wavefront's SIMD (this kernel leaves them
     // registers): let the instruction arbiter prefer the GEMM.
@@ -237,6 +253,7 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
     tile_of(blockIdx.x, p.tiles_m, p.tiles_n, &tm, &tn);
     const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
     const int64_t M = p.M, N = p.N, K = p.K;
+    const char* smem_bytes = reinterpret_cast<const char*>(smem);
 
     f32x4 acc[8][8];
 #pragma unroll
@@ -254,13 +271,23 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
     const int srow = wave * 8 + (lane >> 3);
     const int scg = (lane & 7) ^ ((srow >> 1) & 7);
     const char* base_a = reinterpret_cast<const char*>(p.A + m0 * K);
-    const char* base_b = reinterpret_cast<const char*>(p.B + n0 * K);
+    // B stored [K,N]: a tile is 64 rows (k) of 512 bytes (256 n = 32 groups).  Load d fills rows
+    // 8*d + 2*wave + lane/32, stored group lane%32 holding source group (lane%32) ^ kn_swz(row);
+    // groups past the last column re-read the last one.  Successive K-steps are 64 rows of B apart.
+    const char* base_b = reinterpret_cast<const char*>(B_KN ? p.B + n0 : p.B + n0 * K);
+    const int64_t b_step = B_KN ? 2 * BK * N : 2 * BK;   // bytes from one K-step's tile of B to the next
     uint32_t a_off[8], b_off[8];
 #pragma unroll
     for (int d = 0; d < 8; ++d) {
         const int64_t r = srow + 32 * d, last_a = M - 1 - m0, last_b = N - 1 - n0;
         a_off[d] = (uint32_t)(((r < last_a ? r : last_a) * K + scg * 8) * 2);
-        b_off[d] = (uint32_t)(((r < last_b ? r : last_b) * K + scg * 8) * 2);
+        if (B_KN) {
+            const int krow = 8 * d + 2 * wave + (lane >> 5);
+            const int64_t grp = (lane & 31) ^ kn_swz(krow), last_grp = (N - n0) / 8 - 1;
+            b_off[d] = (uint32_t)((krow * N + (grp < last_grp ? grp : last_grp) * 8) * 2);
+        } else {
+            b_off[d] = (uint32_t)(((r < last_b ? r : last_b) * K + scg * 8) * 2);
+        }
     }
     // LDS byte address of this wavefront's 1 KiB window of load 0 in slot 0
     const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) char*)smem + wave * 1024;
@@ -273,7 +300,6 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
     auto set_m0 = [&](uint32_t slot_base, int d) { asm volatile("s_add_i32 m0, %0, %1" ::"s"(slot_base), "n"(d * 4096) : "memory"); };
     // (no immediate offset: the hardware would add it to the LDS address as well)
     auto load_m0 = [&](const char* sbase, uint32_t voff) { asm volatile("global_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase) : "memory"); };
-    auto slot_ptr = [&](int slot) -> u32x4* { return smem + slot * TILE_SLOTS; };
 
     const int64_t ksteps = K / BK;
     // prologue: A0 -> slot 0, B0 -> slot 1, A1 -> slot 2, first half of B1 -> slot 3
@@ -285,7 +311,7 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
 #pragma unroll
         for (int d = 0; d < 8; ++d) load_now(base_a + BK * 2, a_off[d], 2, d);
 #pragma unroll
-        for (int d = 0; d < 4; ++d) load_now(base_b + BK * 2, b_off[d], 3, d);
+        for (int d = 0; d < 4; ++d) load_now(base_b + b_step, b_off[d], 3, d);
         asm volatile("s_waitcnt vmcnt(12)" ::: "memory");   // loads complete in issue order: A0 and B0 are in
     } else {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -295,12 +321,42 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
     // Fragment r of a 32-wide k-slice: lane -> row 16*r + lane%16, 16-byte group 4*slice + lane/16.
     const int arow = wm * 128 + (lane & 15), brow = wn * 128 + (lane & 15), kq = lane >> 4;
     bf16x8 fa[2][8], fb[2][8];
-    auto read_frag = [&](const u32x4* sa, const u32x4* sb, int ks, int r, int buf) {   // r: 0..7 = A0..A7, 8..15 = B0..B7
-        if (r < 8) fa[buf][r] = __builtin_bit_cast(bf16x8, sa[swz64(arow + r * 16, ks * 4 + kq)]);
-        else fb[buf][r - 8] = __builtin_bit_cast(bf16x8, sb[swz64(brow + (r - 8) * 16, ks * 4 + kq)]);
+    // B stored [K,N]: fragment j of a k-slice is two transposing reads (h = 0, 1).  In each, lane
+    // 16*q + i hands in the address of B[8q + 4h + i/4][16j + 4*(i%4) .. +3] and receives
+    // B[8q + 4h + 0..3][16j + i]: together the 8 consecutive k of column 16j + lane%16 that the MFMA
+    // pairs with A[row][8q .. 8q+7].  kn_frag[j]: the lane's byte offset for fragment j in a tile's slot;
+    // slice and h move it by whole rows (16 KiB, 2 KiB), which the swizzle does not see.
+    s16x4 fbh[B_KN ? 2 : 1][B_KN ? 8 : 1][2];
+    uint32_t kn_frag[B_KN ? 8 : 1];
+    if (B_KN) {
+        const int i = lane & 15, r = i >> 2;
+        const int krow = 8 * kq + r;                                   // slice 0, h = 0
+        const int grp0 = wn * 16 + ((i & 3) >> 1);                     // source group of fragment 0
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            kn_frag[j] = (uint32_t)(krow * 512 + (((grp0 + 2 * j) ^ kn_swz(krow)) << 4) + 8 * (i & 1));
+    }
+    // r: 0..7 = A0..A7, 8..15 = B0..B7; half: which of the two reads of a [K,N] B fragment
+    auto read_frag = [&](const u32x4* sa, const u32x4* sb, int ks, int r, int buf, int half) {
+        if (r < 8) {
+            fa[buf][r] = __builtin_bit_cast(bf16x8, sa[swz64(arow + r * 16, ks * 4 + kq)]);
+        } else if (!B_KN) {
+            fb[buf][r - 8] = __builtin_bit_cast(bf16x8, sb[swz64(brow + (r - 8) * 16, ks * 4 + kq)]);
+        } else {
+            typedef s16x4 __attribute__((address_space(3))) * tr_ptr;
+            fbh[buf][r - 8][half] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (tr_ptr)((lds_bytes)(const char*)sb + kn_frag[r - 8] + ks * 16384 + half * 2048));
+        }
+    };
+    auto b_frag = [&](int buf, int j) -> bf16x8 {
+        if (!B_KN) return fb[buf][j];
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(fbh[buf][j][0], fbh[buf][j][1], 0, 1, 2, 3, 4, 5, 6, 7));
     };
 #pragma unroll
-    for (int r = 0; r < 16; ++r) read_frag(slot_ptr(0), slot_ptr(1), 0, r, 0);
+    for (int r = 0; r < 16; ++r) {
+        read_frag(smem, smem + SLOT_BYTES / 16, 0, r, 0, 0);
+        if (B_KN && r >= 8) read_frag(smem, smem + SLOT_BYTES / 16, 0, r, 0, 1);
+    }
 
     // One K-step = 2 k-slices x 8 groups x 8 MFMAs (group g: A fragment g against the 8 B fragments).
     // MORE1 / MORE2: tiles kt+1 / kt+2 exist (compile-time, so that the steady-state loop has no
@@ -319,11 +375,19 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
     // every role two slots along a ring of five, which is a pure rotation of these five values.
     uint32_t o_a = 0, o_b = SLOT_BYTES, o_a1 = 2 * SLOT_BYTES, o_b1 = 3 * SLOT_BYTES, o_a2 = 4 * SLOT_BYTES;
     const char* g_a = base_a + 2 * (BK * 2);   // &A[m0][(kt+2)*64]
-    const char* g_b = base_b + BK * 2;         // &B[n0][(kt+1)*64]; tile kt+2 of B is reached through b_off_next
+    const char* g_b = base_b + b_step;         // tile kt+1 of B; tile kt+2 is reached through b_off_next
     uint32_t b_off_next[4];
 #pragma unroll
-    for (int d = 0; d < 4; ++d) b_off_next[d] = b_off[d] + BK * 2;
-    const char* smem_bytes = reinterpret_cast<const char*>(smem);
+    for (int d = 0; d < 4; ++d) b_off_next[d] = b_off[d] + (uint32_t)b_step;
+    // Fragment reads of one k-slice in the order the MFMAs consume them.  [N,K]: 16 reads, A0, B0..B7,
+    // A1..A7.  [K,N]: 24 reads, every B fragment being two.
+    constexpr int kReads = B_KN ? 24 : 16;
+    auto read_nth = [&](const u32x4* sa, const u32x4* sb, int ks, int n, int buf) {
+        if (!B_KN) read_frag(sa, sb, ks, kReadOrder[n], buf, 0);
+        else if (n == 0) read_frag(sa, sb, ks, 0, buf, 0);
+        else if (n <= 16) read_frag(sa, sb, ks, 8 + (n - 1) / 2, buf, (n - 1) & 1);
+        else read_frag(sa, sb, ks, n - 16, buf, 0);
+    };
     auto step = [&](auto more1_c, auto more2_c) {
         constexpr bool more1 = decltype(more1_c)::value, more2 = decltype(more2_c)::value;
         const u32x4* sa = reinterpret_cast<const u32x4*>(smem_bytes + o_a);
@@ -346,7 +410,7 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
                     // B fragment first: the lane's 4 results are C[row lane%16][4 consecutive columns]
-                    LAGOM_MFMA_16x16x32(acc[g][j], fb[ks][j], fa[ks][g]);
+                    LAGOM_MFMA_16x16x32(acc[g][j], b_frag(ks, j), fa[ks][g]);
                     __builtin_amdgcn_sched_barrier(0);
                     if (j == 0) {
                         if (q < 4) { if (more1) set_m0(l_b1, 4 + q); }
@@ -358,11 +422,17 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
                         else if (q < 12) { if (more2) load_m0(g_a, a_off[q - 4]); }
                         else { if (more2) load_m0(g_b, b_off_next[q - 12]); }
                     }
-                    if (ks == 0) {
-                        if (j == 3) read_frag(sa, sb, 1, kReadOrder[2 * g], 1);
-                        if (j == 5) read_frag(sa, sb, 1, kReadOrder[2 * g + 1], 1);
-                    } else if (more1 && g >= 4) {
-                        if (j & 1) read_frag(sa1, sb1, 0, kReadOrder[(g - 4) * 4 + (j >> 1)], 0);
+                    if (ks == 0) {   // slice 1 of this tile: 2 (3) reads per group
+                        if (j == 3) read_nth(sa, sb, 1, (kReads / 8) * g, 1);
+                        if (j == 5) read_nth(sa, sb, 1, (kReads / 8) * g + 1, 1);
+                        if (B_KN && j == 6) read_nth(sa, sb, 1, 3 * g + 2, 1);
+                    } else if (more1 && g >= 4) {   // slice 0 of tile kt+1: 4 (6) reads per group
+                        if (!B_KN) {
+                            if (j & 1) read_nth(sa1, sb1, 0, (g - 4) * 4 + (j >> 1), 0);
+                        } else {
+                            constexpr int kSlot[8] = {-1, 0, -1, 1, 2, 3, 4, 5};
+                            if (kSlot[j] >= 0) read_nth(sa1, sb1, 0, (g - 4) * 6 + kSlot[j], 0);
+                        }
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -371,7 +441,7 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
         const uint32_t t_a = o_a, t_b = o_b;
         o_a = o_a1; o_b = o_b1; o_a1 = o_a2; o_b1 = t_a; o_a2 = t_b;
         g_a += BK * 2;
-        g_b += BK * 2;
+        g_b += b_step;
     };
     int kt = 0;
     const int nk = (int)ksteps;
@@ -453,11 +523,16 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p)
 }
 
 template <bool OUT_BF16>
+__global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p) { fast_gemm_body<false, OUT_BF16>(p); }
+template <bool OUT_BF16>
+__global__ void __launch_bounds__(THREADS) gemm_bf16_kn_kernel(const GemmArgs p) { fast_gemm_body<true, OUT_BF16>(p); }
+
+template <void (*KERNEL)(const GemmArgs)>
 int launch_fast(const GemmArgs& a, dim3 grid, hipStream_t st) {
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_nk_kernel<OUT_BF16>),
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(KERNEL),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, FAST_LDS_BYTES);
     if (attr != hipSuccess) return lagom::fail(LAGOM_EHIP, "gemm: cannot raise the LDS limit: %s", hipGetErrorString(attr));
-    hipLaunchKernelGGL((gemm_bf16_nk_kernel<OUT_BF16>), grid, dim3(THREADS), FAST_LDS_BYTES, st, a);
+    hipLaunchKernelGGL(KERNEL, grid, dim3(THREADS), FAST_LDS_BYTES, st, a);
     return LAGOM_OK;
 }
 
@@ -512,8 +587,12 @@ extern "C" int lagom_gemm(const void* A, const void* B, void* C, int64_t M, int6
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const dim3 grid((unsigned)tiles), block(THREADS);
     const bool bf = out_dt == LAGOM_BF16;
-    if (b_is_nk && K % BK == 0 && K <= FAST_MAX_K) {
-        if (int rc = bf ? launch_fast<true>(a, grid, st) : launch_fast<false>(a, grid, st)) return rc;
+    const bool fast = K % BK == 0 && K <= FAST_MAX_K && (b_is_nk || N <= FAST_MAX_N_KN);
+    if (fast) {
+        int rc;
+        if (b_is_nk) rc = bf ? launch_fast<gemm_bf16_nk_kernel<true>>(a, grid, st) : launch_fast<gemm_bf16_nk_kernel<false>>(a, grid, st);
+        else rc = bf ? launch_fast<gemm_bf16_kn_kernel<true>>(a, grid, st) : launch_fast<gemm_bf16_kn_kernel<false>>(a, grid, st);
+        if (rc) return rc;
     } else if (b_is_nk) {
         if (bf) hipLaunchKernelGGL((gemm_bf16_general_kernel<true, true>), grid, block, 0, st, a);
         else hipLaunchKernelGGL((gemm_bf16_general_kernel<true, false>), grid, block, 0, st, a);

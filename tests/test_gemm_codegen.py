@@ -11,7 +11,7 @@ import pytest
 
 from paper_2602_20656_amd import build as lb
 
-KERNELS = ("gemm_bf16_nk_kernelILb1E", "gemm_bf16_nk_kernelILb0E")
+KERNELS = ("gemm_bf16_nk_kernelILb1E", "gemm_bf16_nk_kernelILb0E", "gemm_bf16_kn_kernelILb1E", "gemm_bf16_kn_kernelILb0E")
 AGPR = re.compile(r"\ba(\[\d+:\d+\]|\d+)\b")
 
 
@@ -93,7 +93,12 @@ def test_steady_state_step_is_branch_free_with_one_side_instruction_per_mfma(ass
     body = [l for l in lines[head + 1:back] if not l.endswith(":")]
     assert sum(l.startswith("v_mfma") for l in body) == 128
     assert sum(l.startswith("global_load_lds_dwordx4") for l in body) == 16
-    assert sum(l.startswith("ds_read_b128") for l in body) == 32
+    if "_nk_" in name:
+        assert sum(l.startswith("ds_read_b128") for l in body) == 32
+    else:   # B stored [K,N]: 16 reads of A, 2 x 16 transposing reads of B
+        assert sum(l.startswith("ds_read_b128") for l in body) == 16
+        assert sum(l.startswith("ds_read_b64_tr_b16") for l in body) == 32
+        assert not any(l.startswith(("v_mov_b32", "v_perm_b32")) for l in body)   # fragment halves land in place
     assert sum(l.startswith("s_barrier") for l in body) == 1
     run, worst, lead = 0, 0, None
     for l in body:      # side instructions between two MFMAs
@@ -106,4 +111,5 @@ def test_steady_state_step_is_branch_free_with_one_side_instruction_per_mfma(ass
         elif not l.startswith(("s_waitcnt", "s_barrier")):
             run += 1
     assert worst <= 2, worst        # an M0 write, a load or a fragment read; nothing longer
-    assert lead + run <= 24, (lead, run)   # slot rotation, two running pointers, the counter
+    # slot rotation, two running pointers, the counter ([K,N]: and the slot's base added to 8 fragment addresses)
+    assert lead + run <= 24, (lead, run)

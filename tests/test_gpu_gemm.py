@@ -66,6 +66,33 @@ def test_gemm_integer_inputs_are_exact():
     assert np.array_equal(got.astype(np.int64), ai @ bi.T)
 
 
+@pytest.mark.parametrize("M,N,K", [(260, 272, 320), (100, 8, 64), (256, 776, 128), (513, 264, 192), (64, 1032, 576)])
+@pytest.mark.parametrize("out", ["bf16", "f32"])
+def test_gemm_b_kn_integer_inputs_are_exact(M, N, K, out):
+    """B stored [K,N] with K a multiple of 64 takes the kernel whose LDS reads transpose B: any mix-up of
+    rows, columns or k order shows as a wrong integer.  One to nine K-steps, ragged M and N tiles, N = 8."""
+    rng = np.random.default_rng(M + N + K)
+    ai = rng.integers(-3, 4, size=(M, K)); bi = rng.integers(-3, 4, size=(K, N))
+    a, b = inputs.to_bf16_bits(ai.astype(np.float32)), inputs.to_bf16_bits(bi.astype(np.float32))
+    got = _gemm(a, b, False, out)
+    want = ai @ bi
+    if out == "bf16":   # |sums| < 9 * 576: not all representable in bf16; compare after the same rounding
+        want = oc.bf16_to_f32(inputs.to_bf16_bits(want.astype(np.float32)))
+    assert np.array_equal(got.astype(np.float64), want.astype(np.float64))
+
+
+def test_gemm_b_kn_full_size_sampled_rows():
+    M = N = K = 4096
+    a = inputs.normal_bf16(2, (M, K))
+    b = inputs.normal_bf16(3, (K, N), scale=0.02)
+    got = _gemm(a, b, False, "bf16")
+    rng = np.random.default_rng(11)
+    rows = np.unique(np.concatenate([rng.integers(0, M, size=32), np.arange(0, 2), np.arange(M - 2, M)]))
+    ref = og.gemm_f64(a, b, False, rows=rows)
+    e_max, e_fro = og.rel_errors(got[rows], ref)
+    assert e_max <= GATE and e_fro <= GATE, (e_max, e_fro)
+
+
 def test_b_kn_layout_rejects_unaligned_n():
     with pytest.raises(lg.LagomError):
         lg.lagom_gemm(4096, 8192, 16384, 64, 60, 64, False)
