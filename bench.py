@@ -182,6 +182,45 @@ def standalone_comm_roofline(st1, st2, iters, final_iters=20):
     us = t.X_us / nrot
     best.update({"achieved": best["bytes_per_launch"] / us / 1e3, "frac": best["bytes_per_launch"] / us / 1e3 / HBM_PEAK_GBPS,
                  "us_per_launch": us, "launches_timed": nrot * final_iters})
+    del bufs, launches
+    # context only: the same operator on an 8 times longer buffer (576 MiB per launch, two rotated sets), where the
+    # fixed cost of a launch weighs less: what the kernel sustains once a launch is long enough
+    try:
+        big = count * 8
+        bufs = [[torch.empty(big, dtype=torch.float32, device="cuda").uniform_(-1, 1).to(tdt) for _ in range(nsrc + 1)]
+                for _ in range(2)]
+        launches = [lg.CommLaunch(lg.LAGOM_REDUCE_COPY, dt, b[:nsrc], [b[nsrc]], big, 0) for b in bufs]
+        big_bytes = lg.lagom_comm_bytes(lg.LAGOM_REDUCE_COPY, dt, nsrc, 1, big)
+        cands = [tuple(best["cfg"]), (1024, 1024, 16 << 10), (2048, 1024, 16 << 10), (4096, 512, 8 << 10), (4096, 1024, 16 << 10)]
+        t_big = min((lg.lagom_overlap_run(launches, [c], [], st1, st2, 1, iters, lg.LAGOM_ALONE_COMM).X_us / 2, c) for c in cands)
+        best["long_launch"] = {"count": big, "bytes_per_launch": big_bytes, "cfg": list(t_big[1]), "us_per_launch": t_big[0],
+                               "achieved": big_bytes / t_big[0] / 1e3, "frac": big_bytes / t_big[0] / 1e3 / HBM_PEAK_GBPS}
+        del bufs, launches
+    except RuntimeError:
+        best["long_launch"] = None
+    # context only: the vendor's device-to-device copy (torch's copy_) moving the same number of bytes per launch,
+    # half read and half written, on buffers rotated the same way, launches back to back
+    try:
+        half = best["bytes_per_launch"] // 2
+        pairs = [(torch.empty(half, dtype=torch.uint8, device="cuda").random_(), torch.empty(half, dtype=torch.uint8, device="cuda"))
+                 for _ in range(nrot)]
+        for src, dst in pairs:
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        times = []
+        for _ in range(final_iters):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for src, dst in pairs:
+                dst.copy_(src)
+            e1.record()
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1) * 1e3 / nrot)
+        v_us = float(np.median(times))
+        best.update({"vendor_copy_us_per_launch": v_us, "vendor_copy_gbps": 2 * half / v_us / 1e3})
+        del pairs
+    except RuntimeError:
+        best.update({"vendor_copy_us_per_launch": None, "vendor_copy_gbps": None})
     return best
 
 
