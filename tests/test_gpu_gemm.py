@@ -81,6 +81,28 @@ def test_gemm_b_kn_integer_inputs_are_exact(M, N, K, out):
     assert np.array_equal(got.astype(np.float64), want.astype(np.float64))
 
 
+def _random_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    shapes = []
+    for i in range(n):
+        M = int(rng.integers(1, 700)); N = 8 * int(rng.integers(1, 90))
+        K = 64 * int(rng.integers(1, 7)) if i % 3 else 8 * int(rng.integers(1, 40))   # two in three on the LDS-direct kernels
+        shapes.append((M, N, K))
+    return shapes
+
+
+@pytest.mark.parametrize("b_is_nk", [True, False])
+def test_gemm_seeded_random_shapes(b_is_nk):
+    """24 seeded shapes with ragged tiles in M and N and one to six K-steps, both kernels of each layout."""
+    for n, (M, N, K) in enumerate(_random_shapes(24, 77)):
+        a = inputs.normal_bf16(100 + n, (M, K))
+        b = inputs.normal_bf16(200 + n, (N, K) if b_is_nk else (K, N))
+        ref = og.gemm_f64(a, b, b_is_nk)
+        got = _gemm(a, b, b_is_nk, "f32" if n % 2 else "bf16")
+        e_max, e_fro = og.rel_errors(got, ref)
+        assert e_max <= GATE and e_fro <= GATE, (M, N, K, e_max, e_fro)
+
+
 def test_gemm_b_kn_full_size_sampled_rows():
     M = N = K = 4096
     a = inputs.normal_bf16(2, (M, K))
