@@ -48,6 +48,17 @@ def normal_bf16(seed: int, shape, scale: float = 1.0) -> np.ndarray:
     return to_bf16_bits(normal_f32(seed, shape, scale))
 
 
+def random_bits_bf16(seed: int, shape) -> np.ndarray:
+    """bf16 bit patterns drawn directly (cheap for very large arrays): random sign, exponent field in
+    120..127 (magnitudes in [2^-7, 2)), random 7-bit mantissa; no zeros, infinities or NaNs."""
+    n = int(np.prod(shape))
+    words = _gen(seed).integers(0, np.iinfo(np.uint64).max, size=(n + 3) // 4, dtype=np.uint64, endpoint=True)
+    r = words.view(np.uint16)[:n]
+    r &= np.uint16(0x83FF)      # keep sign, the low 3 exponent bits and the mantissa
+    r |= np.uint16(0x3C00)      # exponent bits 7..3 = 01111
+    return r.reshape(shape)
+
+
 def uniform_bf16(seed: int, n: int) -> np.ndarray:
     return to_bf16_bits(uniform_f32(seed, n))
 

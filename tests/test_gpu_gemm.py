@@ -58,6 +58,24 @@ def test_gemm_longest_k_of_the_fast_kernel_and_the_first_beyond_it(K):
         assert e_max <= GATE and e_fro <= GATE, (K, out, e_max, e_fro)
 
 
+def test_gemm_b_kn_widest_n_of_the_fast_kernel_and_the_first_beyond_it():
+    """B stored [K,N]: N = 2^23 is the widest row the LDS-direct kernel takes (its lane offsets reach two
+    K-steps = 128 rows of B ahead in 32 bits); N + 8 goes to the general one.  Three K-steps, so that the
+    look-ahead offsets are used.  Checked on the first, some middle and the last columns."""
+    M, K, wide = 2, 192, (1 << 23) + 8
+    a = inputs.normal_bf16(2, (M, K))
+    b_wide = inputs.random_bits_bf16(3, (K, wide))
+    for N in (wide, 1 << 23):
+        b = b_wide if N == wide else np.ascontiguousarray(b_wide[:, :N])
+        got = _gemm(a, b, False, "f32")
+        rng = np.random.default_rng(N)
+        cols = np.unique(np.concatenate([np.arange(0, 64), rng.integers(0, N, size=256), np.arange(N - 300, N)]))
+        ref = og.gemm_f64(a, np.ascontiguousarray(b[:, cols]), False)
+        e_max, e_fro = og.rel_errors(got[:, cols], ref)
+        assert e_max <= GATE and e_fro <= GATE and e_fro < 1e-5, (N, e_max, e_fro)
+        del b, got
+
+
 def test_gemm_integer_inputs_are_exact():
     rng = np.random.default_rng(5)
     ai = rng.integers(-4, 5, size=(260, 320)); bi = rng.integers(-4, 5, size=(270, 320))
