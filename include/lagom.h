@@ -85,7 +85,7 @@ int lagom_comm_kernel(lagom_op op, lagom_dtype dt,
  *   B : device, bf16, row-major [N,K] when b_is_nk != 0 (weight layout), else [K,N].
  *   C : device, row-major [M,N], bf16 (round-to-nearest-even) or fp32 per out_dt.
  *   M, N, K >= 1; K a multiple of 8 (16-byte rows); [K,N] also needs N a multiple of 8;
- *   pointers 16-byte aligned.  Either layout runs the fastest kernel when K is a multiple of 64.
+ *   pointers 16-byte aligned.  Fastest when K is a multiple of 64; K < 64 takes a slow path.
  * Enqueue only on hip_stream.  Errors: LAGOM_EINVAL, LAGOM_EALIGN, LAGOM_EHIP.
  */
 int lagom_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K,

@@ -7,7 +7,7 @@
 // Workgroup ids are remapped so that the workgroups of one XCD (ids equal modulo 8) cover a
 // compact block of tiles and share A/B panels in that XCD's L2.
 //
-// Fast kernel (K a multiple of 64, K <= 2^22; described for B stored [N,K]):
+// Fast kernel (64 <= K <= 2^22; described for B stored [N,K] and K a multiple of 64):
 //   * v_mfma_f32_16x16x32_bf16, 8 x 8 MFMA tiles per wavefront.  Under random operands the chip
 //     is power limited, and this shape costs less energy per flop than 32x32x16: a register-only
 //     loop sustains 86 % of the 2.5 PFLOP/s peak at 2.14 GHz with it against 77 % at 1.89 GHz.
@@ -35,9 +35,12 @@
 //     in memory, 64 rows (k) of 256 columns, and ds_read_b64_tr_b16 transposes while reading: two
 //     reads give a lane the 8 consecutive k of one column.  48 instead of 32 LDS reads per K-step,
 //     still one per MFMA.
+//   * K not a multiple of 64 (kernels of their own): after the loop's whole steps the last K % 64
+//     columns are fetched with guarded loads, zero filled from K on, stored to LDS in the loop's
+//     layout and multiplied by the same reads and MFMAs.
 // General kernel (any K multiple of 8, either B layout, v_mfma_f32_32x32x16_bf16): tiles are
 // fetched into registers with bounds checks and zero fill, then stored to LDS ([K,N]: 8 x 8
-// blocks transposed in registers first); single buffered.  Slower; used for ragged K and beyond
+// blocks transposed in registers first); single buffered.  Slower; used for K < 64 and beyond
 // the fast kernel's size limits.
 #include <hip/hip_runtime.h>
 #include <type_traits>
@@ -239,7 +242,8 @@ typedef __attribute__((address_space(3))) char* lds_bytes;
 
 // B_KN = false: B stored [N,K]; true: B stored [K,N], its tiles kept in LDS as 64 rows (k) of 256 columns
 // and transposed by the LDS reads.
-template <bool B_KN, bool OUT_BF16>
+// K_TAIL: K is not a multiple of 64; the last K % 64 columns are multiplied in a step of their own after the loop.
+template <bool B_KN, bool OUT_BF16, bool K_TAIL>
 __device__ __forceinline__ void fast_gemm_body(const GemmArgs& p) {
     extern __shared__ u32x4 smem[];   // LDS_SLOTS operand tiles of 2048 16-byte slots
     // Wavefronts of a communication kernel may share this wavefront's SIMD (this kernel leaves them
@@ -448,6 +452,51 @@ __device__ __forceinline__ void fast_gemm_body(const GemmArgs& p) {
     for (; kt + 2 < nk; ++kt) step(std::true_type{}, std::true_type{});
     if (kt + 1 < nk) { step(std::true_type{}, std::false_type{}); ++kt; }
     if (kt < nk) step(std::false_type{}, std::false_type{});
+    if (K_TAIL) {
+        // The last K % 64 columns: fetched with ordinary guarded loads (zeros from K on, in both operands),
+        // put into the first two slots in the layout the loop uses, and multiplied by the same fragment
+        // reads and MFMAs.  Every wavefront is past the last step's barrier, behind which nothing reads
+        // LDS and no LDS-direct load is in flight.
+        const int64_t kbase = ksteps * BK;
+        u32x4 ta[8], tb[8];
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int id = tid + THREADS * i;
+            const int64_t gm = m0 + (id >> 3), gk = kbase + (id & 7) * 8;
+            ta[i] = (gm < M && gk < K) ? *reinterpret_cast<const u32x4*>(p.A + gm * K + gk) : zero;
+            if (B_KN) {
+                const int64_t bk = kbase + (id >> 5), gn = n0 + (id & 31) * 8;
+                tb[i] = (bk < K && gn < N) ? *reinterpret_cast<const u32x4*>(p.B + bk * N + gn) : zero;
+            } else {
+                const int64_t gn = n0 + (id >> 3);
+                tb[i] = (gn < N && gk < K) ? *reinterpret_cast<const u32x4*>(p.B + gn * K + gk) : zero;
+            }
+        }
+        u32x4* slot_a = smem;
+        u32x4* slot_b = smem + SLOT_BYTES / 16;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int id = tid + THREADS * i;
+            slot_a[swz64(id >> 3, id & 7)] = ta[i];
+            if (B_KN) slot_b[(id >> 5) * 32 + ((id & 31) ^ kn_swz(id >> 5))] = tb[i];
+            else slot_b[swz64(id >> 3, id & 7)] = tb[i];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            if (ks == 1 && K - kbase <= 32) break;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                read_frag(slot_a, slot_b, ks, r, 0, 0);
+                if (B_KN && r >= 8) read_frag(slot_a, slot_b, ks, r, 0, 1);
+            }
+#pragma unroll
+            for (int g = 0; g < 8; ++g)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) LAGOM_MFMA_16x16x32(acc[g][j], b_frag(0, j), fa[0][g]);
+        }
+    }
     // The compiler does not see an MFMA inside the asm statements and therefore adds none of the wait
     // states an accumulator read needs after one: give the last results their cycles here, and make
     // every later use of an accumulator depend on a statement that follows these cycles.
@@ -523,9 +572,14 @@ __device__ __forceinline__ void fast_gemm_body(const GemmArgs& p) {
 }
 
 template <bool OUT_BF16>
-__global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p) { fast_gemm_body<false, OUT_BF16>(p); }
+__global__ void __launch_bounds__(THREADS) gemm_bf16_nk_kernel(const GemmArgs p) { fast_gemm_body<false, OUT_BF16, false>(p); }
 template <bool OUT_BF16>
-__global__ void __launch_bounds__(THREADS) gemm_bf16_kn_kernel(const GemmArgs p) { fast_gemm_body<true, OUT_BF16>(p); }
+__global__ void __launch_bounds__(THREADS) gemm_bf16_kn_kernel(const GemmArgs p) { fast_gemm_body<true, OUT_BF16, false>(p); }
+// K >= 64 and not a multiple of 64 (kernels of their own: the extra step costs registers the others leave free)
+template <bool OUT_BF16>
+__global__ void __launch_bounds__(THREADS) gemm_bf16_nk_tail_kernel(const GemmArgs p) { fast_gemm_body<false, OUT_BF16, true>(p); }
+template <bool OUT_BF16>
+__global__ void __launch_bounds__(THREADS) gemm_bf16_kn_tail_kernel(const GemmArgs p) { fast_gemm_body<true, OUT_BF16, true>(p); }
 
 template <void (*KERNEL)(const GemmArgs)>
 int launch_fast(const GemmArgs& a, dim3 grid, hipStream_t st) {
@@ -587,11 +641,16 @@ extern "C" int lagom_gemm(const void* A, const void* B, void* C, int64_t M, int6
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const dim3 grid((unsigned)tiles), block(THREADS);
     const bool bf = out_dt == LAGOM_BF16;
-    const bool fast = K % BK == 0 && K <= FAST_MAX_K && (b_is_nk || N <= FAST_MAX_N_KN);
+    const bool fast = K >= BK && K <= FAST_MAX_K && (b_is_nk || N <= FAST_MAX_N_KN);
     if (fast) {
         int rc;
-        if (b_is_nk) rc = bf ? launch_fast<gemm_bf16_nk_kernel<true>>(a, grid, st) : launch_fast<gemm_bf16_nk_kernel<false>>(a, grid, st);
-        else rc = bf ? launch_fast<gemm_bf16_kn_kernel<true>>(a, grid, st) : launch_fast<gemm_bf16_kn_kernel<false>>(a, grid, st);
+        if (K % BK == 0) {
+            if (b_is_nk) rc = bf ? launch_fast<gemm_bf16_nk_kernel<true>>(a, grid, st) : launch_fast<gemm_bf16_nk_kernel<false>>(a, grid, st);
+            else rc = bf ? launch_fast<gemm_bf16_kn_kernel<true>>(a, grid, st) : launch_fast<gemm_bf16_kn_kernel<false>>(a, grid, st);
+        } else {
+            if (b_is_nk) rc = bf ? launch_fast<gemm_bf16_nk_tail_kernel<true>>(a, grid, st) : launch_fast<gemm_bf16_nk_tail_kernel<false>>(a, grid, st);
+            else rc = bf ? launch_fast<gemm_bf16_kn_tail_kernel<true>>(a, grid, st) : launch_fast<gemm_bf16_kn_tail_kernel<false>>(a, grid, st);
+        }
         if (rc) return rc;
     } else if (b_is_nk) {
         if (bf) hipLaunchKernelGGL((gemm_bf16_general_kernel<true, true>), grid, block, 0, st, a);

@@ -11,7 +11,7 @@ import pytest
 
 from paper_2602_20656_amd import build as lb
 
-KERNELS = ("gemm_bf16_nk_kernelILb1E", "gemm_bf16_nk_kernelILb0E", "gemm_bf16_kn_kernelILb1E", "gemm_bf16_kn_kernelILb0E")
+KERNELS = tuple("gemm_bf16_%s_kernelILb%dE" % (k, o) for k in ("nk", "kn", "nk_tail", "kn_tail") for o in (1, 0))
 AGPR = re.compile(r"\ba(\[\d+:\d+\]|\d+)\b")
 
 

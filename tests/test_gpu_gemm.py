@@ -99,6 +99,20 @@ def test_gemm_b_kn_integer_inputs_are_exact(M, N, K, out):
     assert np.array_equal(got.astype(np.float64), want.astype(np.float64))
 
 
+@pytest.mark.parametrize("K", [72, 96, 104, 120, 184, 4104])
+@pytest.mark.parametrize("b_is_nk", [True, False])
+def test_gemm_ragged_k_integer_inputs_are_exact(K, b_is_nk):
+    """K >= 64 that is no multiple of 64: the LDS-direct kernels multiply the last K % 64 columns (8 to 56
+    of them, one or two 32-wide slices) in a step of their own, zero filled from K on."""
+    M, N = 260, 272
+    rng = np.random.default_rng(K)
+    ai = rng.integers(-3, 4, size=(M, K)); bi = rng.integers(-3, 4, size=(K, N))
+    a = inputs.to_bf16_bits(ai.astype(np.float32))
+    b = inputs.to_bf16_bits((bi.T if b_is_nk else bi).astype(np.float32))
+    got = _gemm(a, b, b_is_nk, "f32")
+    assert np.array_equal(got.astype(np.int64), ai @ bi)
+
+
 def _random_shapes(n, seed):
     rng = np.random.default_rng(seed)
     shapes = []
