@@ -93,7 +93,8 @@ int lagom_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, int6
 
 /* Workgroup geometry of lagom_gemm for a problem size, as the cost model needs it
  * (Eq. 5-6: mu = total workgroups, TB = workgroups resident per compute unit,
- * D = bytes each workgroup reads and writes).  Host only. */
+ * D = bytes each workgroup reads and writes).  The tiling depends on the size only: 128 x 128
+ * tiles when at most 256 of them cover C and K is a multiple of 64, else 256 x 256.  Host only. */
 typedef struct {
     int64_t mu;
     int32_t tb;

@@ -1,9 +1,11 @@
 // lagom_gemm: C[M,N] = A[M,K] . B, bf16 inputs, fp32 accumulation on the gfx950 matrix
 // cores, the computation whose slow-down the overlap model describes (Sec. 3.2, Fig. 3).
 //
-// Tiling (both kernels): one workgroup of 256 threads (4 wavefronts, 2 x 2) owns a 256 x 256
-// tile of C and walks K in steps of 64; each wavefront owns a 128 x 128 block, i.e. 256 fp32
-// accumulators per lane (the whole AGPR file), so one workgroup is resident per compute unit.
+// Tiling: one workgroup of 256 threads (4 wavefronts, 2 x 2) owns a 256 x 256 tile of C and
+// walks K in steps of 64; each wavefront owns a 128 x 128 block, i.e. 256 fp32 accumulators per
+// lane (the whole AGPR file), so one workgroup is resident per compute unit.  Products that at
+// most 256 tiles of 128 x 128 cover (and K a multiple of 64) use those instead: 256 x 256 tiles
+// would leave most of the 256 compute units idle (see the small-tile kernel below).
 // Workgroup ids are remapped so that the workgroups of one XCD (ids equal modulo 8) cover a
 // compact block of tiles and share A/B panels in that XCD's L2.
 //
@@ -581,6 +583,203 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_tail_kernel(const GemmAr
 template <bool OUT_BF16>
 __global__ void __launch_bounds__(THREADS) gemm_bf16_kn_tail_kernel(const GemmArgs p) { fast_gemm_body<true, OUT_BF16, true>(p); }
 
+// ------------------------------------------------------------------------- small-tile kernel
+// 128 x 128 x 64 tiles for products with too few 256 x 256 tiles to fill the chip.  Same workgroup
+// (4 wavefronts, 2 x 2, each 64 x 64 = 4 x 4 MFMA tiles, 64 accumulators), same LDS-direct loads, row
+// layout and swizzle as the large kernel; a K-step is only 32 MFMAs long, so the ring holds five
+// A+B tile pairs and loads run four K-steps ahead.  One barrier per K-step: behind it tile kt has
+// landed for every wavefront and the slot of tile kt-1 is free for the loads of tile kt+4.
+constexpr int SBM = 128, SBN = 128;
+constexpr int S_STAGES = 5, S_AHEAD = S_STAGES - 1;
+constexpr int S_OPERAND_BYTES = SBM * BK * 2;             // 16 KiB
+constexpr int S_STAGE_BYTES = 2 * S_OPERAND_BYTES;        // A then B
+static_assert(S_STAGES * S_STAGE_BYTES == FAST_LDS_BYTES, "the ring fills the LDS like the large kernel's");
+
+// B stored [K,N]: a B tile is 64 rows (k) of 256 bytes (128 n = 16 groups); group c of row k sits at
+// c ^ kn_swz128(k), which spreads the rows of a transposing read over the 8 32-byte windows of a row.
+__device__ __forceinline__ int kn_swz128(int k) { return (((k >> 3) & 1) << 3) | ((k & 3) << 1); }
+
+template <bool B_KN, bool OUT_BF16>
+__device__ __forceinline__ void small_gemm_body(const GemmArgs& p) {
+    extern __shared__ u32x4 smem[];
+    __builtin_amdgcn_s_setprio(3);
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    int tm, tn;
+    tile_of(blockIdx.x, p.tiles_m, p.tiles_n, &tm, &tn);
+    const int64_t m0 = (int64_t)tm * SBM, n0 = (int64_t)tn * SBN;
+    const int64_t M = p.M, N = p.N, K = p.K;
+    const char* smem_bytes = reinterpret_cast<const char*>(smem);
+
+    f32x4 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // load d (0..3) of an operand tile: rows (d*4 + wave)*8 + lane/8, as in the large kernel
+    const int srow = wave * 8 + (lane >> 3);
+    const int scg = (lane & 7) ^ ((srow >> 1) & 7);
+    const char* g_a = reinterpret_cast<const char*>(p.A + m0 * K);
+    const char* g_b = reinterpret_cast<const char*>(B_KN ? p.B + n0 : p.B + n0 * K);
+    const int64_t b_step = B_KN ? 2 * BK * N : 2 * BK;
+    uint32_t a_off[4], b_off[4];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const int64_t r = srow + 32 * d, last_a = M - 1 - m0, last_b = N - 1 - n0;
+        a_off[d] = (uint32_t)(((r < last_a ? r : last_a) * K + scg * 8) * 2);
+        if (B_KN) {   // load d fills rows 16*d + 4*wave + lane/16 of the [64][128] tile, stored group lane%16
+            const int krow = 16 * d + 4 * wave + (lane >> 4);
+            const int64_t grp = (lane & 15) ^ kn_swz128(krow), last_grp = (N - n0) / 8 - 1;
+            b_off[d] = (uint32_t)((krow * N + (grp < last_grp ? grp : last_grp) * 8) * 2);
+        } else {
+            b_off[d] = (uint32_t)(((r < last_b ? r : last_b) * K + scg * 8) * 2);
+        }
+    }
+    const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) char*)smem + wave * 1024;
+    auto load_tile = [&](int stage) {   // the tile g_a / g_b point at, then advance them one K-step
+        const uint32_t base = lds0 + stage * S_STAGE_BYTES;
+#pragma unroll
+        for (int d = 0; d < 4; ++d)
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(base + d * 4096), "v"(a_off[d]), "s"(g_a) : "memory");
+#pragma unroll
+        for (int d = 0; d < 4; ++d)
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(base + S_OPERAND_BYTES + d * 4096), "v"(b_off[d]), "s"(g_b) : "memory");
+        g_a += BK * 2;
+        g_b += b_step;
+    };
+
+    const int nk = (int)(K / BK);
+    for (int t = 0; t < S_AHEAD && t < nk; ++t) load_tile(t);
+
+    const int arow = wm * 64 + (lane & 15), brow = wn * 64 + (lane & 15), kq = lane >> 4;
+    bf16x8 fa[2][4], fb[2][4];   // fragments of the two 32-wide k-slices, read half a K-step before their MFMAs
+    // B stored [K,N]: fragment j is two transposing reads (rows 8q + 4h + i/4 of the slice, h = 0, 1; see the
+    // large kernel); kn_frag[j] is the lane's byte offset for h = 0 in slice 0
+    uint32_t kn_frag[B_KN ? 4 : 1];
+    if (B_KN) {
+        const int i = lane & 15, krow = 8 * kq + (i >> 2);
+        const int grp0 = wn * 8 + ((i & 3) >> 1);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            kn_frag[j] = (uint32_t)(krow * 256 + (((grp0 + 2 * j) ^ kn_swz128(krow)) << 4) + 8 * (i & 1));
+    }
+    auto read_slice = [&](int stage, int ks) {
+        const u32x4* sa = reinterpret_cast<const u32x4*>(smem_bytes + stage * S_STAGE_BYTES);
+        const u32x4* sb = sa + S_OPERAND_BYTES / 16;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            fa[ks][r] = __builtin_bit_cast(bf16x8, sa[swz64(arow + r * 16, ks * 4 + kq)]);
+            if (!B_KN) {
+                fb[ks][r] = __builtin_bit_cast(bf16x8, sb[swz64(brow + r * 16, ks * 4 + kq)]);
+            } else {
+                typedef s16x4 __attribute__((address_space(3))) * tr_ptr;
+                const lds_bytes at = (lds_bytes)(const char*)sb + kn_frag[r] + ks * 8192;
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((tr_ptr)at);
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((tr_ptr)(at + 1024));
+                fb[ks][r] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+            }
+        }
+    };
+    auto mfma_slice = [&](int ks) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)   // B fragment first: a lane holds 4 consecutive columns of one row
+                LAGOM_MFMA_16x16x32(acc[i][j], fb[ks][j], fa[ks][i]);
+    };
+    // loads complete in issue order: wait until all but the youngest `tiles` tiles (8 loads each) have landed
+    auto wait_all_but = [&](int tiles) {
+        if (tiles >= 3) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+        else if (tiles == 2) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+        else if (tiles == 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    };
+    wait_all_but(nk - 1 < S_AHEAD - 1 ? nk - 1 : S_AHEAD - 1);   // tile 0
+    __builtin_amdgcn_s_barrier();
+    read_slice(0, 0);
+    int stage = 0, next_stage = S_AHEAD;
+    for (int kt = 0; kt < nk; ++kt) {
+        const int stage1 = stage + 1 == S_STAGES ? 0 : stage + 1;
+        read_slice(stage, 1);
+        mfma_slice(0);
+        // In the middle of the step: tile kt+1 must have landed for every wavefront before its first slice is
+        // read, and behind this barrier no wavefront reads tile kt-1 any more, whose slot tile kt+4 goes into.
+        // Issued so far: tiles up to kt+3.
+        const int issued_after_next = nk - 2 - kt < S_AHEAD - 2 ? nk - 2 - kt : S_AHEAD - 2;
+        if (kt + 1 < nk) wait_all_but(issued_after_next);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        if (kt + S_AHEAD < nk) load_tile(next_stage);
+        if (kt + 1 < nk) read_slice(stage1, 0);
+        mfma_slice(1);
+        stage = stage1;
+        next_stage = next_stage + 1 == S_STAGES ? 0 : next_stage + 1;
+    }
+    // wait states behind the last inline-asm MFMA, as in the large kernel
+    asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) asm volatile("" : "+a"(acc[i][j]));
+    __builtin_amdgcn_s_barrier();   // every wavefront is past its last LDS read before the ring is reused below
+
+    // Epilogue: acc[i][j][v] is row 16*i + lane%16, column 16*j + 4*(lane/16) + v of the wavefront's 64 x 64
+    // block, staged in the wavefront's own LDS as rows of ROW_BYTES (16-byte group c of row r at c ^ (r % GROUPS))
+    // and written out as 16-byte vectors, whole rows of the block contiguous.
+    constexpr int ESZ = OUT_BF16 ? 2 : 4;
+    constexpr int ROW_BYTES = 64 * ESZ, GROUPS = ROW_BYTES / 16, ROWS_PER_READ = 64 / GROUPS, VEC = 16 / ESZ;
+    char* st = reinterpret_cast<char*>(smem) + wave * (64 * ROW_BYTES);
+    const int r_in = lane & 15, c_q = 4 * (lane >> 4);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int r = i * 16 + r_in;
+            const int cb = (j * 16 + c_q) * ESZ;
+            char* dst = st + r * ROW_BYTES + (((cb >> 4) ^ (r & (GROUPS - 1))) << 4) + (cb & 15);
+            if (OUT_BF16) {
+                const bf16x2 lo = __builtin_convertvector(f32x2{acc[i][j][0], acc[i][j][1]}, bf16x2);
+                const bf16x2 hi = __builtin_convertvector(f32x2{acc[i][j][2], acc[i][j][3]}, bf16x2);
+                uint2 v;
+                v.x = __builtin_bit_cast(uint32_t, lo);
+                v.y = __builtin_bit_cast(uint32_t, hi);
+                *reinterpret_cast<uint2*>(dst) = v;
+            } else {
+                *reinterpret_cast<f32x4*>(dst) = acc[i][j];
+            }
+        }
+    const bool interior = m0 + SBM <= M && n0 + SBN <= N;
+    const bool vector_ok = (N % VEC) == 0;
+    const int rd_row = lane / GROUPS, rd_cv = lane % GROUPS;
+    const int64_t gcol = n0 + wn * 64 + rd_cv * VEC;
+    const int64_t row0 = m0 + wm * 64 + rd_row;
+#pragma unroll
+    for (int e = 0; e < GROUPS; ++e) {   // GROUPS reads of ROWS_PER_READ rows cover the 64 rows
+        const int r = rd_row + ROWS_PER_READ * e;
+        const u32x4 val = *reinterpret_cast<const u32x4*>(st + r * ROW_BYTES + ((rd_cv ^ (r & (GROUPS - 1))) << 4));
+        const int64_t grow = row0 + ROWS_PER_READ * e;
+        char* out = reinterpret_cast<char*>(p.C) + (grow * N + gcol) * ESZ;
+        if (vector_ok) {
+            if (interior || (grow < M && gcol < N)) __builtin_nontemporal_store(val, reinterpret_cast<u32x4*>(out));
+        } else if (grow < M) {
+#pragma unroll
+            for (int k = 0; k < VEC; ++k)
+                if (gcol + k < N) {
+                    if (OUT_BF16) reinterpret_cast<uint16_t*>(out)[k] = (uint16_t)(val[k >> 1] >> (16 * (k & 1)));
+                    else reinterpret_cast<uint32_t*>(out)[k] = val[k];
+                }
+        }
+    }
+}
+
+template <bool OUT_BF16>
+__global__ void __launch_bounds__(THREADS) gemm_bf16_nk128_kernel(const GemmArgs p) { small_gemm_body<false, OUT_BF16>(p); }
+template <bool OUT_BF16>
+__global__ void __launch_bounds__(THREADS) gemm_bf16_kn128_kernel(const GemmArgs p) { small_gemm_body<true, OUT_BF16>(p); }
+
 template <void (*KERNEL)(const GemmArgs)>
 int launch_fast(const GemmArgs& a, dim3 grid, hipStream_t st) {
     static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(KERNEL),
@@ -588,6 +787,13 @@ int launch_fast(const GemmArgs& a, dim3 grid, hipStream_t st) {
     if (attr != hipSuccess) return lagom::fail(LAGOM_EHIP, "gemm: cannot raise the LDS limit: %s", hipGetErrorString(attr));
     hipLaunchKernelGGL(KERNEL, grid, dim3(THREADS), FAST_LDS_BYTES, st, a);
     return LAGOM_OK;
+}
+
+// 128 x 128 tiles when they still fit the chip in one round (256 compute units), i.e. when 256 x 256 tiles
+// would leave three quarters of it idle.
+bool small_tiles(int64_t M, int64_t N, int64_t K) {
+    const int64_t n128 = ((M + SBM - 1) / SBM) * ((N + SBN - 1) / SBN);
+    return n128 <= 256 && K % BK == 0 && K <= FAST_MAX_K;
 }
 
 }  // namespace
@@ -606,11 +812,14 @@ int check_gemm_args(const void* A, const void* B, const void* C, int64_t M, int6
 
 extern "C" int lagom_gemm_describe(int64_t M, int64_t N, int64_t K, lagom_dtype out_dt, lagom_gemm_geometry* out) {
     if (!out || M < 1 || N < 1 || K < 1 || lagom::elem_size(out_dt) == 0) return lagom::fail(LAGOM_EINVAL, "bad argument");
-    const int64_t tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN;
+    // the tiling lagom_gemm uses for this shape (it does not depend on B's layout)
+    const bool small = small_tiles(M, N, K);
+    const int64_t bm = small ? SBM : BM, bn = small ? SBN : BN;
+    const int64_t tm = (M + bm - 1) / bm, tn = (N + bn - 1) / bn;
     out->mu = tm * tn;
-    out->tb = 1;   // 256 accumulators per lane fill the AGPR file: one workgroup per compute unit
-    out->d_bytes = (double)(BM + BN) * (double)K * 2.0 + (double)BM * BN * lagom::elem_size(out_dt);
-    out->tile_m = BM; out->tile_n = BN; out->tile_k = BK; out->threads = THREADS;
+    out->tb = 1;   // either kernel takes all of a compute unit's LDS: one workgroup per compute unit
+    out->d_bytes = (double)(bm + bn) * (double)K * 2.0 + (double)bm * bn * lagom::elem_size(out_dt);
+    out->tile_m = (int32_t)bm; out->tile_n = (int32_t)bn; out->tile_k = BK; out->threads = THREADS;
     // the block of tiles an XCD works on at a time under tile_of() (32 compute units per XCD): n tiles in
     // r tile-rows and c tile-columns need r A panels and c B panels between them
     const int64_t total = tm * tn;
@@ -625,8 +834,8 @@ extern "C" int lagom_gemm_describe(int64_t M, int64_t N, int64_t K, lagom_dtype 
         rows = 1;
         cols = n;
     }
-    out->d_bytes_past_l2 = ((double)rows * BM + (double)cols * BN) * (double)K * 2.0 / (double)n +
-                           (double)BM * BN * lagom::elem_size(out_dt);
+    out->d_bytes_past_l2 = ((double)rows * bm + (double)cols * bn) * (double)K * 2.0 / (double)n +
+                           (double)bm * bn * lagom::elem_size(out_dt);
     return LAGOM_OK;
 }
 
@@ -634,6 +843,19 @@ extern "C" int lagom_gemm(const void* A, const void* B, void* C, int64_t M, int6
                           int b_is_nk, lagom_dtype out_dt, void* hip_stream) {
     if (int rc = lagom::check_gemm_args(A, B, C, M, N, K, out_dt)) return rc;
     if (!b_is_nk && (N % 8)) return lagom::fail(LAGOM_EINVAL, "B stored [K,N] needs N to be a multiple of 8");
+    if (small_tiles(M, N, K)) {
+        GemmArgs a{static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(B), C, M, N, K,
+                   (int32_t)((M + SBM - 1) / SBM), (int32_t)((N + SBN - 1) / SBN)};
+        const dim3 grid((unsigned)(a.tiles_m * a.tiles_n));
+        hipStream_t st = static_cast<hipStream_t>(hip_stream);
+        int rc;
+        if (b_is_nk) rc = out_dt == LAGOM_BF16 ? launch_fast<gemm_bf16_nk128_kernel<true>>(a, grid, st) : launch_fast<gemm_bf16_nk128_kernel<false>>(a, grid, st);
+        else rc = out_dt == LAGOM_BF16 ? launch_fast<gemm_bf16_kn128_kernel<true>>(a, grid, st) : launch_fast<gemm_bf16_kn128_kernel<false>>(a, grid, st);
+        if (rc) return rc;
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return lagom::fail(LAGOM_EHIP, "gemm launch: %s", hipGetErrorString(e));
+        return LAGOM_OK;
+    }
     GemmArgs a{static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(B), C, M, N, K,
                (int32_t)((M + BM - 1) / BM), (int32_t)((N + BN - 1) / BN)};
     const int64_t tiles = (int64_t)a.tiles_m * a.tiles_n;

@@ -32,7 +32,9 @@ def _gemm(a_bits, b_bits, b_is_nk, out):
 
 
 @pytest.mark.parametrize("M,N,K", [(512, 512, 512), (1, 1, 8), (300, 200, 136), (700, 520, 264), (256, 256, 64),
-                                   (257, 255, 72), (33, 1000, 4096), (130, 77, 128), (513, 260, 192), (700, 300, 320), (1000, 520, 256), (300, 300, 64)])
+                                   (257, 255, 72), (33, 1000, 4096), (130, 77, 128), (513, 260, 192), (700, 300, 320), (1000, 520, 256), (300, 300, 64),
+                                   # more than 256 tiles of 128 x 128: the 256 x 256 kernels, ragged in M and N, 1 to 3 K-steps, a K tail
+                                   (2100, 2200, 192), (2100, 2200, 64), (2312, 1800, 136), (1800, 2440, 128)])
 @pytest.mark.parametrize("b_is_nk", [True, False])
 @pytest.mark.parametrize("out", ["bf16", "f32"])
 def test_gemm_small_shapes(M, N, K, b_is_nk, out):
@@ -84,11 +86,13 @@ def test_gemm_integer_inputs_are_exact():
     assert np.array_equal(got.astype(np.int64), ai @ bi.T)
 
 
-@pytest.mark.parametrize("M,N,K", [(260, 272, 320), (100, 8, 64), (256, 776, 128), (513, 264, 192), (64, 1032, 576)])
+@pytest.mark.parametrize("M,N,K", [(260, 272, 320), (100, 8, 64), (256, 776, 128), (513, 264, 192), (64, 1032, 576),
+                                   (2100, 2056, 128), (2304, 2312, 320)])
 @pytest.mark.parametrize("out", ["bf16", "f32"])
 def test_gemm_b_kn_integer_inputs_are_exact(M, N, K, out):
     """B stored [K,N] with K a multiple of 64 takes the kernel whose LDS reads transpose B: any mix-up of
-    rows, columns or k order shows as a wrong integer.  One to nine K-steps, ragged M and N tiles, N = 8."""
+    rows, columns or k order shows as a wrong integer.  One to nine K-steps, ragged M and N tiles, N = 8; the last
+    two shapes have more than 256 tiles of 128 x 128 and run on 256 x 256 tiles, the others on the small ones."""
     rng = np.random.default_rng(M + N + K)
     ai = rng.integers(-3, 4, size=(M, K)); bi = rng.integers(-3, 4, size=(K, N))
     a, b = inputs.to_bf16_bits(ai.astype(np.float32)), inputs.to_bf16_bits(bi.astype(np.float32))
@@ -101,10 +105,12 @@ def test_gemm_b_kn_integer_inputs_are_exact(M, N, K, out):
 
 @pytest.mark.parametrize("K", [72, 96, 104, 120, 184, 4104])
 @pytest.mark.parametrize("b_is_nk", [True, False])
-def test_gemm_ragged_k_integer_inputs_are_exact(K, b_is_nk):
+@pytest.mark.parametrize("M,N", [(260, 272), (2100, 2056)])
+def test_gemm_ragged_k_integer_inputs_are_exact(K, b_is_nk, M, N):
     """K >= 64 that is no multiple of 64: the LDS-direct kernels multiply the last K % 64 columns (8 to 56
     of them, one or two 32-wide slices) in a step of their own, zero filled from K on."""
-    M, N = 260, 272
+    if K == 4104 and M > 1000:
+        pytest.skip("one long K is enough")
     rng = np.random.default_rng(K)
     ai = rng.integers(-3, 4, size=(M, K)); bi = rng.integers(-3, 4, size=(K, N))
     a = inputs.to_bf16_bits(ai.astype(np.float32))

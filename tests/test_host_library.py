@@ -43,12 +43,20 @@ def test_host_only_helpers():
     g = lg.lagom_gemm_describe(8192, 8192, 8192)
     assert g.mu == (8192 // g.tile_m) * (8192 // g.tile_n) and g.tb >= 1
     assert g.d_bytes == (g.tile_m + g.tile_n) * 8192 * 2 + g.tile_m * g.tile_n * 2
-    assert lg.lagom_gemm_describe(100, 300, 64).mu == math.ceil(100 / g.tile_m) * math.ceil(300 / g.tile_n)
+    assert (g.tile_m, g.tile_n, g.tile_k) == (256, 256, 64)
+    # at most 256 tiles of 128 x 128 (and K a multiple of 64): the small tiling
+    few = lg.lagom_gemm_describe(100, 300, 64)
+    assert (few.tile_m, few.tile_n, few.mu, few.tb) == (128, 128, 1 * 3, 1)
+    assert few.d_bytes == (128 + 128) * 64 * 2 + 128 * 128 * 2
+    assert lg.lagom_gemm_describe(2048, 2048, 4096).mu == 256 and lg.lagom_gemm_describe(2048, 2176, 4096).tile_m == 256
+    assert lg.lagom_gemm_describe(512, 512, 72).tile_m == 256       # ragged K stays on the large tiles
     # bytes past an XCD's L2: the 32 tiles an XCD holds at a time form an 8 x 4 block -> A panels shared by 4, B by 8
     for M, N, K in [(4096, 4096, 4096), (8192, 4096, 4096), (8192, 8192, 8192)]:
         assert lg.lagom_gemm_describe(M, N, K).d_bytes_past_l2 == (8 * 256 + 4 * 256) * K * 2 / 32 + 256 * 256 * 2
-    small = lg.lagom_gemm_describe(512, 512, 512)          # 4 tiles: nothing is shared
-    assert small.d_bytes_past_l2 == small.d_bytes
+    small = lg.lagom_gemm_describe(512, 512, 512)          # 16 small tiles, two per XCD, in one tile-column: a B panel shared by 2
+    assert small.d_bytes_past_l2 == (2 * 128 + 1 * 128) * 512 * 2 / 2 + 128 * 128 * 2
+    lone = lg.lagom_gemm_describe(256, 256, 512)           # 4 tiles: nothing is shared
+    assert lone.d_bytes_past_l2 == lone.d_bytes
     # 16 x 14 tiles: 28 per XCD at a time, 8 tile-rows x 4 tile-columns (the last one half full)
     assert lg.lagom_gemm_describe(4096, 3584, 8192).d_bytes_past_l2 == (8 * 256 + 4 * 256) * 8192 * 2 / 28 + 256 * 256 * 2
 
