@@ -653,9 +653,21 @@ __device__ __forceinline__ void small_gemm_body(const GemmArgs& p) {
 
     const int nk = (int)(K / BK);
     for (int t = 0; t < S_AHEAD && t < nk; ++t) load_tile(t);
+    // Tile t >= 4 is loaded in two halves: A behind the barrier of step t-5, B in the first half of step t-4
+    // (g_a / g_b point at the next tile to load of their operand).
+    auto set_m0 = [&](uint32_t lds) { asm volatile("s_mov_b32 m0, %0" ::"s"(lds) : "memory"); };
+    auto load_m0 = [&](const char* sbase, uint32_t voff) { asm volatile("global_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase) : "memory"); };
+    if (S_AHEAD < nk) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d)
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds0 + S_AHEAD * S_STAGE_BYTES + d * 4096), "v"(a_off[d]), "s"(g_a) : "memory");
+        g_a += BK * 2;
+    }
 
     const int arow = wm * 64 + (lane & 15), brow = wn * 64 + (lane & 15), kq = lane >> 4;
-    bf16x8 fa[2][4], fb[2][4];   // fragments of the two 32-wide k-slices, read half a K-step before their MFMAs
+    bf16x8 fa[2][4];
+    bf16x8 fb[2][4];             // fragments of the two 32-wide k-slices, read half a K-step before their MFMAs
+    s16x4 fbh[B_KN ? 2 : 1][B_KN ? 4 : 1][2];
     // B stored [K,N]: fragment j is two transposing reads (rows 8q + 4h + i/4 of the slice, h = 0, 1; see the
     // large kernel); kn_frag[j] is the lane's byte offset for h = 0 in slice 0
     uint32_t kn_frag[B_KN ? 4 : 1];
@@ -666,58 +678,94 @@ __device__ __forceinline__ void small_gemm_body(const GemmArgs& p) {
         for (int j = 0; j < 4; ++j)
             kn_frag[j] = (uint32_t)(krow * 256 + (((grp0 + 2 * j) ^ kn_swz128(krow)) << 4) + 8 * (i & 1));
     }
-    auto read_slice = [&](int stage, int ks) {
-        const u32x4* sa = reinterpret_cast<const u32x4*>(smem_bytes + stage * S_STAGE_BYTES);
+    // read unit u of a slice, in the order the MFMAs consume them: A0, B0, B1, B2, B3, A1, A2, A3
+    auto read_unit = [&](uint32_t stage_bytes, int ks, int u) {
+        const u32x4* sa = reinterpret_cast<const u32x4*>(smem_bytes + stage_bytes);
         const u32x4* sb = sa + S_OPERAND_BYTES / 16;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
+        if (u == 0 || u >= 5) {
+            const int r = u == 0 ? 0 : u - 4;
             fa[ks][r] = __builtin_bit_cast(bf16x8, sa[swz64(arow + r * 16, ks * 4 + kq)]);
-            if (!B_KN) {
-                fb[ks][r] = __builtin_bit_cast(bf16x8, sb[swz64(brow + r * 16, ks * 4 + kq)]);
-            } else {
-                typedef s16x4 __attribute__((address_space(3))) * tr_ptr;
-                const lds_bytes at = (lds_bytes)(const char*)sb + kn_frag[r] + ks * 8192;
-                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((tr_ptr)at);
-                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((tr_ptr)(at + 1024));
-                fb[ks][r] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-            }
+        } else if (!B_KN) {
+            fb[ks][u - 1] = __builtin_bit_cast(bf16x8, sb[swz64(brow + (u - 1) * 16, ks * 4 + kq)]);
+        } else {
+            typedef s16x4 __attribute__((address_space(3))) * tr_ptr;
+            const lds_bytes at = (lds_bytes)(const char*)sb + kn_frag[u - 1] + ks * 8192;
+            fbh[ks][u - 1][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((tr_ptr)at);
+            fbh[ks][u - 1][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((tr_ptr)(at + 1024));
         }
     };
-    auto mfma_slice = [&](int ks) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)   // B fragment first: a lane holds 4 consecutive columns of one row
-                LAGOM_MFMA_16x16x32(acc[i][j], fb[ks][j], fa[ks][i]);
+    auto b_frag = [&](int ks, int j) -> bf16x8 {
+        if (!B_KN) return fb[ks][j];
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(fbh[ks][j][0], fbh[ks][j][1], 0, 1, 2, 3, 4, 5, 6, 7));
     };
-    // loads complete in issue order: wait until all but the youngest `tiles` tiles (8 loads each) have landed
-    auto wait_all_but = [&](int tiles) {
-        if (tiles >= 3) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
-        else if (tiles == 2) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-        else if (tiles == 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    // loads complete in issue order: wait until all but the youngest `loads` have landed
+    auto wait_all_but = [&](int loads) {
+        if (loads >= 24) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+        else if (loads >= 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+        else if (loads >= 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     };
-    wait_all_but(nk - 1 < S_AHEAD - 1 ? nk - 1 : S_AHEAD - 1);   // tile 0
+    wait_all_but(8 * (nk - 1 < S_AHEAD - 1 ? nk - 1 : S_AHEAD - 1) + (S_AHEAD < nk ? 4 : 0));   // tile 0
     __builtin_amdgcn_s_barrier();
-    read_slice(0, 0);
-    int stage = 0, next_stage = S_AHEAD;
-    for (int kt = 0; kt < nk; ++kt) {
-        const int stage1 = stage + 1 == S_STAGES ? 0 : stage + 1;
-        read_slice(stage, 1);
-        mfma_slice(0);
-        // In the middle of the step: tile kt+1 must have landed for every wavefront before its first slice is
-        // read, and behind this barrier no wavefront reads tile kt-1 any more, whose slot tile kt+4 goes into.
-        // Issued so far: tiles up to kt+3.
-        const int issued_after_next = nk - 2 - kt < S_AHEAD - 2 ? nk - 2 - kt : S_AHEAD - 2;
-        if (kt + 1 < nk) wait_all_but(issued_after_next);
-        asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-        if (kt + S_AHEAD < nk) load_tile(next_stage);
-        if (kt + 1 < nk) read_slice(stage1, 0);
-        mfma_slice(1);
-        stage = stage1;
-        next_stage = next_stage + 1 == S_STAGES ? 0 : next_stage + 1;
-    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) read_unit(0, 0, u);
+
+    // One K-step = 2 k-slices x 16 MFMAs, each MFMA followed by one side instruction (a B fragment of the
+    // [K,N] layout being two reads):
+    //   first half   8 fragment reads of slice 1; then the B half of tile kt+4 (M0 write and load alternating)
+    //   barrier      behind vmcnt: tile kt+1 has landed for every wavefront; nobody reads tile kt any more
+    //                (its fragments are in registers), so its slot can take the A half of tile kt+5
+    //   second half  8 fragment reads of slice 0 of tile kt+1; then the A half of tile kt+5
+    // LOAD_B / LOAD_A / NEXT: tiles kt+4 / kt+5 / kt+1 exist (compile time: no branch inside a step).
+    uint32_t o_cur = 0, o_next = S_STAGE_BYTES, o_b4 = S_AHEAD * S_STAGE_BYTES;   // byte offsets of the slots of tiles kt, kt+1, kt+4
+    int kt = 0;
+    auto step = [&](auto load_b_c, auto load_a_c, auto next_c) {
+        constexpr bool LOAD_B = decltype(load_b_c)::value, LOAD_A = decltype(load_a_c)::value, NEXT = decltype(next_c)::value;
+        const uint32_t l_b = lds0 + o_b4 + S_OPERAND_BYTES, l_a = lds0 + o_cur;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            if (ks == 1) {
+                // issued and not needed yet: whole tiles kt+2 .. kt+4 that exist
+                if (LOAD_B) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+                else if (NEXT) wait_all_but(8 * (nk - 2 - kt));
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int sl = i * 4 + j;     // slot within the half
+                    // B fragment first: a lane holds 4 consecutive columns of one row
+                    LAGOM_MFMA_16x16x32(acc[i][j], b_frag(ks, j), fa[ks][i]);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (sl < 8) {
+                        if (ks == 0) read_unit(o_cur, 1, sl);
+                        else if (NEXT) read_unit(o_next, 0, sl);
+                    } else {
+                        const int d = (sl - 8) >> 1;
+                        if (ks == 0 && LOAD_B) { if (sl & 1) load_m0(g_b, b_off[d]); else set_m0(l_b + d * 4096); }
+                        if (ks == 1 && LOAD_A) { if (sl & 1) load_m0(g_a, a_off[d]); else set_m0(l_a + d * 4096); }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+        }
+        if (LOAD_B) g_b += b_step;
+        if (LOAD_A) g_a += BK * 2;
+        o_cur = o_next;
+        o_next = o_next + S_STAGE_BYTES == S_STAGES * S_STAGE_BYTES ? 0 : o_next + S_STAGE_BYTES;
+        o_b4 = o_b4 + S_STAGE_BYTES == S_STAGES * S_STAGE_BYTES ? 0 : o_b4 + S_STAGE_BYTES;
+        ++kt;
+    };
+    while (kt + 5 < nk) step(std::true_type{}, std::true_type{}, std::true_type{});
+    // at most five steps are left, peeled in straight-line code (a loop over step variants makes the register
+    // allocator copy accumulators between them, with none of the wait states a copy behind an MFMA needs)
+    if (kt + 4 < nk) step(std::true_type{}, std::false_type{}, std::true_type{});
+    if (kt + 1 < nk) step(std::false_type{}, std::false_type{}, std::true_type{});
+    if (kt + 1 < nk) step(std::false_type{}, std::false_type{}, std::true_type{});
+    if (kt + 1 < nk) step(std::false_type{}, std::false_type{}, std::true_type{});
+    if (kt < nk) step(std::false_type{}, std::false_type{}, std::false_type{});
     // wait states behind the last inline-asm MFMA, as in the large kernel
     asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
 #pragma unroll

@@ -114,3 +114,31 @@ def test_steady_state_step_is_branch_free_with_one_side_instruction_per_mfma(ass
     assert worst <= 2, worst        # an M0 write, a load or a fragment read; nothing longer
     # slot rotation, two running pointers, the counter ([K,N]: and the slot's base added to 8 fragment addresses)
     assert lead + run <= 24, (lead, run)
+
+
+@pytest.mark.parametrize("name", SMALL)
+def test_small_tile_step_has_one_side_instruction_per_mfma(assembly, name):
+    _, lines = _body(assembly, name)
+    lines = [l for l in lines if l]
+    first = next(i for i, l in enumerate(lines) if l.startswith("v_mfma"))
+    back = next(i for i in range(first, len(lines)) if lines[i].startswith("s_cbranch"))
+    label = lines[back].split()[-1] + ":"
+    head = max(i for i in range(first) if lines[i].startswith(label))
+    body = [l for l in lines[head + 1:back] if not l.endswith(":")]
+    assert sum(l.startswith("v_mfma") for l in body) == 32
+    assert sum(l.startswith("global_load_lds_dwordx4") for l in body) == 8
+    assert sum(l.startswith("s_barrier") for l in body) == 1
+    if "_nk128_" in name:
+        assert sum(l.startswith("ds_read_b128") for l in body) == 16
+    else:   # B stored [K,N]: 8 reads of A, 2 x 8 transposing reads of B
+        assert sum(l.startswith("ds_read_b128") for l in body) == 8
+        assert sum(l.startswith("ds_read_b64_tr_b16") for l in body) == 16
+    run, worst, seen = 0, 0, False
+    for l in body:
+        if l.startswith("v_mfma"):
+            if seen:
+                worst = max(worst, run)
+            seen, run = True, 0
+        elif not l.startswith(("s_waitcnt", "s_barrier")):
+            run += 1
+    assert worst <= 4, worst   # an address add or two with a read; an offset add with an M0 write
