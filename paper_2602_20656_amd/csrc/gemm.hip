@@ -4,8 +4,8 @@
 // Tiling: one workgroup of 256 threads (4 wavefronts, 2 x 2) owns a 256 x 256 tile of C and
 // walks K in steps of 64; each wavefront owns a 128 x 128 block, i.e. 256 fp32 accumulators per
 // lane (the whole AGPR file), so one workgroup is resident per compute unit.  Products that at
-// most 256 tiles of 128 x 128 cover (and K a multiple of 64) use those instead: 256 x 256 tiles
-// would leave most of the 256 compute units idle (see the small-tile kernel below).
+// most 256 tiles of 128 x 128 or of 256 x 128 cover (and K a multiple of 64) use those instead:
+// 256 x 256 tiles would leave compute units idle (see the small-tile kernels below).
 // Workgroup ids are remapped so that the workgroups of one XCD (ids equal modulo 8) cover a
 // compact block of tiles and share A/B panels in that XCD's L2.
 //
@@ -583,24 +583,34 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_nk_tail_kernel(const GemmAr
 template <bool OUT_BF16>
 __global__ void __launch_bounds__(THREADS) gemm_bf16_kn_tail_kernel(const GemmArgs p) { fast_gemm_body<true, OUT_BF16, true>(p); }
 
-// ------------------------------------------------------------------------- small-tile kernel
-// 128 x 128 x 64 tiles for products with too few 256 x 256 tiles to fill the chip.  Same workgroup
-// (4 wavefronts, 2 x 2, each 64 x 64 = 4 x 4 MFMA tiles, 64 accumulators), same LDS-direct loads, row
-// layout and swizzle as the large kernel; a K-step is only 32 MFMAs long, so the ring holds five
-// A+B tile pairs and loads run four K-steps ahead.  One barrier per K-step: behind it tile kt has
-// landed for every wavefront and the slot of tile kt-1 is free for the loads of tile kt+4.
-constexpr int SBM = 128, SBN = 128;
-constexpr int S_STAGES = 5, S_AHEAD = S_STAGES - 1;
-constexpr int S_OPERAND_BYTES = SBM * BK * 2;             // 16 KiB
-constexpr int S_STAGE_BYTES = 2 * S_OPERAND_BYTES;        // A then B
-static_assert(S_STAGES * S_STAGE_BYTES == FAST_LDS_BYTES, "the ring fills the LDS like the large kernel's");
+// ------------------------------------------------------------------------- small-tile kernels
+// 128 x 128 x 64 and 256 x 128 x 64 tiles for products with too few 256 x 256 tiles to fill the chip.
+// Same workgroup (4 wavefronts, 2 x 2; a wavefront owns NI x 4 MFMA tiles, NI = 4 or 8, i.e. 64 or 128
+// accumulators), same LDS-direct loads, row layout and swizzles as the large kernel.  LDS holds a ring of
+// A+B tile pairs: five for NI = 4 (a K-step is only 32 MFMAs long, loads run four to five steps ahead),
+// three for NI = 8.  One barrier per K-step, in its middle.
+constexpr int SBN = 128;
+constexpr int S_B_BYTES = SBN * BK * 2;                   // 16 KiB
+template <int NI> struct SmallTile {
+    static constexpr int BM_ = 32 * NI;                   // rows of a tile
+    static constexpr int A_BYTES = BM_ * BK * 2;          // 16 or 32 KiB
+    static constexpr int STAGE_BYTES = A_BYTES + S_B_BYTES;
+    static constexpr int STAGES = NI == 4 ? 5 : 3;
+    static constexpr int AHEAD = STAGES - 1;
+    static constexpr int LA = NI, LB = 4;                 // load instructions per wavefront for an A / a B tile
+    static_assert(STAGES * STAGE_BYTES <= FAST_LDS_BYTES, "the ring fits the LDS");
+};
+constexpr int SBM = SmallTile<4>::BM_, MBM = SmallTile<8>::BM_;
 
 // B stored [K,N]: a B tile is 64 rows (k) of 256 bytes (128 n = 16 groups); group c of row k sits at
 // c ^ kn_swz128(k), which spreads the rows of a transposing read over the 8 32-byte windows of a row.
 __device__ __forceinline__ int kn_swz128(int k) { return (((k >> 3) & 1) << 3) | ((k & 3) << 1); }
 
-template <bool B_KN, bool OUT_BF16>
+template <int NI, bool B_KN, bool OUT_BF16>
 __device__ __forceinline__ void small_gemm_body(const GemmArgs& p) {
+    typedef SmallTile<NI> T;
+    constexpr int S_STAGES = T::STAGES, S_AHEAD = T::AHEAD, S_STAGE_BYTES = T::STAGE_BYTES, S_OPERAND_BYTES = T::A_BYTES;
+    constexpr int LA = T::LA, LB = T::LB, PER_TILE = LA + LB;
     extern __shared__ u32x4 smem[];
     __builtin_amdgcn_s_setprio(3);
     const int tid = threadIdx.x;
@@ -609,27 +619,31 @@ __device__ __forceinline__ void small_gemm_body(const GemmArgs& p) {
     const int wm = wave >> 1, wn = wave & 1;
     int tm, tn;
     tile_of(blockIdx.x, p.tiles_m, p.tiles_n, &tm, &tn);
-    const int64_t m0 = (int64_t)tm * SBM, n0 = (int64_t)tn * SBN;
+    const int64_t m0 = (int64_t)tm * T::BM_, n0 = (int64_t)tn * SBN;
     const int64_t M = p.M, N = p.N, K = p.K;
     const char* smem_bytes = reinterpret_cast<const char*>(smem);
 
-    f32x4 acc[4][4];
+    f32x4 acc[NI][4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < NI; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // load d (0..3) of an operand tile: rows (d*4 + wave)*8 + lane/8, as in the large kernel
+    // load d of an operand tile: rows (d*4 + wave)*8 + lane/8, as in the large kernel
     const int srow = wave * 8 + (lane >> 3);
     const int scg = (lane & 7) ^ ((srow >> 1) & 7);
     const char* g_a = reinterpret_cast<const char*>(p.A + m0 * K);
     const char* g_b = reinterpret_cast<const char*>(B_KN ? p.B + n0 : p.B + n0 * K);
     const int64_t b_step = B_KN ? 2 * BK * N : 2 * BK;
-    uint32_t a_off[4], b_off[4];
+    uint32_t a_off[LA], b_off[LB];
 #pragma unroll
-    for (int d = 0; d < 4; ++d) {
-        const int64_t r = srow + 32 * d, last_a = M - 1 - m0, last_b = N - 1 - n0;
+    for (int d = 0; d < LA; ++d) {
+        const int64_t r = srow + 32 * d, last_a = M - 1 - m0;
         a_off[d] = (uint32_t)(((r < last_a ? r : last_a) * K + scg * 8) * 2);
+    }
+#pragma unroll
+    for (int d = 0; d < LB; ++d) {
+        const int64_t r = srow + 32 * d, last_b = N - 1 - n0;
         if (B_KN) {   // load d fills rows 16*d + 4*wave + lane/16 of the [64][128] tile, stored group lane%16
             const int krow = 16 * d + 4 * wave + (lane >> 4);
             const int64_t grp = (lane & 15) ^ kn_swz128(krow), last_grp = (N - n0) / 8 - 1;
@@ -642,10 +656,10 @@ __device__ __forceinline__ void small_gemm_body(const GemmArgs& p) {
     auto load_tile = [&](int stage) {   // the tile g_a / g_b point at, then advance them one K-step
         const uint32_t base = lds0 + stage * S_STAGE_BYTES;
 #pragma unroll
-        for (int d = 0; d < 4; ++d)
+        for (int d = 0; d < LA; ++d)
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(base + d * 4096), "v"(a_off[d]), "s"(g_a) : "memory");
 #pragma unroll
-        for (int d = 0; d < 4; ++d)
+        for (int d = 0; d < LB; ++d)
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(base + S_OPERAND_BYTES + d * 4096), "v"(b_off[d]), "s"(g_b) : "memory");
         g_a += BK * 2;
         g_b += b_step;
@@ -653,19 +667,19 @@ __device__ __forceinline__ void small_gemm_body(const GemmArgs& p) {
 
     const int nk = (int)(K / BK);
     for (int t = 0; t < S_AHEAD && t < nk; ++t) load_tile(t);
-    // Tile t >= 4 is loaded in two halves: A behind the barrier of step t-5, B in the first half of step t-4
-    // (g_a / g_b point at the next tile to load of their operand).
+    // Tile t >= AHEAD is loaded in two halves: A behind the barrier of step t-STAGES, B in the first half of
+    // step t-AHEAD (g_a / g_b point at the next tile to load of their operand).
     auto set_m0 = [&](uint32_t lds) { asm volatile("s_mov_b32 m0, %0" ::"s"(lds) : "memory"); };
     auto load_m0 = [&](const char* sbase, uint32_t voff) { asm volatile("global_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase) : "memory"); };
     if (S_AHEAD < nk) {
 #pragma unroll
-        for (int d = 0; d < 4; ++d)
+        for (int d = 0; d < LA; ++d)
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds0 + S_AHEAD * S_STAGE_BYTES + d * 4096), "v"(a_off[d]), "s"(g_a) : "memory");
         g_a += BK * 2;
     }
 
-    const int arow = wm * 64 + (lane & 15), brow = wn * 64 + (lane & 15), kq = lane >> 4;
-    bf16x8 fa[2][4];
+    const int arow = wm * (16 * NI) + (lane & 15), brow = wn * 64 + (lane & 15), kq = lane >> 4;
+    bf16x8 fa[2][NI];
     bf16x8 fb[2][4];             // fragments of the two 32-wide k-slices, read half a K-step before their MFMAs
     s16x4 fbh[B_KN ? 2 : 1][B_KN ? 4 : 1][2];
     // B stored [K,N]: fragment j is two transposing reads (rows 8q + 4h + i/4 of the slice, h = 0, 1; see the
@@ -678,7 +692,8 @@ __device__ __forceinline__ void small_gemm_body(const GemmArgs& p) {
         for (int j = 0; j < 4; ++j)
             kn_frag[j] = (uint32_t)(krow * 256 + (((grp0 + 2 * j) ^ kn_swz128(krow)) << 4) + 8 * (i & 1));
     }
-    // read unit u of a slice, in the order the MFMAs consume them: A0, B0, B1, B2, B3, A1, A2, A3
+    constexpr int UNITS = NI + 4;
+    // read unit u of a slice, in the order the MFMAs consume them: A0, B0, B1, B2, B3, A1, A2, ...
     auto read_unit = [&](uint32_t stage_bytes, int ks, int u) {
         const u32x4* sa = reinterpret_cast<const u32x4*>(smem_bytes + stage_bytes);
         const u32x4* sb = sa + S_OPERAND_BYTES / 16;
@@ -698,25 +713,26 @@ __device__ __forceinline__ void small_gemm_body(const GemmArgs& p) {
         if (!B_KN) return fb[ks][j];
         return __builtin_bit_cast(bf16x8, __builtin_shufflevector(fbh[ks][j][0], fbh[ks][j][1], 0, 1, 2, 3, 4, 5, 6, 7));
     };
-    // loads complete in issue order: wait until all but the youngest `loads` have landed
-    auto wait_all_but = [&](int loads) {
-        if (loads >= 24) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
-        else if (loads >= 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-        else if (loads >= 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    // loads complete in issue order: wait until all but the youngest `tiles` whole tiles have landed
+    auto wait_all_but = [&](int tiles) {
+        if (tiles >= 3 && S_AHEAD > 3) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(3 * PER_TILE) : "memory");
+        else if (tiles >= 2 && S_AHEAD > 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * PER_TILE) : "memory");
+        else if (tiles >= 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PER_TILE) : "memory");
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     };
-    wait_all_but(8 * (nk - 1 < S_AHEAD - 1 ? nk - 1 : S_AHEAD - 1) + (S_AHEAD < nk ? 4 : 0));   // tile 0
+    wait_all_but(nk - 1 < S_AHEAD - 1 ? nk - 1 : S_AHEAD - 1);   // tile 0 (the A half of tile AHEAD, if any, may fly on as well)
     __builtin_amdgcn_s_barrier();
 #pragma unroll
-    for (int u = 0; u < 8; ++u) read_unit(0, 0, u);
+    for (int u = 0; u < UNITS; ++u) read_unit(0, 0, u);
 
-    // One K-step = 2 k-slices x 16 MFMAs, each MFMA followed by one side instruction (a B fragment of the
-    // [K,N] layout being two reads):
-    //   first half   8 fragment reads of slice 1; then the B half of tile kt+4 (M0 write and load alternating)
+    // One K-step = 2 k-slices x 4*NI MFMAs, each MFMA followed by at most one side instruction (a B fragment
+    // of the [K,N] layout being two reads):
+    //   first half   NI + 4 fragment reads of slice 1; then the B half of tile kt+AHEAD (M0 write and load
+    //                alternating)
     //   barrier      behind vmcnt: tile kt+1 has landed for every wavefront; nobody reads tile kt any more
-    //                (its fragments are in registers), so its slot can take the A half of tile kt+5
-    //   second half  8 fragment reads of slice 0 of tile kt+1; then the A half of tile kt+5
-    // LOAD_B / LOAD_A / NEXT: tiles kt+4 / kt+5 / kt+1 exist (compile time: no branch inside a step).
+    //                (its fragments are in registers), so its slot can take the A half of tile kt+STAGES
+    //   second half  NI + 4 fragment reads of slice 0 of tile kt+1; then the A half of tile kt+STAGES
+    // LOAD_B / LOAD_A / NEXT: tiles kt+AHEAD / kt+STAGES / kt+1 exist (compile time: no branch inside a step).
     uint32_t o_cur = 0, o_next = S_STAGE_BYTES, o_b4 = S_AHEAD * S_STAGE_BYTES;   // byte offsets of the slots of tiles kt, kt+1, kt+4
     int kt = 0;
     auto step = [&](auto load_b_c, auto load_a_c, auto next_c) {
@@ -725,28 +741,28 @@ __device__ __forceinline__ void small_gemm_body(const GemmArgs& p) {
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
             if (ks == 1) {
-                // issued and not needed yet: whole tiles kt+2 .. kt+4 that exist
-                if (LOAD_B) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
-                else if (NEXT) wait_all_but(8 * (nk - 2 - kt));
+                // issued and not needed yet: the whole tiles kt+2 .. kt+AHEAD that exist
+                if (LOAD_B) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S_AHEAD - 1) * PER_TILE) : "memory");
+                else if (NEXT) wait_all_but(nk - 2 - kt);
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 __builtin_amdgcn_s_barrier();
                 __builtin_amdgcn_sched_barrier(0);
             }
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < NI; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int sl = i * 4 + j;     // slot within the half
                     // B fragment first: a lane holds 4 consecutive columns of one row
                     LAGOM_MFMA_16x16x32(acc[i][j], b_frag(ks, j), fa[ks][i]);
                     __builtin_amdgcn_sched_barrier(0);
-                    if (sl < 8) {
+                    if (sl < UNITS) {
                         if (ks == 0) read_unit(o_cur, 1, sl);
                         else if (NEXT) read_unit(o_next, 0, sl);
                     } else {
-                        const int d = (sl - 8) >> 1;
-                        if (ks == 0 && LOAD_B) { if (sl & 1) load_m0(g_b, b_off[d]); else set_m0(l_b + d * 4096); }
-                        if (ks == 1 && LOAD_A) { if (sl & 1) load_m0(g_a, a_off[d]); else set_m0(l_a + d * 4096); }
+                        const int d = (sl - UNITS) >> 1, odd = (sl - UNITS) & 1;
+                        if (ks == 0 && LOAD_B && d < LB) { if (odd) load_m0(g_b, b_off[d]); else set_m0(l_b + d * 4096); }
+                        if (ks == 1 && LOAD_A && d < LA) { if (odd) load_m0(g_a, a_off[d]); else set_m0(l_a + d * 4096); }
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -758,31 +774,35 @@ __device__ __forceinline__ void small_gemm_body(const GemmArgs& p) {
         o_b4 = o_b4 + S_STAGE_BYTES == S_STAGES * S_STAGE_BYTES ? 0 : o_b4 + S_STAGE_BYTES;
         ++kt;
     };
-    while (kt + 5 < nk) step(std::true_type{}, std::true_type{}, std::true_type{});
-    // at most five steps are left, peeled in straight-line code (a loop over step variants makes the register
+    while (kt + S_STAGES < nk) step(std::true_type{}, std::true_type{}, std::true_type{});
+    // at most STAGES steps are left, peeled in straight-line code (a loop over step variants makes the register
     // allocator copy accumulators between them, with none of the wait states a copy behind an MFMA needs)
-    if (kt + 4 < nk) step(std::true_type{}, std::false_type{}, std::true_type{});
+    if (kt + S_AHEAD < nk) step(std::true_type{}, std::false_type{}, std::true_type{});
     if (kt + 1 < nk) step(std::false_type{}, std::false_type{}, std::true_type{});
-    if (kt + 1 < nk) step(std::false_type{}, std::false_type{}, std::true_type{});
-    if (kt + 1 < nk) step(std::false_type{}, std::false_type{}, std::true_type{});
+    if (S_AHEAD > 2) {
+        if (kt + 1 < nk) step(std::false_type{}, std::false_type{}, std::true_type{});
+        if (kt + 1 < nk) step(std::false_type{}, std::false_type{}, std::true_type{});
+    }
     if (kt < nk) step(std::false_type{}, std::false_type{}, std::false_type{});
     // wait states behind the last inline-asm MFMA, as in the large kernel
     asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < NI; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) asm volatile("" : "+a"(acc[i][j]));
     __builtin_amdgcn_s_barrier();   // every wavefront is past its last LDS read before the ring is reused below
 
-    // Epilogue: acc[i][j][v] is row 16*i + lane%16, column 16*j + 4*(lane/16) + v of the wavefront's 64 x 64
+    // Epilogue: acc[i][j][v] is row 16*i + lane%16, column 16*j + 4*(lane/16) + v of the wavefront's 16*NI x 64
     // block, staged in the wavefront's own LDS as rows of ROW_BYTES (16-byte group c of row r at c ^ (r % GROUPS))
     // and written out as 16-byte vectors, whole rows of the block contiguous.
     constexpr int ESZ = OUT_BF16 ? 2 : 4;
     constexpr int ROW_BYTES = 64 * ESZ, GROUPS = ROW_BYTES / 16, ROWS_PER_READ = 64 / GROUPS, VEC = 16 / ESZ;
-    char* st = reinterpret_cast<char*>(smem) + wave * (64 * ROW_BYTES);
+    constexpr int WROWS = 16 * NI;
+    static_assert(4 * WROWS * ROW_BYTES <= T::STAGES * T::STAGE_BYTES, "the staging areas fit the ring");
+    char* st = reinterpret_cast<char*>(smem) + wave * (WROWS * ROW_BYTES);
     const int r_in = lane & 15, c_q = 4 * (lane >> 4);
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < NI; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int r = i * 16 + r_in;
@@ -799,13 +819,13 @@ __device__ __forceinline__ void small_gemm_body(const GemmArgs& p) {
                 *reinterpret_cast<f32x4*>(dst) = acc[i][j];
             }
         }
-    const bool interior = m0 + SBM <= M && n0 + SBN <= N;
+    const bool interior = m0 + T::BM_ <= M && n0 + SBN <= N;
     const bool vector_ok = (N % VEC) == 0;
     const int rd_row = lane / GROUPS, rd_cv = lane % GROUPS;
     const int64_t gcol = n0 + wn * 64 + rd_cv * VEC;
-    const int64_t row0 = m0 + wm * 64 + rd_row;
+    const int64_t row0 = m0 + wm * WROWS + rd_row;
 #pragma unroll
-    for (int e = 0; e < GROUPS; ++e) {   // GROUPS reads of ROWS_PER_READ rows cover the 64 rows
+    for (int e = 0; e < WROWS / ROWS_PER_READ; ++e) {   // each read covers ROWS_PER_READ whole rows of the block
         const int r = rd_row + ROWS_PER_READ * e;
         const u32x4 val = *reinterpret_cast<const u32x4*>(st + r * ROW_BYTES + ((rd_cv ^ (r & (GROUPS - 1))) << 4));
         const int64_t grow = row0 + ROWS_PER_READ * e;
@@ -824,9 +844,14 @@ __device__ __forceinline__ void small_gemm_body(const GemmArgs& p) {
 }
 
 template <bool OUT_BF16>
-__global__ void __launch_bounds__(THREADS) gemm_bf16_nk128_kernel(const GemmArgs p) { small_gemm_body<false, OUT_BF16>(p); }
+__global__ void __launch_bounds__(THREADS) gemm_bf16_nk128_kernel(const GemmArgs p) { small_gemm_body<4, false, OUT_BF16>(p); }
 template <bool OUT_BF16>
-__global__ void __launch_bounds__(THREADS) gemm_bf16_kn128_kernel(const GemmArgs p) { small_gemm_body<true, OUT_BF16>(p); }
+__global__ void __launch_bounds__(THREADS) gemm_bf16_kn128_kernel(const GemmArgs p) { small_gemm_body<4, true, OUT_BF16>(p); }
+// 256 x 128 tiles
+template <bool OUT_BF16>
+__global__ void __launch_bounds__(THREADS) gemm_bf16_nk256x128_kernel(const GemmArgs p) { small_gemm_body<8, false, OUT_BF16>(p); }
+template <bool OUT_BF16>
+__global__ void __launch_bounds__(THREADS) gemm_bf16_kn256x128_kernel(const GemmArgs p) { small_gemm_body<8, true, OUT_BF16>(p); }
 
 template <void (*KERNEL)(const GemmArgs)>
 int launch_fast(const GemmArgs& a, dim3 grid, hipStream_t st) {
@@ -837,11 +862,16 @@ int launch_fast(const GemmArgs& a, dim3 grid, hipStream_t st) {
     return LAGOM_OK;
 }
 
-// 128 x 128 tiles when they still fit the chip in one round (256 compute units), i.e. when 256 x 256 tiles
-// would leave three quarters of it idle.
-bool small_tiles(int64_t M, int64_t N, int64_t K) {
-    const int64_t n128 = ((M + SBM - 1) / SBM) * ((N + SBN - 1) / SBN);
-    return n128 <= 256 && K % BK == 0 && K <= FAST_MAX_K;
+// The smallest tile that still covers C in one round of workgroups (256 compute units): 128 x 128, else
+// 256 x 128, else 256 x 256.  Fewer, larger tiles would leave compute units idle; smaller tiles in several
+// rounds lose more to their lower arithmetic intensity than they gain.
+enum Tiling { TILE_128x128, TILE_256x128, TILE_256x256 };
+Tiling choose_tiling(int64_t M, int64_t N, int64_t K) {
+    if (K % BK != 0 || K > FAST_MAX_K) return TILE_256x256;
+    const int64_t cols = (N + SBN - 1) / SBN;
+    if (((M + SBM - 1) / SBM) * cols <= 256) return TILE_128x128;
+    if (((M + MBM - 1) / MBM) * cols <= 256) return TILE_256x128;
+    return TILE_256x256;
 }
 
 }  // namespace
@@ -861,8 +891,8 @@ int check_gemm_args(const void* A, const void* B, const void* C, int64_t M, int6
 extern "C" int lagom_gemm_describe(int64_t M, int64_t N, int64_t K, lagom_dtype out_dt, lagom_gemm_geometry* out) {
     if (!out || M < 1 || N < 1 || K < 1 || lagom::elem_size(out_dt) == 0) return lagom::fail(LAGOM_EINVAL, "bad argument");
     // the tiling lagom_gemm uses for this shape (it does not depend on B's layout)
-    const bool small = small_tiles(M, N, K);
-    const int64_t bm = small ? SBM : BM, bn = small ? SBN : BN;
+    const Tiling tiling = choose_tiling(M, N, K);
+    const int64_t bm = tiling == TILE_128x128 ? SBM : BM, bn = tiling == TILE_256x256 ? BN : SBN;
     const int64_t tm = (M + bm - 1) / bm, tn = (N + bn - 1) / bn;
     out->mu = tm * tn;
     out->tb = 1;   // either kernel takes all of a compute unit's LDS: one workgroup per compute unit
@@ -891,14 +921,22 @@ extern "C" int lagom_gemm(const void* A, const void* B, void* C, int64_t M, int6
                           int b_is_nk, lagom_dtype out_dt, void* hip_stream) {
     if (int rc = lagom::check_gemm_args(A, B, C, M, N, K, out_dt)) return rc;
     if (!b_is_nk && (N % 8)) return lagom::fail(LAGOM_EINVAL, "B stored [K,N] needs N to be a multiple of 8");
-    if (small_tiles(M, N, K)) {
+    const Tiling tiling = choose_tiling(M, N, K);
+    if (tiling != TILE_256x256) {
+        const int bm = tiling == TILE_128x128 ? SBM : MBM;
         GemmArgs a{static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(B), C, M, N, K,
-                   (int32_t)((M + SBM - 1) / SBM), (int32_t)((N + SBN - 1) / SBN)};
+                   (int32_t)((M + bm - 1) / bm), (int32_t)((N + SBN - 1) / SBN)};
         const dim3 grid((unsigned)(a.tiles_m * a.tiles_n));
         hipStream_t st = static_cast<hipStream_t>(hip_stream);
+        const bool bf = out_dt == LAGOM_BF16;
         int rc;
-        if (b_is_nk) rc = out_dt == LAGOM_BF16 ? launch_fast<gemm_bf16_nk128_kernel<true>>(a, grid, st) : launch_fast<gemm_bf16_nk128_kernel<false>>(a, grid, st);
-        else rc = out_dt == LAGOM_BF16 ? launch_fast<gemm_bf16_kn128_kernel<true>>(a, grid, st) : launch_fast<gemm_bf16_kn128_kernel<false>>(a, grid, st);
+        if (tiling == TILE_128x128) {
+            if (b_is_nk) rc = bf ? launch_fast<gemm_bf16_nk128_kernel<true>>(a, grid, st) : launch_fast<gemm_bf16_nk128_kernel<false>>(a, grid, st);
+            else rc = bf ? launch_fast<gemm_bf16_kn128_kernel<true>>(a, grid, st) : launch_fast<gemm_bf16_kn128_kernel<false>>(a, grid, st);
+        } else {
+            if (b_is_nk) rc = bf ? launch_fast<gemm_bf16_nk256x128_kernel<true>>(a, grid, st) : launch_fast<gemm_bf16_nk256x128_kernel<false>>(a, grid, st);
+            else rc = bf ? launch_fast<gemm_bf16_kn256x128_kernel<true>>(a, grid, st) : launch_fast<gemm_bf16_kn256x128_kernel<false>>(a, grid, st);
+        }
         if (rc) return rc;
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return lagom::fail(LAGOM_EHIP, "gemm launch: %s", hipGetErrorString(e));

@@ -13,6 +13,8 @@ from paper_2602_20656_amd import build as lb
 
 KERNELS = tuple("gemm_bf16_%s_kernelILb%dE" % (k, o) for k in ("nk", "kn", "nk_tail", "kn_tail") for o in (1, 0))
 SMALL = tuple("gemm_bf16_%s128_kernelILb%dE" % (k, o) for k in ("nk", "kn") for o in (1, 0))   # 128 x 128 tiles, 64 accumulators
+MEDIUM = tuple("gemm_bf16_%s256x128_kernelILb%dE" % (k, o) for k in ("nk", "kn") for o in (1, 0))   # 256 x 128 tiles, 128 accumulators
+ACCS = {**{k: 256 for k in KERNELS}, **{k: 64 for k in SMALL}, **{k: 128 for k in MEDIUM}}
 AGPR = re.compile(r"\ba(\[\d+:\d+\]|\d+)\b")
 
 
@@ -38,12 +40,12 @@ def _metadata(text, sym):
     raise AssertionError(sym)
 
 
-@pytest.mark.parametrize("name", KERNELS + SMALL)
+@pytest.mark.parametrize("name", KERNELS + SMALL + MEDIUM)
 def test_no_spills_and_all_agprs_for_accumulators(assembly, name):
     sym, _ = _body(assembly, name)
     meta = _metadata(assembly, sym)
     assert meta["vgpr_spill_count"] == "0" and meta["sgpr_spill_count"] == "0", meta
-    assert meta["agpr_count"] == ("64" if name in SMALL else "256"), meta
+    assert meta["agpr_count"] == str(ACCS[name]), meta
     assert meta["private_segment_fixed_size"] == "0", meta
 
 
@@ -63,11 +65,11 @@ def _blocks(lines):
     return blocks
 
 
-@pytest.mark.parametrize("name", KERNELS + SMALL)
+@pytest.mark.parametrize("name", KERNELS + SMALL + MEDIUM)
 def test_only_mfmas_touch_accumulators_until_the_wait_states(assembly, name):
     _, lines = _body(assembly, name)
     mfma = [i for i, l in enumerate(lines) if l.startswith("v_mfma_f32_16x16x32_bf16")]
-    assert len(mfma) >= (32 if name in SMALL else 3 * 128)        # large kernels: steady-state step and the two peeled steps
+    assert len(mfma) >= 3 * ACCS[name] // 2        # the steady-state step and at least two peeled steps
     nop = next(i for i in range(mfma[-1], len(lines)) if lines[i].startswith("s_nop 7"))
     assert lines[nop + 1].startswith("s_nop 7") and lines[nop + 2].startswith("s_nop 7")
     for falls_in, block in _blocks(lines[mfma[0]:nop]):
@@ -116,8 +118,9 @@ def test_steady_state_step_is_branch_free_with_one_side_instruction_per_mfma(ass
     assert lead + run <= 24, (lead, run)
 
 
-@pytest.mark.parametrize("name", SMALL)
+@pytest.mark.parametrize("name", SMALL + MEDIUM)
 def test_small_tile_step_has_one_side_instruction_per_mfma(assembly, name):
+    ni = 4 if name in SMALL else 8          # A fragments per wavefront and k-slice; 4 B fragments
     _, lines = _body(assembly, name)
     lines = [l for l in lines if l]
     first = next(i for i, l in enumerate(lines) if l.startswith("v_mfma"))
@@ -125,13 +128,13 @@ def test_small_tile_step_has_one_side_instruction_per_mfma(assembly, name):
     label = lines[back].split()[-1] + ":"
     head = max(i for i in range(first) if lines[i].startswith(label))
     body = [l for l in lines[head + 1:back] if not l.endswith(":")]
-    assert sum(l.startswith("v_mfma") for l in body) == 32
-    assert sum(l.startswith("global_load_lds_dwordx4") for l in body) == 8
+    assert sum(l.startswith("v_mfma") for l in body) == 2 * ni * 4
+    assert sum(l.startswith("global_load_lds_dwordx4") for l in body) == ni + 4
     assert sum(l.startswith("s_barrier") for l in body) == 1
-    if "_nk128_" in name:
-        assert sum(l.startswith("ds_read_b128") for l in body) == 16
-    else:   # B stored [K,N]: 8 reads of A, 2 x 8 transposing reads of B
-        assert sum(l.startswith("ds_read_b128") for l in body) == 8
+    if "_nk" in name:
+        assert sum(l.startswith("ds_read_b128") for l in body) == 2 * (ni + 4)
+    else:   # B stored [K,N]: reads of A, 2 x 8 transposing reads of B
+        assert sum(l.startswith("ds_read_b128") for l in body) == 2 * ni
         assert sum(l.startswith("ds_read_b64_tr_b16") for l in body) == 16
     run, worst, seen = 0, 0, False
     for l in body:

@@ -33,8 +33,10 @@ def _gemm(a_bits, b_bits, b_is_nk, out):
 
 @pytest.mark.parametrize("M,N,K", [(512, 512, 512), (1, 1, 8), (300, 200, 136), (700, 520, 264), (256, 256, 64),
                                    (257, 255, 72), (33, 1000, 4096), (130, 77, 128), (513, 260, 192), (700, 300, 320), (1000, 520, 256), (300, 300, 64),
-                                   # more than 256 tiles of 128 x 128: the 256 x 256 kernels, ragged in M and N, 1 to 3 K-steps, a K tail
-                                   (2100, 2200, 192), (2100, 2200, 64), (2312, 1800, 136), (1800, 2440, 128)])
+                                   # more than 256 tiles of 128 x 128 but not of 256 x 128: the 256 x 128 kernels, ragged, 1 to 4 K-steps
+                                   (2100, 2200, 192), (2100, 2200, 64), (1800, 2440, 128), (2312, 1800, 256),
+                                   # more than 256 tiles of 256 x 128, or a K tail: the 256 x 256 kernels, ragged in M and N
+                                   (2100, 3720, 192), (2100, 3720, 64), (2312, 1800, 136)])
 @pytest.mark.parametrize("b_is_nk", [True, False])
 @pytest.mark.parametrize("out", ["bf16", "f32"])
 def test_gemm_small_shapes(M, N, K, b_is_nk, out):
@@ -87,12 +89,12 @@ def test_gemm_integer_inputs_are_exact():
 
 
 @pytest.mark.parametrize("M,N,K", [(260, 272, 320), (100, 8, 64), (256, 776, 128), (513, 264, 192), (64, 1032, 576),
-                                   (2100, 2056, 128), (2304, 2312, 320)])
+                                   (2100, 2056, 128), (2304, 2312, 320), (2100, 3720, 128)])
 @pytest.mark.parametrize("out", ["bf16", "f32"])
 def test_gemm_b_kn_integer_inputs_are_exact(M, N, K, out):
     """B stored [K,N] with K a multiple of 64 takes the kernel whose LDS reads transpose B: any mix-up of
-    rows, columns or k order shows as a wrong integer.  One to nine K-steps, ragged M and N tiles, N = 8; the last
-    two shapes have more than 256 tiles of 128 x 128 and run on 256 x 256 tiles, the others on the small ones."""
+    rows, columns or k order shows as a wrong integer.  One to nine K-steps, ragged M and N tiles, N = 8; the
+    last three shapes run on 256 x 128 (two) and 256 x 256 tiles, the others on 128 x 128."""
     rng = np.random.default_rng(M + N + K)
     ai = rng.integers(-3, 4, size=(M, K)); bi = rng.integers(-3, 4, size=(K, N))
     a, b = inputs.to_bf16_bits(ai.astype(np.float32)), inputs.to_bf16_bits(bi.astype(np.float32))

@@ -48,7 +48,11 @@ def test_host_only_helpers():
     few = lg.lagom_gemm_describe(100, 300, 64)
     assert (few.tile_m, few.tile_n, few.mu, few.tb) == (128, 128, 1 * 3, 1)
     assert few.d_bytes == (128 + 128) * 64 * 2 + 128 * 128 * 2
-    assert lg.lagom_gemm_describe(2048, 2048, 4096).mu == 256 and lg.lagom_gemm_describe(2048, 2176, 4096).tile_m == 256
+    assert lg.lagom_gemm_describe(2048, 2048, 4096).mu == 256
+    mid = lg.lagom_gemm_describe(2048, 2176, 4096)             # 272 tiles of 128 x 128, 136 of 256 x 128
+    assert (mid.tile_m, mid.tile_n, mid.mu) == (256, 128, 8 * 17)
+    assert mid.d_bytes == (256 + 128) * 4096 * 2 + 256 * 128 * 2
+    assert lg.lagom_gemm_describe(3072, 3072, 3072).tile_n == 256   # 288 tiles of 256 x 128: the large tiling
     assert lg.lagom_gemm_describe(512, 512, 72).tile_m == 256       # ragged K stays on the large tiles
     # bytes past an XCD's L2: the 32 tiles an XCD holds at a time form an 8 x 4 block -> A panels shared by 4, B by 8
     for M, N, K in [(4096, 4096, 4096), (8192, 4096, 4096), (8192, 8192, 8192)]:
