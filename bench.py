@@ -26,9 +26,9 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 BF16_PEAK_TFLOPS = 2500.0       # MI355X dense bf16 MFMA, published
 LAMBDA = 256                    # compute units
 # Bytes past L2 per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by the same counters' reading of a plain
-# 64 MiB copy (factors 1.9984 and 0.9992); figures and commands: profiles/bench_dp_bucket_hbm_counters.md
+# 64 MiB copy (factors 1.9986 and 0.9994); figures and commands: profiles/bench_dp_bucket_hbm_counters.md
 MEASURED_TRAFFIC_BYTES = {
-    "gemm 4096x4096x4096": int(224.2 * (1 << 20)),
+    "gemm 4096x4096x4096": int(224.3 * (1 << 20)),
     "reduce_copy bf16 S=8 D=1 count=4194304": int(72.0 * (1 << 20)),
     "reduce_copy f32 S=2 D=1 count=4194304": int(48.0 * (1 << 20)),
 }
@@ -172,17 +172,7 @@ def standalone_comm_roofline(st1, st2, iters, final_iters=20):
                                 "us_per_launch": us, "bytes_per_launch": per_launch, "cfg": [nc, nt, chunk],
                                 "rotation_mib": nrot * per_launch >> 20}
         del bufs, launches
-    # the figure that is reported: the winning configuration once more, final_iters passes of nrot launches each
-    # (these are the last dispatches of that kernel in a trace of this run)
     name, dt, tdt, nsrc, count, nrot = best_shape
-    bufs = [[torch.empty(count, dtype=torch.float32, device="cuda").uniform_(-1, 1).to(tdt) for _ in range(nsrc + 1)]
-            for _ in range(nrot)]
-    launches = [lg.CommLaunch(lg.LAGOM_REDUCE_COPY, dt, b[:nsrc], [b[nsrc]], count, 0) for b in bufs]
-    t = lg.lagom_overlap_run(launches, [tuple(best["cfg"])], [], st1, st2, 2, final_iters, lg.LAGOM_ALONE_COMM)
-    us = t.X_us / nrot
-    best.update({"achieved": best["bytes_per_launch"] / us / 1e3, "frac": best["bytes_per_launch"] / us / 1e3 / HBM_PEAK_GBPS,
-                 "us_per_launch": us, "launches_timed": nrot * final_iters})
-    del bufs, launches
     # context only: the same operator on an 8 times longer buffer (576 MiB per launch, two rotated sets), where the
     # fixed cost of a launch weighs less: what the kernel sustains once a launch is long enough
     try:
@@ -221,6 +211,16 @@ def standalone_comm_roofline(st1, st2, iters, final_iters=20):
         del pairs
     except RuntimeError:
         best.update({"vendor_copy_us_per_launch": None, "vendor_copy_gbps": None})
+    # the figure that is reported, measured last: the winning configuration once more, final_iters passes of nrot launches each
+    # (these are the last dispatches of that kernel in a trace of this run)
+    bufs = [[torch.empty(count, dtype=torch.float32, device="cuda").uniform_(-1, 1).to(tdt) for _ in range(nsrc + 1)]
+            for _ in range(nrot)]
+    launches = [lg.CommLaunch(lg.LAGOM_REDUCE_COPY, dt, b[:nsrc], [b[nsrc]], count, 0) for b in bufs]
+    t = lg.lagom_overlap_run(launches, [tuple(best["cfg"])], [], st1, st2, 2, final_iters, lg.LAGOM_ALONE_COMM)
+    us = t.X_us / nrot
+    best.update({"achieved": best["bytes_per_launch"] / us / 1e3, "frac": best["bytes_per_launch"] / us / 1e3 / HBM_PEAK_GBPS,
+                 "us_per_launch": us, "launches_timed": nrot * final_iters})
+    del bufs, launches
     return best
 
 
@@ -268,6 +268,10 @@ def main():
     ap.add_argument("--dependent", action="store_true",
                     help="fsdp_chain only: GEMM i (i > 0) consumes the weight gathered by communication i-1 and waits for it")
     ap.add_argument("--dump", default=None, help="write the sweep table and tuner traces to this JSON file")
+    ap.add_argument("--standalone-only", action="store_true",
+                    help="run every kernel of the benchmark alone (the sweep's communication launches, the GEMM, the standalone "
+                         "roofline passes, the calibration copy) and nothing that needs two kernels at once: the form to run under "
+                         "rocprofv3 --pmc, which serialises dispatches")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build covers one GPU's share of the overlapped step; run with --gpus 1 "
@@ -278,7 +282,7 @@ def main():
     from paper_2602_20656_amd import binding as lg
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
-    s_comm, s_comp = lg.overlapping_streams()
+    s_comm, s_comp = (torch.cuda.Stream(), torch.cuda.Stream()) if args.standalone_only else lg.overlapping_streams()
 
     dependent = args.dependent and args.workload == "fsdp_chain"
     w, launches, comps, ncomm, keep, (dep_arg, dep_comm) = build_workload(args.workload, dependent)
@@ -289,6 +293,20 @@ def main():
 
     # ---- contention profiler over the workload's grid (NT fixed at 256 unless the workload sweeps it)
     points = [(nc, nt, c) for nt in w.nt_grid for nc in w.nc_grid for c in w.chunk_grid]
+    if args.standalone_only:
+        comm_alone = [lg.lagom_overlap_run(launches, [p] * ncomm, comps, s_comm, s_comp, 1, args.sweep_iters, lg.LAGOM_ALONE_COMM).X_us
+                      for p in points]
+        t_gemm = lg.lagom_overlap_run(launches, [DEFAULT_CFG] * ncomm, comps, s_comm, s_comp, args.warmup, args.steps, lg.LAGOM_ALONE_COMP)
+        gemm_us = t_gemm.Y_us / len(comps)
+        roofline_comm = standalone_comm_roofline(s_comm, s_comp, 5)
+        cal_src = torch.empty(16 << 20, dtype=torch.float32, device="cuda").uniform_(-1, 1)
+        cal_dst = torch.empty_like(cal_src)
+        lg.lagom_comm_kernel(lg.LAGOM_GATHER_COPY, lg.LAGOM_F32, [cal_src], [cal_dst], 16 << 20, (1000, 512, 64 << 10), s_comm)
+        torch.cuda.synchronize()
+        print(json.dumps({"mode": "standalone-only", "config": {"workload": args.workload}, "gemm_alone_us": gemm_us,
+                          "gemm_mfma_util": flops / gemm_us / 1e6 / BF16_PEAK_TFLOPS, "roofline_comm": roofline_comm,
+                          "fastest_comm_alone_us": min(comm_alone), "sweep_points": len(points)}))
+        return
     t0 = time.perf_counter()
     sweep = lg.lagom_contention_sweep(launches, ncomm, comps, points, s_comm, s_comp, 1, args.sweep_iters)
     sweep_s = time.perf_counter() - t0
