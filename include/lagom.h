@@ -94,8 +94,8 @@ int lagom_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, int6
 /* Workgroup geometry of lagom_gemm for a problem size, as the cost model needs it
  * (Eq. 5-6: mu = total workgroups, TB = workgroups resident per compute unit,
  * D = bytes each workgroup reads and writes).  The tiling depends on the size only: the smallest
- * of 128 x 128, 256 x 128 and 256 x 256 of which at most 256 tiles cover C (256 x 256 whenever K
- * is no multiple of 64).  Host only. */
+ * of 128 x 128, 256 x 128 and 256 x 256 of which at most 256 tiles cover C (256 x 256 whenever
+ * K < 64 or K > 2^22).  Host only. */
 typedef struct {
     int64_t mu;
     int32_t tb;

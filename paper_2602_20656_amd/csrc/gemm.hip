@@ -4,8 +4,8 @@
 // Tiling: one workgroup of 256 threads (4 wavefronts, 2 x 2) owns a 256 x 256 tile of C and
 // walks K in steps of 64; each wavefront owns a 128 x 128 block, i.e. 256 fp32 accumulators per
 // lane (the whole AGPR file), so one workgroup is resident per compute unit.  Products that at
-// most 256 tiles of 128 x 128 or of 256 x 128 cover (and K a multiple of 64) use those instead:
-// 256 x 256 tiles would leave compute units idle (see the small-tile kernels below).
+// most 256 tiles of 128 x 128 or of 256 x 128 cover use those instead: 256 x 256 tiles would
+// leave compute units idle (see the small-tile kernels below).
 // Workgroup ids are remapped so that the workgroups of one XCD (ids equal modulo 8) cover a
 // compact block of tiles and share A/B panels in that XCD's L2.
 //
@@ -606,7 +606,8 @@ constexpr int SBM = SmallTile<4>::BM_, MBM = SmallTile<8>::BM_;
 // c ^ kn_swz128(k), which spreads the rows of a transposing read over the 8 32-byte windows of a row.
 __device__ __forceinline__ int kn_swz128(int k) { return (((k >> 3) & 1) << 3) | ((k & 3) << 1); }
 
-template <int NI, bool B_KN, bool OUT_BF16>
+// K_TAIL: K is not a multiple of 64; the last K % 64 columns get a step of their own (see the large kernel).
+template <int NI, bool B_KN, bool OUT_BF16, bool K_TAIL>
 __device__ __forceinline__ void small_gemm_body(const GemmArgs& p) {
     typedef SmallTile<NI> T;
     constexpr int S_STAGES = T::STAGES, S_AHEAD = T::AHEAD, S_STAGE_BYTES = T::STAGE_BYTES, S_OPERAND_BYTES = T::A_BYTES;
@@ -784,6 +785,53 @@ __device__ __forceinline__ void small_gemm_body(const GemmArgs& p) {
         if (kt + 1 < nk) step(std::false_type{}, std::false_type{}, std::true_type{});
     }
     if (kt < nk) step(std::false_type{}, std::false_type{}, std::false_type{});
+    if (K_TAIL) {
+        // Every wavefront is past the barrier of the last step, behind which nothing reads LDS and no
+        // LDS-direct load is in flight: the first slot takes the zero-filled rest of K in the loop's layout.
+        const int64_t kbase = (int64_t)nk * BK;
+        u32x4 ta[LA], tb[LB];
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int i = 0; i < LA; ++i) {
+            const int id = tid + THREADS * i;
+            const int64_t gm = m0 + (id >> 3), gk = kbase + (id & 7) * 8;
+            ta[i] = (gm < M && gk < K) ? *reinterpret_cast<const u32x4*>(p.A + gm * K + gk) : zero;
+        }
+#pragma unroll
+        for (int i = 0; i < LB; ++i) {
+            const int id = tid + THREADS * i;
+            if (B_KN) {
+                const int64_t bk = kbase + (id >> 4), gn = n0 + (id & 15) * 8;
+                tb[i] = (bk < K && gn < N) ? *reinterpret_cast<const u32x4*>(p.B + bk * N + gn) : zero;
+            } else {
+                const int64_t gn = n0 + (id >> 3), gk = kbase + (id & 7) * 8;
+                tb[i] = (gn < N && gk < K) ? *reinterpret_cast<const u32x4*>(p.B + gn * K + gk) : zero;
+            }
+        }
+        u32x4* slot_b = smem + S_OPERAND_BYTES / 16;
+#pragma unroll
+        for (int i = 0; i < LA; ++i) {
+            const int id = tid + THREADS * i;
+            smem[swz64(id >> 3, id & 7)] = ta[i];
+        }
+#pragma unroll
+        for (int i = 0; i < LB; ++i) {
+            const int id = tid + THREADS * i;
+            if (B_KN) slot_b[(id >> 4) * 16 + ((id & 15) ^ kn_swz128(id >> 4))] = tb[i];
+            else slot_b[swz64(id >> 3, id & 7)] = tb[i];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            if (ks == 1 && K - kbase <= 32) break;
+#pragma unroll
+            for (int u = 0; u < UNITS; ++u) read_unit(0, 0 + ks, u);
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) LAGOM_MFMA_16x16x32(acc[i][j], b_frag(ks, j), fa[ks][i]);
+        }
+    }
     // wait states behind the last inline-asm MFMA, as in the large kernel
     asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
 #pragma unroll
@@ -844,14 +892,23 @@ __device__ __forceinline__ void small_gemm_body(const GemmArgs& p) {
 }
 
 template <bool OUT_BF16>
-__global__ void __launch_bounds__(THREADS) gemm_bf16_nk128_kernel(const GemmArgs p) { small_gemm_body<4, false, OUT_BF16>(p); }
+__global__ void __launch_bounds__(THREADS) gemm_bf16_nk128_kernel(const GemmArgs p) { small_gemm_body<4, false, OUT_BF16, false>(p); }
 template <bool OUT_BF16>
-__global__ void __launch_bounds__(THREADS) gemm_bf16_kn128_kernel(const GemmArgs p) { small_gemm_body<4, true, OUT_BF16>(p); }
+__global__ void __launch_bounds__(THREADS) gemm_bf16_kn128_kernel(const GemmArgs p) { small_gemm_body<4, true, OUT_BF16, false>(p); }
 // 256 x 128 tiles
 template <bool OUT_BF16>
-__global__ void __launch_bounds__(THREADS) gemm_bf16_nk256x128_kernel(const GemmArgs p) { small_gemm_body<8, false, OUT_BF16>(p); }
+__global__ void __launch_bounds__(THREADS) gemm_bf16_nk256x128_kernel(const GemmArgs p) { small_gemm_body<8, false, OUT_BF16, false>(p); }
 template <bool OUT_BF16>
-__global__ void __launch_bounds__(THREADS) gemm_bf16_kn256x128_kernel(const GemmArgs p) { small_gemm_body<8, true, OUT_BF16>(p); }
+__global__ void __launch_bounds__(THREADS) gemm_bf16_kn256x128_kernel(const GemmArgs p) { small_gemm_body<8, true, OUT_BF16, false>(p); }
+// K >= 64 and not a multiple of 64
+template <bool OUT_BF16>
+__global__ void __launch_bounds__(THREADS) gemm_bf16_nk128_tail_kernel(const GemmArgs p) { small_gemm_body<4, false, OUT_BF16, true>(p); }
+template <bool OUT_BF16>
+__global__ void __launch_bounds__(THREADS) gemm_bf16_kn128_tail_kernel(const GemmArgs p) { small_gemm_body<4, true, OUT_BF16, true>(p); }
+template <bool OUT_BF16>
+__global__ void __launch_bounds__(THREADS) gemm_bf16_nk256x128_tail_kernel(const GemmArgs p) { small_gemm_body<8, false, OUT_BF16, true>(p); }
+template <bool OUT_BF16>
+__global__ void __launch_bounds__(THREADS) gemm_bf16_kn256x128_tail_kernel(const GemmArgs p) { small_gemm_body<8, true, OUT_BF16, true>(p); }
 
 template <void (*KERNEL)(const GemmArgs)>
 int launch_fast(const GemmArgs& a, dim3 grid, hipStream_t st) {
@@ -867,7 +924,7 @@ int launch_fast(const GemmArgs& a, dim3 grid, hipStream_t st) {
 // rounds lose more to their lower arithmetic intensity than they gain.
 enum Tiling { TILE_128x128, TILE_256x128, TILE_256x256 };
 Tiling choose_tiling(int64_t M, int64_t N, int64_t K) {
-    if (K % BK != 0 || K > FAST_MAX_K) return TILE_256x256;
+    if (K < BK || K > FAST_MAX_K) return TILE_256x256;
     const int64_t cols = (N + SBN - 1) / SBN;
     if (((M + SBM - 1) / SBM) * cols <= 256) return TILE_128x128;
     if (((M + MBM - 1) / MBM) * cols <= 256) return TILE_256x128;
@@ -929,14 +986,17 @@ extern "C" int lagom_gemm(const void* A, const void* B, void* C, int64_t M, int6
         const dim3 grid((unsigned)(a.tiles_m * a.tiles_n));
         hipStream_t st = static_cast<hipStream_t>(hip_stream);
         const bool bf = out_dt == LAGOM_BF16;
+        const bool tail = K % BK != 0;
         int rc;
+#define LAGOM_PICK(NAME) (bf ? launch_fast<NAME<true>>(a, grid, st) : launch_fast<NAME<false>>(a, grid, st))
         if (tiling == TILE_128x128) {
-            if (b_is_nk) rc = bf ? launch_fast<gemm_bf16_nk128_kernel<true>>(a, grid, st) : launch_fast<gemm_bf16_nk128_kernel<false>>(a, grid, st);
-            else rc = bf ? launch_fast<gemm_bf16_kn128_kernel<true>>(a, grid, st) : launch_fast<gemm_bf16_kn128_kernel<false>>(a, grid, st);
+            if (b_is_nk) rc = tail ? LAGOM_PICK(gemm_bf16_nk128_tail_kernel) : LAGOM_PICK(gemm_bf16_nk128_kernel);
+            else rc = tail ? LAGOM_PICK(gemm_bf16_kn128_tail_kernel) : LAGOM_PICK(gemm_bf16_kn128_kernel);
         } else {
-            if (b_is_nk) rc = bf ? launch_fast<gemm_bf16_nk256x128_kernel<true>>(a, grid, st) : launch_fast<gemm_bf16_nk256x128_kernel<false>>(a, grid, st);
-            else rc = bf ? launch_fast<gemm_bf16_kn256x128_kernel<true>>(a, grid, st) : launch_fast<gemm_bf16_kn256x128_kernel<false>>(a, grid, st);
+            if (b_is_nk) rc = tail ? LAGOM_PICK(gemm_bf16_nk256x128_tail_kernel) : LAGOM_PICK(gemm_bf16_nk256x128_kernel);
+            else rc = tail ? LAGOM_PICK(gemm_bf16_kn256x128_tail_kernel) : LAGOM_PICK(gemm_bf16_kn256x128_kernel);
         }
+#undef LAGOM_PICK
         if (rc) return rc;
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return lagom::fail(LAGOM_EHIP, "gemm launch: %s", hipGetErrorString(e));

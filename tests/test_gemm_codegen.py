@@ -12,8 +12,8 @@ import pytest
 from paper_2602_20656_amd import build as lb
 
 KERNELS = tuple("gemm_bf16_%s_kernelILb%dE" % (k, o) for k in ("nk", "kn", "nk_tail", "kn_tail") for o in (1, 0))
-SMALL = tuple("gemm_bf16_%s128_kernelILb%dE" % (k, o) for k in ("nk", "kn") for o in (1, 0))   # 128 x 128 tiles, 64 accumulators
-MEDIUM = tuple("gemm_bf16_%s256x128_kernelILb%dE" % (k, o) for k in ("nk", "kn") for o in (1, 0))   # 256 x 128 tiles, 128 accumulators
+SMALL = tuple("gemm_bf16_%s128%s_kernelILb%dE" % (k, t, o) for k in ("nk", "kn") for t in ("", "_tail") for o in (1, 0))   # 128 x 128 tiles, 64 accumulators
+MEDIUM = tuple("gemm_bf16_%s256x128%s_kernelILb%dE" % (k, t, o) for k in ("nk", "kn") for t in ("", "_tail") for o in (1, 0))   # 256 x 128 tiles, 128 accumulators
 ACCS = {**{k: 256 for k in KERNELS}, **{k: 64 for k in SMALL}, **{k: 128 for k in MEDIUM}}
 AGPR = re.compile(r"\ba(\[\d+:\d+\]|\d+)\b")
 

@@ -36,7 +36,9 @@ def _gemm(a_bits, b_bits, b_is_nk, out):
                                    # more than 256 tiles of 128 x 128 but not of 256 x 128: the 256 x 128 kernels, ragged, 1 to 4 K-steps
                                    (2100, 2200, 192), (2100, 2200, 64), (1800, 2440, 128), (2312, 1800, 256),
                                    # more than 256 tiles of 256 x 128, or a K tail: the 256 x 256 kernels, ragged in M and N
-                                   (2100, 3720, 192), (2100, 3720, 64), (2312, 1800, 136)])
+                                   (2100, 3720, 192), (2100, 3720, 64), (2100, 3720, 136),
+                                   # K tails on the two smaller tilings
+                                   (2312, 1800, 136), (1000, 520, 328)])
 @pytest.mark.parametrize("b_is_nk", [True, False])
 @pytest.mark.parametrize("out", ["bf16", "f32"])
 def test_gemm_small_shapes(M, N, K, b_is_nk, out):
@@ -107,10 +109,11 @@ def test_gemm_b_kn_integer_inputs_are_exact(M, N, K, out):
 
 @pytest.mark.parametrize("K", [72, 96, 104, 120, 184, 4104])
 @pytest.mark.parametrize("b_is_nk", [True, False])
-@pytest.mark.parametrize("M,N", [(260, 272), (2100, 2056)])
+@pytest.mark.parametrize("M,N", [(260, 272), (2100, 2056), (2100, 3720)])
 def test_gemm_ragged_k_integer_inputs_are_exact(K, b_is_nk, M, N):
     """K >= 64 that is no multiple of 64: the LDS-direct kernels multiply the last K % 64 columns (8 to 56
-    of them, one or two 32-wide slices) in a step of their own, zero filled from K on."""
+    of them, one or two 32-wide slices) in a step of their own, zero filled from K on.  The three shapes
+    run on 128 x 128, 256 x 128 and 256 x 256 tiles."""
     if K == 4104 and M > 1000:
         pytest.skip("one long K is enough")
     rng = np.random.default_rng(K)

@@ -53,7 +53,8 @@ def test_host_only_helpers():
     assert (mid.tile_m, mid.tile_n, mid.mu) == (256, 128, 8 * 17)
     assert mid.d_bytes == (256 + 128) * 4096 * 2 + 256 * 128 * 2
     assert lg.lagom_gemm_describe(3072, 3072, 3072).tile_n == 256   # 288 tiles of 256 x 128: the large tiling
-    assert lg.lagom_gemm_describe(512, 512, 72).tile_m == 256       # ragged K stays on the large tiles
+    assert lg.lagom_gemm_describe(512, 512, 72).tile_m == 128       # K need not be a multiple of 64 for that
+    assert lg.lagom_gemm_describe(512, 512, 56).tile_m == 256       # K < 64: the general kernel's tiling
     # bytes past an XCD's L2: the 32 tiles an XCD holds at a time form an 8 x 4 block -> A panels shared by 4, B by 8
     for M, N, K in [(4096, 4096, 4096), (8192, 4096, 4096), (8192, 8192, 8192)]:
         assert lg.lagom_gemm_describe(M, N, K).d_bytes_past_l2 == (8 * 256 + 4 * 256) * K * 2 / 32 + 256 * 256 * 2
