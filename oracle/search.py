@@ -268,3 +268,114 @@ def coordinate_descent(spaces: Sequence[Space], profile: ProfileFn) -> Result:
                         break
     X = _sum(x)
     return Result(levels=[i[0] for i in idx], cfgs=cfgs_of(idx), x=x, X=X, Y=Y, Z=max(X, Y), calls=calls)
+
+
+def hide_search(spaces: Sequence[Space], profile: ProfileFn) -> Result:
+    """The computation-bound objective (Sec. 3.1, Eq. 3): once the communication is hidden the makespan is
+    Y, and Y grows with the resources the communications hold (Sec. 3.2), so the goal is the least Y
+    subject to X <= Y.  The paper's own loop (Alg. 1 driving Alg. 2) already walks up from the minimum
+    resources and stops at "X' < Y'"; this variant keeps exactly that walk and changes only what happens
+    at the stop: the baseline ends the search when X <= Y, and the first trial with X' <= Y' is kept and
+    ends the search for every communication (the lowest resources on the path that hide the
+    communication -- anything raised further can only add contention).  If no visited vector hides the
+    communication, the walk ends as Alg. 1/2 ends and its last accepted vector is returned.
+    """
+    N = len(spaces)
+    lev = [0] * N
+    H = [H_INIT] * N
+    lr: List[Optional[float]] = [None] * N
+    done = [sp.K == 1 for sp in spaces]
+    trace: List[Step] = []
+
+    x, Y = profile([sp.cfg(l) for sp, l in zip(spaces, lev)])
+    x = [float(v) for v in x]; Y = float(Y)
+    X = _sum(x); Z = max(X, Y)
+    calls = 1
+    if X <= Y:
+        done = [True] * N
+    trace.append(Step(-1, 0, 0, True, all(done), math.nan, math.nan, X, Y, Z, H_INIT, math.nan))
+
+    while not all(done):
+        j = -1
+        for i in range(N):
+            if not done[i] and (j < 0 or H[i] < H[j]):
+                j = i
+        new = next_level(spaces[j], lev[j], lr[j])
+        trial = list(lev); trial[j] = new
+        x2, Y2 = profile([sp.cfg(l) for sp, l in zip(spaces, trial)])
+        x2 = [float(v) for v in x2]; Y2 = float(Y2)
+        X2 = _sum(x2); Z2 = max(X2, Y2)
+        calls += 1
+        if x2[j] - x[j] > 0.0:
+            done[j] = True
+            accepted = False
+        elif X2 <= Y2:              # hidden: keep it, and nothing else needs raising
+            accepted = True
+            done = [True] * N
+        else:
+            accepted = True
+            H[j] = priority_metric(Y, Y2, x[j], x2[j])
+            den = x[j] - x2[j]
+            lr[j] = math.inf if x2[j] == 0.0 else den / x2[j]
+            if new == spaces[j].K - 1:
+                done[j] = True
+        trace.append(Step(j, lev[j], new, accepted, done[j], x[j], x2[j], X2, Y2, Z2, H[j],
+                          math.nan if lr[j] is None else lr[j]))
+        if accepted:
+            lev, x, Y, X, Z = trial, x2, Y2, X2, Z2
+    return Result(levels=lev, cfgs=[sp.cfg(l) for sp, l in zip(spaces, lev)],
+                  x=x, X=X, Y=Y, Z=Z, calls=calls, trace=trace)
+
+
+def brute_force_hide(spaces: Sequence[Space], profile: ProfileFn) -> Result:
+    """Exhaustive counterpart of hide_search: among the level vectors with X <= Y the smallest Y (ties:
+    smallest level sum, then lexicographic); if no vector hides the communication, the smallest Z with
+    the same tie-breaks (which is brute_force's answer)."""
+    best_hidden = None
+    best_any = None
+    calls = 0
+    for levels in itertools.product(*[range(sp.K) for sp in spaces]):
+        x, Y = profile([sp.cfg(l) for sp, l in zip(spaces, levels)])
+        x = [float(v) for v in x]; Y = float(Y)
+        X = _sum(x); Z = max(X, Y)
+        calls += 1
+        rec = (list(levels), x, X, Y, Z)
+        key_any = (Z, sum(levels), tuple(levels))
+        if best_any is None or key_any < best_any[0]:
+            best_any = (key_any, rec)
+        if X <= Y:
+            key_h = (Y, sum(levels), tuple(levels))
+            if best_hidden is None or key_h < best_hidden[0]:
+                best_hidden = (key_h, rec)
+    levels, x, X, Y, Z = (best_hidden or best_any)[1]
+    return Result(levels=levels, cfgs=[sp.cfg(l) for sp, l in zip(spaces, levels)],
+                  x=x, X=X, Y=Y, Z=Z, calls=calls)
+
+
+LADDER_FULL, LADDER_CUT, LADDER_FIXED_CHUNK = 0, 1, 2
+
+
+def ladder_chunks(chunk_grid: Sequence[int], nc_max: int, nt_ref: int, bytes_per_source: int, kind: int,
+                  alone_us=None) -> List[int]:
+    """The chunk grid a ladder is built from.  Chunk g of a launch goes to channel g mod NC (Sec. 3.2: NC
+    blocks move data at granularity C), so when chunk * nc_max exceeds the bytes a launch moves per source
+    some channels have nothing to move.  FULL: the grid; CUT: the chunks with chunk * nc_max <=
+    bytes_per_source (at least the smallest); FIXED_CHUNK: the single chunk with the smallest standalone
+    communication time at (nc_max, nt_ref), first smallest in grid order -- `alone_us` maps
+    (nc, nt, chunk) to that time."""
+    grid = list(chunk_grid)
+    if kind == LADDER_FULL:
+        return grid
+    if kind == LADDER_CUT:
+        kept = [c for c in grid if c * nc_max <= bytes_per_source]
+        return kept if kept else [grid[0]]
+    if kind == LADDER_FIXED_CHUNK:
+        best = None
+        for c in grid:
+            t = alone_us.get((nc_max, nt_ref, c))
+            if t is not None and (best is None or t < best[0]):
+                best = (t, c)
+        if best is None:
+            raise ValueError("no sweep point at (nc_max, nt_ref)")
+        return [best[1]]
+    raise ValueError("unknown ladder kind")

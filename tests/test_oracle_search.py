@@ -222,3 +222,88 @@ def test_coordinate_descent_climbs_when_more_resources_always_help_and_stays_whe
     assert up.cfgs == [(8, 256, 16384)]
     stay = os_.coordinate_descent([sp], lambda c: ([float(c[0][0] + c[0][1] + c[0][2])], 0.0))
     assert stay.cfgs == [(1, 128, 4096)] and stay.calls == 1 + 3   # one failed probe per coordinate
+
+
+# ------------------------------------------- computation-bound objective: least Y subject to X <= Y
+def test_hide_search_hand_worked_traces(golden_dir):
+    fx = json.load(open(os.path.join(golden_dir, "hide_worked.json")))
+    for case in fx["cases"]:
+        spaces, profile = _fixture_profile(case)
+        res = os_.hide_search(spaces, profile)
+        assert res.levels == case["final_levels"] and res.Y == case["final_Y"] and res.calls == case["calls"], case["name"]
+        assert len(res.trace) == len(case["trace"])
+        for got, want in zip(res.trace, case["trace"]):
+            assert (got.comm, got.level_from, got.level_to, got.accepted, got.done) == \
+                (want["comm"], want["from"], want["to"], want["accepted"], want["done"]), case["name"]
+            assert (got.X, got.Y, got.Z) == (want["X"], want["Y"], want["Z"])
+            if "H" in want:
+                assert got.H == pytest.approx(want["H"], rel=1e-15)
+        bf = os_.brute_force_hide(spaces, profile)
+        assert bf.levels == case["brute_levels"] and bf.Y == case["brute_Y"], case["name"]
+
+
+def test_hide_search_single_comm_unit_steps_equals_brute_force():
+    """One communication on a doubling ladder, x falling by less than 2x per level (so every step is one level), Y never
+    falling.  While x keeps falling the first level with X <= Y on the way up is the hiding level with the least Y, so the
+    walk and the exhaustive search agree.  When x turns before the communication is hidden, Alg. 2 stops at the turn; a
+    level beyond it can still satisfy X <= Y because Y grew, which the exhaustive search then takes -- at a makespan that
+    is never below the walk's (Y' >= X' >= x at the turn)."""
+    rng = np.random.default_rng(515)
+    hidden = differ = 0
+    for trial in range(600):
+        K = int(rng.integers(1, 9))
+        x, Y = _random_unimodal_case(rng, K)
+        if trial % 2 == 0:                               # x falls all the way
+            x = sorted(x, reverse=True)
+            x = [x[0]] + [min(b, a * 0.99) for a, b in zip(x, x[1:])]
+            x = [x[0] * 0.6 ** l for l in range(K)] if any(b < a * 0.5 for a, b in zip(x, x[1:])) else x
+        sp = _ladder(K)
+        prof = lambda cfgs: ([x[int(math.log2(cfgs[0][0]))]], Y[int(math.log2(cfgs[0][0]))])
+        hs, bf = os_.hide_search([sp], prof), os_.brute_force_hide([sp], prof)
+        assert hs.calls <= 1 + K
+        if trial % 2 == 0 or hs.X <= hs.Y:
+            assert hs.levels == bf.levels and hs.Y == bf.Y and hs.Z == bf.Z, (trial, x, Y)
+        else:
+            assert hs.Z <= bf.Z, (trial, x, Y)
+            differ += hs.levels != bf.levels
+        hidden += hs.X <= hs.Y
+    assert 100 < hidden < 600 and differ > 0             # every branch above was exercised
+
+
+def test_hide_brute_force_prefers_the_least_y_among_hidden_vectors_and_the_least_z_otherwise():
+    spaces = [os_.Space([1, 2, 4], [64], [16]), os_.Space([1, 2], [64], [16])]
+    tab = {(0, 0): (50.0, 50.0, 60.0), (0, 1): (20.0, 20.0, 70.0), (1, 0): (30.0, 30.0, 61.0), (1, 1): (10.0, 10.0, 90.0),
+           (2, 0): (29.0, 30.0, 59.5), (2, 1): (5.0, 5.0, 95.0)}                       # (x0, x1, Y)
+
+    def profile(cfgs):
+        lv = tuple(int(math.log2(c[0])) for c in cfgs)
+        return list(tab[lv][:2]), tab[lv][2]
+    # hidden: (0,1) Y=70, (1,0) Y=61, (1,1), (2,0) Y=59.5 (X=59 <= 59.5), (2,1) -> least Y is (2,0)
+    assert os_.brute_force_hide(spaces, profile).levels == [2, 0]
+    # the plain makespan objective picks the same vector here (Z = Y = 59.5)
+    assert os_.brute_force(spaces, profile).levels == [2, 0]
+    never = lambda cfgs: ([100.0 / c[0] for c in cfgs], 1.0)
+    assert os_.brute_force_hide(spaces, never).levels == os_.brute_force(spaces, never).levels == [2, 1]
+    ties = lambda cfgs: ([1.0, 1.0], 5.0)                                             # every vector hides, all Y equal
+    assert os_.brute_force_hide(spaces, ties).levels == [0, 0]
+
+
+def test_hide_search_stops_at_the_baseline_when_the_minimum_already_hides():
+    spaces = [_ladder(4), _ladder(3)]
+    res = os_.hide_search(spaces, lambda cfgs: ([10.0, 20.0], 30.0))                  # X == Y counts as hidden
+    assert res.levels == [0, 0] and res.calls == 1
+    assert os_.priority_search(spaces, lambda cfgs: ([10.0, 20.0], 30.0)).calls > 1   # Alg. 2's strict test does not stop here
+
+
+def test_ladder_chunks():
+    grid = [32768 << i for i in range(8)]                                             # 32 KiB .. 4 MiB
+    assert os_.ladder_chunks(grid, 32, 256, 3276800, os_.LADDER_FULL) == grid
+    # 3,276,800 bytes per source over 32 channels: 102,400 bytes each -> 32 KiB and 64 KiB chunks keep every channel busy
+    assert os_.ladder_chunks(grid, 32, 256, 3276800, os_.LADDER_CUT) == [32768, 65536]
+    assert os_.ladder_chunks(grid, 32, 256, 1000, os_.LADDER_CUT) == [32768]          # never empty
+    assert os_.ladder_chunks(grid, 1, 256, 4 << 20, os_.LADDER_CUT) == grid
+    alone = {(32, 256, c): t for c, t in zip(grid, [50.0, 48.0, 47.0, 47.0, 60.0, 90.0, 150.0, 300.0])}
+    alone.update({(16, 256, c): 1.0 for c in grid})                                   # other NC: ignored
+    assert os_.ladder_chunks(grid, 32, 256, 0, os_.LADDER_FIXED_CHUNK, alone) == [131072]   # first of the two smallest
+    with pytest.raises(ValueError):
+        os_.ladder_chunks(grid, 64, 256, 0, os_.LADDER_FIXED_CHUNK, alone)
