@@ -144,6 +144,12 @@ typedef struct {
     double Z_us;      /* common start to the later of the two ends                      */
     double* x_us;     /* host [ncfg]  per communication (nullable)                      */
     double* y_us;     /* host [ncomp] per computation   (nullable)                      */
+    /* Spread over the `iters` repetitions, as median absolute deviations (outputs; a caller that
+     * does not want x_mad_us sets it to null before the call):                             */
+    double* x_mad_us; /* host [ncfg]  per communication (nullable)                      */
+    double Ysum_us;   /* median over repetitions of sum_i y_i of that repetition        */
+    double Ysum_mad_us;
+    double Z_mad_us;
 } lagom_timing;
 
 /*   launches[nlaunch] : communication kernels in stream order; cfgs[ncfg] their
@@ -276,6 +282,54 @@ typedef struct {
 int lagom_cost_model(const lagom_model* m, const lagom_cfg* cfgs, int ncomm, lagom_pred* out);
 
 /* ---------------------------------------------------------------------------------
+ * lagom_model_fill, lagom_model_calibrate -- the contention wave model (Eq. 4-6) filled from a
+ * sweep of the contention profiler.  The paper measures x_j (Sec. 3.4, ProfileTime) and names
+ * theta and V(NC, C) in Eq. 6 without printing how they are obtained; this is the reading:
+ *   t_alone = median over the points (not held out) of comp_alone_us, divided by ncomp;
+ *   theta   = t_alone / g0 - lambda*TB*D/B, g0 = ceil(mu / (lambda*TB)), floored at 0
+ *             (Eq. 5-6 with no communication active, solved for theta);
+ *   per communication j and swept configuration: x_j = (bytes_j / sum bytes) * comm_corun_us,
+ *   V = min(v_corun, v_cap_frac * B).
+ * Host only.
+ */
+typedef struct {
+    int32_t lambda;             /* compute units                                            */
+    double  bw_peak;            /* B, bytes per microsecond                                 */
+    int64_t mu; int32_t tb; double d_bytes;   /* geometry shared by the group's computations
+                                                 (lagom_gemm_describe)                      */
+    int32_t ncomp;
+    int32_t ncomm;
+    const double* comm_bytes;   /* host [ncomm]: algorithmic bytes of each communication    */
+    double  v_cap_frac;         /* V is capped at this fraction of B (Eq. 6 needs V < B);
+                                   0 selects 0.99                                           */
+} lagom_fill_desc;
+
+/*   pts[npts]     : sweep points (lagom_contention_sweep); held_out[npts] nullable, non-zero =
+ *                   the point's standalone time is not used for theta.
+ *   entries       : out, host [ncomm * npts]; tables[ncomm] out, pointing into entries;
+ *   comps[ncomp]  : out; t_alone_us out, nullable.
+ * The caller assembles a lagom_model from tables and comps (and sets dependencies, corun_share).
+ * Errors: LAGOM_EINVAL (null, npts < 1, bad description, negative times, all points held out). */
+int lagom_model_fill(const lagom_sweep_point* pts, int npts, const uint8_t* held_out, const lagom_fill_desc* d,
+                     lagom_table_entry* entries, lagom_comm_table* tables, lagom_comp_model* comps, double* t_alone_us);
+
+/* Picks the co-run share sigma (lagom_model.corun_share) among sigmas[nsigma]: the model is filled
+ * as by lagom_model_fill, every candidate is scored by the mean of |Y_model - Y_measured| /
+ * Y_measured over the points that are not held out (all communications at the point's
+ * configuration), the first smallest mean wins; the same error over the held-out points is
+ * reported beside it.  x and V of every point stay in the tables: they are measured inputs of
+ * Eq. 1, not predictions.  comp_after_comm / comm_after_comp as in lagom_model (nullable). */
+typedef struct {
+    double  sigma, theta_us;
+    double  fit_mean, fit_max;      /* over the points not held out                         */
+    double  held_mean, held_max;    /* over the held-out points (0 when there are none)     */
+    int32_t n_fit, n_held;
+} lagom_calibration;
+int lagom_model_calibrate(const lagom_sweep_point* pts, int npts, const uint8_t* held_out, const lagom_fill_desc* d,
+                          const int32_t* comp_after_comm, const int32_t* comm_after_comp,
+                          const double* sigmas, int nsigma, lagom_calibration* out);
+
+/* ---------------------------------------------------------------------------------
  * lagom_tune -- priority-based parameter search (Sec. 3.3-3.4: metric H of Eq. 7,
  * the cost-effectiveness loop of Alg. 1, resource-efficient tuning of Alg. 2), or
  * exhaustive search over the same space.  Host only; all measuring is done by the
@@ -304,6 +358,16 @@ int lagom_cost_model(const lagom_model* m, const lagom_cfg* cfgs, int ncomm, lag
  * strictly, else down while it falls strictly; repeat until a sweep changes nothing.  This is
  * the point a tuner that looks at communication time only would pick.  trace->levels receives
  * the NC grid index of every communication; no steps are recorded.
+ * LAGOM_HIDE_COMM: the computation-bound objective (Sec. 3.1, Eq. 3: once communication is hidden
+ * the makespan is Y, which the communications' resources inflate): the least Y subject to
+ * X <= Y.  The loop of LAGOM_PRIORITY with two changes: the baseline ends the search when
+ * X <= Y; a trial with X' <= Y' is kept and ends the search for every communication (the lowest
+ * resources on the path that hide the communication; raising anything further only adds
+ * contention).  If no visited vector hides the communication the result is the priority
+ * search's last accepted vector.
+ * LAGOM_EXHAUSTIVE_HIDE: every level vector; among those with X <= Y the smallest Y wins (ties:
+ * smallest level sum, then lexicographic); if none has X <= Y, the smallest Z as in
+ * LAGOM_EXHAUSTIVE.
  */
 typedef int (*lagom_profile_fn)(void* user, const lagom_cfg* cfgs, int ncomm,
                                 double* x_us /* out [ncomm] */, double* Y_us /* out */);
@@ -332,7 +396,8 @@ typedef struct {
     int32_t* levels;             /* host [ncomm] out (nullable)                         */
 } lagom_trace;
 
-typedef enum { LAGOM_PRIORITY = 0, LAGOM_EXHAUSTIVE = 1, LAGOM_COMM_OPTIMAL = 2 } lagom_tune_mode;
+typedef enum { LAGOM_PRIORITY = 0, LAGOM_EXHAUSTIVE = 1, LAGOM_COMM_OPTIMAL = 2,
+               LAGOM_HIDE_COMM = 3, LAGOM_EXHAUSTIVE_HIDE = 4 } lagom_tune_mode;
 
 /*   spaces[ncomm], out_cfgs[ncomm] host arrays; trace nullable.
  * Errors: LAGOM_EINVAL (null, ncomm < 1 or > LAGOM_MAX_COMMS, empty or non-ascending
@@ -341,16 +406,48 @@ typedef enum { LAGOM_PRIORITY = 0, LAGOM_EXHAUSTIVE = 1, LAGOM_COMM_OPTIMAL = 2 
 int lagom_tune(const lagom_tune_space* spaces, int ncomm, lagom_profile_fn profile, void* user,
                int mode, lagom_cfg* out_cfgs, lagom_trace* trace);
 
+/* The chunk grid of a ladder.  Chunk g of a launch goes to channel g mod NC, so once
+ * chunk * nc_max exceeds the bytes a launch moves per source, some channels of every launch have
+ * no chunk; and on a ladder NC and C rise together (Alg. 2).
+ *   LAGOM_LADDER_FULL        : the grid as given;
+ *   LAGOM_LADDER_CUT         : the chunks with chunk * nc_max <= bytes_per_source (at least the smallest);
+ *   LAGOM_LADDER_FIXED_CHUNK : one chunk, the one with the smallest standalone communication time
+ *                              among the sweep points with nc == nc_max and nt == nt_ref (first
+ *                              smallest in grid order; the ladder then raises NC and NT only).
+ * chunk_grid strictly ascending; out_chunks has room for n_chunk values; pts may be null unless
+ * kind is LAGOM_LADDER_FIXED_CHUNK.  Host only.  Errors: LAGOM_EINVAL. */
+typedef enum { LAGOM_LADDER_FULL = 0, LAGOM_LADDER_CUT = 1, LAGOM_LADDER_FIXED_CHUNK = 2 } lagom_ladder_kind;
+int lagom_ladder_chunks(const int64_t* chunk_grid, int n_chunk, int32_t nc_max, int32_t nt_ref, int64_t bytes_per_source,
+                        int kind, const lagom_sweep_point* pts, int npts, int64_t* out_chunks, int32_t* out_n);
+
 /* Ready-made callbacks for lagom_tune. */
 /* user = const lagom_model*: x_j from the tables, Y from lagom_cost_model.             */
 int lagom_model_profile(void* user, const lagom_cfg* cfgs, int ncomm, double* x_us, double* Y_us);
 /* user = const lagom_overlap_ctx*: one measured co-run of the group (ProfileTime); x_j per
  * communication and Y = sum of the per-GEMM times y_i, as in Eq. 1.                      */
+/* What every call of lagom_overlap_profile measured, in call order (optional). */
+typedef struct {
+    int32_t capacity;            /* calls the arrays have room for                          */
+    int32_t ncomm;               /* row length of cfgs / x_us / x_mad_us                    */
+    int32_t n;                   /* out: calls made (recording stops at capacity)           */
+    lagom_cfg* cfgs;             /* host [capacity * ncomm]                                 */
+    double* x_us;  double* x_mad_us;    /* host [capacity * ncomm]                          */
+    double* Y_us;  double* Y_mad_us;    /* host [capacity]: Y as returned, spread of sum y_i */
+    double* Z_us;  double* Z_mad_us;    /* host [capacity]                                  */
+    int32_t* iters;              /* host [capacity]: repetitions the call measured          */
+} lagom_profile_log;
+
 typedef struct {
     const lagom_comm_desc* launches; int32_t nlaunch;
     const lagom_gemm_desc* comps;    int32_t ncomp;
     void* comm_stream; void* comp_stream;
     int32_t warmup, iters;
+    /* A short group is noisy at a fixed repetition count: when min_total_us > 0 and
+     * iters * Z < min_total_us after the first measurement, the group is measured again with
+     * ceil(min_total_us / Z) repetitions (at most max_iters) and that result is returned.   */
+    double  min_total_us;
+    int32_t max_iters;
+    lagom_profile_log* log;      /* nullable                                                */
 } lagom_overlap_ctx;
 int lagom_overlap_profile(void* user, const lagom_cfg* cfgs, int ncomm, double* x_us, double* Y_us);
 

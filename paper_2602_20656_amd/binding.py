@@ -23,12 +23,14 @@ LAGOM_OK, LAGOM_EINVAL, LAGOM_EALIGN, LAGOM_EHIP, LAGOM_ECALLBACK = 0, -1, -2, -
 LAGOM_F32, LAGOM_BF16 = 0, 1
 LAGOM_REDUCE_COPY, LAGOM_GATHER_COPY = 0, 1
 LAGOM_ALONE_COMM, LAGOM_ALONE_COMP, LAGOM_CORUN = 0, 1, 2
-LAGOM_PRIORITY, LAGOM_EXHAUSTIVE, LAGOM_COMM_OPTIMAL = 0, 1, 2
+LAGOM_PRIORITY, LAGOM_EXHAUSTIVE, LAGOM_COMM_OPTIMAL, LAGOM_HIDE_COMM, LAGOM_EXHAUSTIVE_HIDE = 0, 1, 2, 3, 4
+LAGOM_LADDER_FULL, LAGOM_LADDER_CUT, LAGOM_LADDER_FIXED_CHUNK = 0, 1, 2
 LAGOM_MAX_SRCS, LAGOM_MAX_DSTS, LAGOM_MAX_LAUNCHES, LAGOM_MAX_COMMS = 16, 4, 256, 64
 
 EXPORTS = ["lagom_strerror", "lagom_last_error", "lagom_comm_kernel", "lagom_gemm", "lagom_gemm_describe",
            "lagom_overlap_run", "lagom_contention_sweep", "lagom_comm_bytes", "lagom_cost_model", "lagom_tune",
-           "lagom_model_profile", "lagom_overlap_profile", "lagom_streams_overlap", "lagom_overlap_steps", "lagom_overlap_steps_graph"]
+           "lagom_model_profile", "lagom_overlap_profile", "lagom_streams_overlap", "lagom_overlap_steps", "lagom_overlap_steps_graph",
+           "lagom_model_fill", "lagom_model_calibrate", "lagom_ladder_chunks"]
 
 
 class LagomError(RuntimeError):
@@ -61,7 +63,8 @@ class lagom_gemm_desc(C.Structure):
 
 class lagom_timing(C.Structure):
     _fields_ = [("X_us", C.c_double), ("Y_us", C.c_double), ("Z_us", C.c_double),
-                ("x_us", C.POINTER(C.c_double)), ("y_us", C.POINTER(C.c_double))]
+                ("x_us", C.POINTER(C.c_double)), ("y_us", C.POINTER(C.c_double)),
+                ("x_mad_us", C.POINTER(C.c_double)), ("Ysum_us", C.c_double), ("Ysum_mad_us", C.c_double), ("Z_mad_us", C.c_double)]
 
 
 class lagom_sweep_point(C.Structure):
@@ -111,10 +114,28 @@ class lagom_trace(C.Structure):
                 ("levels", C.POINTER(C.c_int32))]
 
 
+class lagom_profile_log(C.Structure):
+    _fields_ = [("capacity", C.c_int32), ("ncomm", C.c_int32), ("n", C.c_int32), ("cfgs", C.POINTER(lagom_cfg)),
+                ("x_us", C.POINTER(C.c_double)), ("x_mad_us", C.POINTER(C.c_double)),
+                ("Y_us", C.POINTER(C.c_double)), ("Y_mad_us", C.POINTER(C.c_double)),
+                ("Z_us", C.POINTER(C.c_double)), ("Z_mad_us", C.POINTER(C.c_double)), ("iters", C.POINTER(C.c_int32))]
+
+
 class lagom_overlap_ctx(C.Structure):
     _fields_ = [("launches", C.POINTER(lagom_comm_desc)), ("nlaunch", C.c_int32),
                 ("comps", C.POINTER(lagom_gemm_desc)), ("ncomp", C.c_int32),
-                ("comm_stream", C.c_void_p), ("comp_stream", C.c_void_p), ("warmup", C.c_int32), ("iters", C.c_int32)]
+                ("comm_stream", C.c_void_p), ("comp_stream", C.c_void_p), ("warmup", C.c_int32), ("iters", C.c_int32),
+                ("min_total_us", C.c_double), ("max_iters", C.c_int32), ("log", C.POINTER(lagom_profile_log))]
+
+
+class lagom_fill_desc(C.Structure):
+    _fields_ = [("lambda_", C.c_int32), ("bw_peak", C.c_double), ("mu", C.c_int64), ("tb", C.c_int32), ("d_bytes", C.c_double),
+                ("ncomp", C.c_int32), ("ncomm", C.c_int32), ("comm_bytes", C.POINTER(C.c_double)), ("v_cap_frac", C.c_double)]
+
+
+class lagom_calibration(C.Structure):
+    _fields_ = [("sigma", C.c_double), ("theta_us", C.c_double), ("fit_mean", C.c_double), ("fit_max", C.c_double),
+                ("held_mean", C.c_double), ("held_max", C.c_double), ("n_fit", C.c_int32), ("n_held", C.c_int32)]
 
 
 PROFILE_FN = C.CFUNCTYPE(C.c_int, C.c_void_p, C.POINTER(lagom_cfg), C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double))
@@ -153,6 +174,14 @@ def lib() -> C.CDLL:
         L.lagom_cost_model.argtypes = [C.POINTER(lagom_model), C.POINTER(lagom_cfg), C.c_int, C.POINTER(lagom_pred)]
         L.lagom_tune.argtypes = [C.POINTER(lagom_tune_space), C.c_int, C.c_void_p, C.c_void_p, C.c_int,
                                  C.POINTER(lagom_cfg), C.POINTER(lagom_trace)]
+        L.lagom_model_fill.argtypes = [C.POINTER(lagom_sweep_point), C.c_int, C.POINTER(C.c_uint8), C.POINTER(lagom_fill_desc),
+                                       C.POINTER(lagom_table_entry), C.POINTER(lagom_comm_table), C.POINTER(lagom_comp_model),
+                                       C.POINTER(C.c_double)]
+        L.lagom_model_calibrate.argtypes = [C.POINTER(lagom_sweep_point), C.c_int, C.POINTER(C.c_uint8), C.POINTER(lagom_fill_desc),
+                                            C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_double), C.c_int,
+                                            C.POINTER(lagom_calibration)]
+        L.lagom_ladder_chunks.argtypes = [C.POINTER(C.c_int64), C.c_int, C.c_int32, C.c_int32, C.c_int64, C.c_int,
+                                          C.POINTER(lagom_sweep_point), C.c_int, C.POINTER(C.c_int64), C.POINTER(C.c_int32)]
         for name in EXPORTS:
             getattr(L, name)
         _lib = L
@@ -248,6 +277,10 @@ class Timing:
     Z_us: float
     x_us: List[float]
     y_us: List[float]
+    x_mad_us: List[float] = field(default_factory=list)   # spread over the repetitions (median absolute deviation)
+    Ysum_us: float = 0.0
+    Ysum_mad_us: float = 0.0
+    Z_mad_us: float = 0.0
 
 
 class _Group:
@@ -294,10 +327,12 @@ def lagom_overlap_run(launches: Sequence[CommLaunch], cfgs: Sequence[CfgLike], c
     ncfg = len(cfgs)
     x = (C.c_double * max(ncfg, 1))()
     y = (C.c_double * max(grp.ncomp, 1))()
-    t = lagom_timing(0.0, 0.0, 0.0, C.cast(x, C.POINTER(C.c_double)), C.cast(y, C.POINTER(C.c_double)))
+    xm = (C.c_double * max(ncfg, 1))()
+    t = lagom_timing(0.0, 0.0, 0.0, C.cast(x, C.POINTER(C.c_double)), C.cast(y, C.POINTER(C.c_double)),
+                     C.cast(xm, C.POINTER(C.c_double)), 0.0, 0.0, 0.0)
     _check(lib().lagom_overlap_run(grp.L, grp.nlaunch, _cfg_array(cfgs), ncfg, grp.G, grp.ncomp,
                                    _stream(comm_stream), _stream(comp_stream), warmup, iters, mode, C.byref(t)))
-    return Timing(t.X_us, t.Y_us, t.Z_us, list(x)[:ncfg], list(y)[:grp.ncomp])
+    return Timing(t.X_us, t.Y_us, t.Z_us, list(x)[:ncfg], list(y)[:grp.ncomp], list(xm)[:ncfg], t.Ysum_us, t.Ysum_mad_us, t.Z_mad_us)
 
 
 def lagom_overlap_steps(launches: Sequence[CommLaunch], cfgs: Sequence[CfgLike], comps: Sequence[GemmDesc],
@@ -340,6 +375,37 @@ def lagom_contention_sweep(launches: Sequence[CommLaunch], ncfg: int, comps: Seq
                                         _stream(comm_stream), _stream(comp_stream), warmup, iters, out))
     return [SweepPoint((o.cfg.nc, o.cfg.nt, o.cfg.chunk_bytes), o.comm_alone_us, o.comm_corun_us, o.comp_alone_us,
                        o.comp_corun_us, o.z_corun_us, o.v_alone, o.v_corun) for o in out]
+
+
+def _sweep_array(points: Sequence["SweepPoint"]):
+    arr = (lagom_sweep_point * max(len(points), 1))()
+    for i, p in enumerate(points):
+        arr[i] = lagom_sweep_point(_cfg(p.cfg), p.comm_alone_us, p.comm_corun_us, p.comp_alone_us, p.comp_corun_us,
+                                   p.z_corun_us, p.v_alone, p.v_corun)
+    return arr
+
+
+def _fill_desc(lam, bw_peak, mu, tb, d_bytes, ncomp, comm_bytes, v_cap_frac=0.0):
+    cb = (C.c_double * max(len(comm_bytes), 1))(*[float(b) for b in comm_bytes])
+    return lagom_fill_desc(int(lam), float(bw_peak), int(mu), int(tb), float(d_bytes), int(ncomp), len(comm_bytes),
+                           C.cast(cb, C.POINTER(C.c_double)), float(v_cap_frac)), cb
+
+
+def _mask(held_out, n):
+    if held_out is None:
+        return None
+    return (C.c_uint8 * max(n, 1))(*[1 if h else 0 for h in held_out])
+
+
+def lagom_ladder_chunks(chunk_grid: Sequence[int], nc_max: int, nt_ref: int, bytes_per_source: int, kind: int,
+                        points: Optional[Sequence["SweepPoint"]] = None) -> List[int]:
+    grid = (C.c_int64 * max(len(chunk_grid), 1))(*[int(c) for c in chunk_grid])
+    out = (C.c_int64 * max(len(chunk_grid), 1))()
+    n = C.c_int32(0)
+    pts = _sweep_array(points) if points else None
+    _check(lib().lagom_ladder_chunks(grid, len(chunk_grid), int(nc_max), int(nt_ref), int(bytes_per_source), int(kind),
+                                     pts, len(points) if points else 0, out, C.byref(n)))
+    return list(out)[:n.value]
 
 
 # ----------------------------------------------------------------- cost model (host)
@@ -407,6 +473,51 @@ def lagom_cost_model(model: Model, cfgs: Sequence[CfgLike]) -> Pred:
                 [[g[i * (n + 1) + s] for s in range(n + 1)] for i in range(mcomp)])
 
 
+def lagom_model_fill(points: Sequence[SweepPoint], lam: int, bw_peak: float, mu: int, tb: int, d_bytes: float, ncomp: int,
+                     comm_bytes: Sequence[float], held_out: Optional[Sequence[bool]] = None, v_cap_frac: float = 0.0,
+                     comp_after_comm=None, comm_after_comp=None, corun_share: float = 0.0) -> Tuple[Model, float]:
+    """The model of one overlap group filled from a sweep; returns (model, t_alone_us)."""
+    desc, keep = _fill_desc(lam, bw_peak, mu, tb, d_bytes, ncomp, comm_bytes, v_cap_frac)
+    n, ncomm = len(points), len(comm_bytes)
+    entries = (lagom_table_entry * max(n * ncomm, 1))()
+    tables = (lagom_comm_table * max(ncomm, 1))()
+    comps = (lagom_comp_model * max(ncomp, 1))()
+    t_alone = C.c_double(0.0)
+    _check(lib().lagom_model_fill(_sweep_array(points), n, _mask(held_out, n), C.byref(desc), entries, tables, comps, C.byref(t_alone)))
+    py_tables = []
+    for j in range(ncomm):
+        tj = tables[j]
+        py_tables.append({(tj.entries[e].cfg.nc, tj.entries[e].cfg.nt, tj.entries[e].cfg.chunk_bytes): (tj.entries[e].x_us, tj.entries[e].v)
+                          for e in range(tj.n)})
+    py_comps = [CompModel(c.mu, c.tb, c.d_bytes, c.theta_us) for c in comps[:ncomp]]
+    return Model(lam, bw_peak, py_comps, py_tables, comp_after_comm, comm_after_comp, corun_share), t_alone.value
+
+
+@dataclass
+class Calibration:
+    sigma: float
+    theta_us: float
+    fit_mean: float
+    fit_max: float
+    held_mean: float
+    held_max: float
+    n_fit: int
+    n_held: int
+
+
+def lagom_model_calibrate(points: Sequence[SweepPoint], lam: int, bw_peak: float, mu: int, tb: int, d_bytes: float, ncomp: int,
+                          comm_bytes: Sequence[float], sigmas: Sequence[float], held_out: Optional[Sequence[bool]] = None,
+                          v_cap_frac: float = 0.0, comp_after_comm=None, comm_after_comp=None) -> Calibration:
+    desc, keep = _fill_desc(lam, bw_peak, mu, tb, d_bytes, ncomp, comm_bytes, v_cap_frac)
+    n = len(points)
+    cac = (C.c_int32 * max(ncomp, 1))(*[int(v) for v in comp_after_comm]) if comp_after_comm is not None else None
+    cap = (C.c_int32 * max(len(comm_bytes), 1))(*[int(v) for v in comm_after_comp]) if comm_after_comp is not None else None
+    sg = (C.c_double * max(len(sigmas), 1))(*[float(v) for v in sigmas])
+    out = lagom_calibration()
+    _check(lib().lagom_model_calibrate(_sweep_array(points), n, _mask(held_out, n), C.byref(desc), cac, cap, sg, len(sigmas), C.byref(out)))
+    return Calibration(out.sigma, out.theta_us, out.fit_mean, out.fit_max, out.held_mean, out.held_max, out.n_fit, out.n_held)
+
+
 # ------------------------------------------------------------------------ tuner (host)
 @dataclass
 class Space:
@@ -452,6 +563,10 @@ class OverlapProfile:
     comp_stream: object
     warmup: int = 1
     iters: int = 5
+    min_total_us: float = 0.0      # measure again, longer, when iters * Z stays below this
+    max_iters: int = 0
+    log_capacity: int = 0          # > 0: record what every call measured; read it back from `.log` after the search
+    log: Optional[list] = None     # out: per call {"cfgs", "x", "x_mad", "Y", "Y_mad", "Z", "Z_mad", "iters"}
 
 
 ProfileLike = Union[Callable[[List[Tuple[int, int, int]]], Tuple[Sequence[float], float]], Model, OverlapProfile]
@@ -487,10 +602,23 @@ def lagom_tune(spaces: Sequence[Space], profile: ProfileLike, mode: int = LAGOM_
         fn, user = C.cast(L.lagom_model_profile, C.c_void_p), C.cast(C.pointer(cm.c), C.c_void_p)
     elif isinstance(profile, OverlapProfile):
         grp = _Group(profile.launches, profile.comps)
+        plog, plog_arrays = None, None
+        if profile.log_capacity > 0:
+            cap_l = int(profile.log_capacity)
+            plog_arrays = {"cfgs": (lagom_cfg * (cap_l * n))(), "x": (C.c_double * (cap_l * n))(), "x_mad": (C.c_double * (cap_l * n))(),
+                           "Y": (C.c_double * cap_l)(), "Y_mad": (C.c_double * cap_l)(), "Z": (C.c_double * cap_l)(),
+                           "Z_mad": (C.c_double * cap_l)(), "iters": (C.c_int32 * cap_l)()}
+            a = plog_arrays
+            plog = lagom_profile_log(cap_l, n, 0, C.cast(a["cfgs"], C.POINTER(lagom_cfg)), C.cast(a["x"], C.POINTER(C.c_double)),
+                                     C.cast(a["x_mad"], C.POINTER(C.c_double)), C.cast(a["Y"], C.POINTER(C.c_double)),
+                                     C.cast(a["Y_mad"], C.POINTER(C.c_double)), C.cast(a["Z"], C.POINTER(C.c_double)),
+                                     C.cast(a["Z_mad"], C.POINTER(C.c_double)), C.cast(a["iters"], C.POINTER(C.c_int32)))
         ctx = lagom_overlap_ctx(C.cast(grp.L, C.POINTER(lagom_comm_desc)), grp.nlaunch,
                                 C.cast(grp.G, C.POINTER(lagom_gemm_desc)), grp.ncomp,
-                                _stream(profile.comm_stream), _stream(profile.comp_stream), profile.warmup, profile.iters)
-        keep += [grp, ctx]
+                                _stream(profile.comm_stream), _stream(profile.comp_stream), profile.warmup, profile.iters,
+                                float(profile.min_total_us), int(profile.max_iters),
+                                C.pointer(plog) if plog is not None else C.POINTER(lagom_profile_log)())
+        keep += [grp, ctx, plog, plog_arrays]
         fn, user = C.cast(L.lagom_overlap_profile, C.c_void_p), C.cast(C.pointer(ctx), C.c_void_p)
     else:
         def _cb(_user, cfgs, ncomm, x_out, y_out):
@@ -506,6 +634,12 @@ def lagom_tune(spaces: Sequence[Space], profile: ProfileLike, mode: int = LAGOM_
         keep.append(cb)
         fn, user = C.cast(cb, C.c_void_p), None
     rc = L.lagom_tune(sp, n, fn, user, mode, out, C.byref(tr))
+    if isinstance(profile, OverlapProfile) and profile.log_capacity > 0:
+        a = plog_arrays
+        profile.log = [{"cfgs": [(a["cfgs"][k * n + j].nc, a["cfgs"][k * n + j].nt, a["cfgs"][k * n + j].chunk_bytes) for j in range(n)],
+                        "x": [a["x"][k * n + j] for j in range(n)], "x_mad": [a["x_mad"][k * n + j] for j in range(n)],
+                        "Y": a["Y"][k], "Y_mad": a["Y_mad"][k], "Z": a["Z"][k], "Z_mad": a["Z_mad"][k], "iters": a["iters"][k]}
+                       for k in range(min(plog.n, plog.capacity))]
     if rc != LAGOM_OK and not (rc == LAGOM_ECALLBACK and not raise_on_callback_error):
         _check(rc)
     trace = [TraceStep(s.comm, s.level_from, s.level_to, bool(s.accepted), bool(s.done), s.xj_prev, s.xj_new,

@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblagom.so")
-SOURCES = ["errors.cpp", "cost_model.cpp", "tune.cpp", "comm_kernel.hip", "gemm.hip", "overlap.hip"]
+SOURCES = ["errors.cpp", "cost_model.cpp", "tune.cpp", "model_fill.cpp", "comm_kernel.hip", "gemm.hip", "overlap.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-I", os.path.join(ROOT, "include"), "-I", CSRC,

@@ -45,6 +45,7 @@
 // blocks transposed in registers first); single buffered.  Slower; used for K < 64 and beyond
 // the fast kernel's size limits.
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <type_traits>
 #include "common.h"
 
@@ -912,9 +913,17 @@ __global__ void __launch_bounds__(THREADS) gemm_bf16_kn256x128_tail_kernel(const
 
 template <void (*KERNEL)(const GemmArgs)>
 int launch_fast(const GemmArgs& a, dim3 grid, hipStream_t st) {
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(KERNEL),
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, FAST_LDS_BYTES);
-    if (attr != hipSuccess) return lagom::fail(LAGOM_EHIP, "gemm: cannot raise the LDS limit: %s", hipGetErrorString(attr));
+    // set once per kernel (and per device: a process may drive several); a failure is not remembered
+    static std::atomic<uint64_t> done_on_device{0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev > 63) dev = 63;
+    const uint64_t bit = uint64_t{1} << dev;
+    if (dev == 63 || !(done_on_device.load(std::memory_order_acquire) & bit)) {
+        const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(KERNEL),
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, FAST_LDS_BYTES);
+        if (attr != hipSuccess) return lagom::fail(LAGOM_EHIP, "gemm: cannot raise the LDS limit: %s", hipGetErrorString(attr));
+        done_on_device.fetch_or(bit, std::memory_order_release);
+    }
     hipLaunchKernelGGL(KERNEL, grid, dim3(THREADS), FAST_LDS_BYTES, st, a);
     return LAGOM_OK;
 }

@@ -9,6 +9,7 @@
 // run back to back, unaffected by host launch latency, and start at a common instant.
 #include <hip/hip_runtime.h>
 #include <algorithm>
+#include <cmath>
 #include <vector>
 #include "common.h"
 
@@ -50,6 +51,23 @@ double median(std::vector<double>& v) {
     std::sort(v.begin(), v.end());
     const size_t n = v.size();
     return n & 1 ? v[n / 2] : 0.5 * (v[n / 2 - 1] + v[n / 2]);
+}
+
+// median absolute deviation around `med`
+double mad(const std::vector<double>& v, double med) {
+    std::vector<double> d(v.size());
+    for (size_t i = 0; i < v.size(); ++i) d[i] = std::fabs(v[i] - med);
+    return median(d);
+}
+
+// After a failure between the first enqueue of a repetition and its end nothing may stay queued on the
+// caller's streams (events the streams still wait on are about to be destroyed): drain both, keep the code.
+int drained(int rc, hipStream_t sa, hipStream_t sb) {
+    if (rc != LAGOM_OK) {
+        (void)hipStreamSynchronize(sa);
+        (void)hipStreamSynchronize(sb);
+    }
+    return rc;
 }
 
 int validate(const lagom_comm_desc* L, int nlaunch, const lagom_cfg* cfgs, int ncfg,
@@ -235,7 +253,9 @@ extern "C" int lagom_overlap_run(const lagom_comm_desc* launches, int nlaunch, c
     std::vector<double> Xs, Ys, Zs;
     hipStream_t gate_stream = run_comm ? sa : sb;
 
-    for (int it = 0; it < warmup + iters; ++it) {
+    std::vector<double> Ysums;
+    // one repetition: gate, both streams enqueued, both drained
+    auto repetition = [&]() -> int {
         hipLaunchKernelGGL(gate_delay_kernel, dim3(1), dim3(64), 0, gate_stream, ticks, max_iter);
         HIP_TRY(hipGetLastError());
         HIP_TRY(hipEventRecord(gate, gate_stream));
@@ -244,10 +264,14 @@ extern "C" int lagom_overlap_run(const lagom_comm_desc* launches, int nlaunch, c
                                    ga_start, ga_end, gb_start, gb_end)) return rc;
         if (run_comm) HIP_TRY(hipStreamSynchronize(sa));
         if (run_comp) HIP_TRY(hipStreamSynchronize(sb));
+        return LAGOM_OK;
+    };
+    for (int it = 0; it < warmup + iters; ++it) {
+        if (int rc = drained(repetition(), sa, sb)) return rc;
         if (it < warmup) continue;
 
         float ms = 0.f;
-        double X = 0.0, Y = 0.0, endA = 0.0, endB = 0.0;
+        double X = 0.0, Y = 0.0, endA = 0.0, endB = 0.0, ysum = 0.0;
         if (run_comm) {
             for (int g = 0; g < ngroups; ++g) {
                 HIP_TRY(hipEventElapsedTime(&ms, ga_start[g], ga_end[g]));
@@ -260,16 +284,24 @@ extern "C" int lagom_overlap_run(const lagom_comm_desc* launches, int nlaunch, c
             for (int i = 0; i < ncomp; ++i) {
                 HIP_TRY(hipEventElapsedTime(&ms, gb_start[i], gb_end[i]));
                 ys[i].push_back((double)ms * 1000.0);
+                ysum = ysum + (double)ms * 1000.0;
             }
             HIP_TRY(hipEventElapsedTime(&ms, gb_start[0], gb_end[ncomp - 1])); Y = (double)ms * 1000.0;
             HIP_TRY(hipEventElapsedTime(&ms, gate, gb_end[ncomp - 1])); endB = (double)ms * 1000.0;
         }
-        Xs.push_back(X); Ys.push_back(Y); Zs.push_back(endA > endB ? endA : endB);
+        Xs.push_back(X); Ys.push_back(Y); Zs.push_back(endA > endB ? endA : endB); Ysums.push_back(ysum);
     }
     out->X_us = median(Xs);
     out->Y_us = median(Ys);
     out->Z_us = median(Zs);
-    if (out->x_us) for (int j = 0; j < ncfg; ++j) out->x_us[j] = median(xs[j]);
+    out->Z_mad_us = mad(Zs, out->Z_us);
+    out->Ysum_us = median(Ysums);
+    out->Ysum_mad_us = mad(Ysums, out->Ysum_us);
+    for (int j = 0; j < ncfg; ++j) {
+        const double m = median(xs[j]);
+        if (out->x_us) out->x_us[j] = m;
+        if (out->x_mad_us) out->x_mad_us[j] = mad(xs[j], m);
+    }
     if (out->y_us) for (int i = 0; i < ncomp; ++i) out->y_us[i] = median(ys[i]);
     return LAGOM_OK;
 }
@@ -301,13 +333,17 @@ extern "C" int lagom_overlap_steps(const lagom_comm_desc* launches, int nlaunch,
     HIP_TRY(hipStreamWaitEvent(sb, t_start, 0));
     for (int it = 0; it < steps; ++it) {
         // the events are re-recorded every repetition: a wait refers to the record that preceded it
-        if (int rc = enqueue_group(plan, launches, nlaunch, cfgs, comps, ncomp, true, sa, sb, nullptr, ga_end, nullptr, gb_end)) return rc;
-        HIP_TRY(hipEventRecord(end_a, sa));
-        HIP_TRY(hipEventRecord(end_b, sb));
-        HIP_TRY(hipStreamWaitEvent(sa, end_b, 0));   // the next repetition starts when this one has ended on both streams
-        HIP_TRY(hipStreamWaitEvent(sb, end_a, 0));
+        auto repetition = [&]() -> int {
+            if (int rc = enqueue_group(plan, launches, nlaunch, cfgs, comps, ncomp, true, sa, sb, nullptr, ga_end, nullptr, gb_end)) return rc;
+            HIP_TRY(hipEventRecord(end_a, sa));
+            HIP_TRY(hipEventRecord(end_b, sb));
+            HIP_TRY(hipStreamWaitEvent(sa, end_b, 0));   // the next repetition starts when this one has ended on both streams
+            HIP_TRY(hipStreamWaitEvent(sb, end_a, 0));
+            return LAGOM_OK;
+        };
+        if (int rc = drained(repetition(), sa, sb)) return rc;
     }
-    HIP_TRY(hipEventRecord(t_end, sa));
+    if (int rc = drained([&]() -> int { HIP_TRY(hipEventRecord(t_end, sa)); return LAGOM_OK; }(), sa, sb)) return rc;
     HIP_TRY(hipStreamSynchronize(sa));
     HIP_TRY(hipStreamSynchronize(sb));
     float ms = 0.f;
@@ -338,7 +374,7 @@ extern "C" int lagom_overlap_steps_graph(const lagom_comm_desc* launches, int nl
     // and a dependency cycle is reported here, where the streams may still be synchronised.
     HIP_TRY(hipEventRecord(fork, sa));
     HIP_TRY(hipStreamWaitEvent(sb, fork, 0));
-    if (int rc = enqueue_group(plan, launches, nlaunch, cfgs, comps, ncomp, true, sa, sb, nullptr, ga_end, nullptr, gb_end)) return rc;
+    if (int rc = drained(enqueue_group(plan, launches, nlaunch, cfgs, comps, ncomp, true, sa, sb, nullptr, ga_end, nullptr, gb_end), sa, sb)) return rc;
     HIP_TRY(hipStreamSynchronize(sa));
     HIP_TRY(hipStreamSynchronize(sb));
 
@@ -426,15 +462,43 @@ extern "C" int lagom_overlap_profile(void* user, const lagom_cfg* cfgs, int ncom
     if (!user || !cfgs || !x_us || !Y_us) return lagom::fail(LAGOM_EINVAL, "null argument");
     const lagom_overlap_ctx* c = static_cast<const lagom_overlap_ctx*>(user);
     if (c->ncomp < 0 || c->ncomp > LAGOM_MAX_LAUNCHES) return lagom::fail(LAGOM_EINVAL, "ncomp=%d out of range", c->ncomp);
-    std::vector<double> yi((size_t)c->ncomp);
+    if (ncomm < 1 || ncomm > LAGOM_MAX_COMMS) return lagom::fail(LAGOM_EINVAL, "ncomm=%d out of range", ncomm);
+    std::vector<double> yi((size_t)c->ncomp), xmad((size_t)ncomm);
     lagom_timing t{};
     t.x_us = x_us;
     t.y_us = yi.data();
+    t.x_mad_us = xmad.data();
+    int iters = c->iters;
     int rc = lagom_overlap_run(c->launches, c->nlaunch, cfgs, ncomm, c->comps, c->ncomp, c->comm_stream, c->comp_stream,
-                               c->warmup, c->iters, LAGOM_CORUN, &t);
+                               c->warmup, iters, LAGOM_CORUN, &t);
     if (rc) return rc;
+    if (c->min_total_us > 0.0 && t.Z_us > 0.0 && (double)iters * t.Z_us < c->min_total_us) {
+        // a short group: the repetitions asked for do not average enough out; measure again, longer
+        const double want = std::ceil(c->min_total_us / t.Z_us);
+        const int cap = c->max_iters > iters ? c->max_iters : iters;
+        iters = want < (double)cap ? (int)want : cap;
+        rc = lagom_overlap_run(c->launches, c->nlaunch, cfgs, ncomm, c->comps, c->ncomp, c->comm_stream, c->comp_stream,
+                               0, iters, LAGOM_CORUN, &t);
+        if (rc) return rc;
+    }
     double Y = 0.0;   // Eq. 1: Y is the sum of the y_i (a GEMM's wait for a communication is not computation time)
     for (double y : yi) Y = Y + y;
     *Y_us = Y;
+    if (lagom_profile_log* g = c->log) {
+        if (g->n < g->capacity && g->ncomm == ncomm) {
+            const int64_t row = (int64_t)g->n * ncomm;
+            for (int j = 0; j < ncomm; ++j) {
+                if (g->cfgs) g->cfgs[row + j] = cfgs[j];
+                if (g->x_us) g->x_us[row + j] = x_us[j];
+                if (g->x_mad_us) g->x_mad_us[row + j] = xmad[j];
+            }
+            if (g->Y_us) g->Y_us[g->n] = Y;
+            if (g->Y_mad_us) g->Y_mad_us[g->n] = t.Ysum_mad_us;
+            if (g->Z_us) g->Z_us[g->n] = t.Z_us;
+            if (g->Z_mad_us) g->Z_mad_us[g->n] = t.Z_mad_us;
+            if (g->iters) g->iters[g->n] = iters;
+        }
+        g->n += 1;
+    }
     return LAGOM_OK;
 }

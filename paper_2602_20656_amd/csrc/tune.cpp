@@ -85,7 +85,9 @@ int push(lagom_trace* tr, const lagom_trace_step& s) {
     return LAGOM_OK;
 }
 
-int priority(const std::vector<Ladder>& L, lagom_profile_fn profile, void* user, lagom_cfg* out_cfgs, lagom_trace* tr) {
+// hide = false: Alg. 1 driving Alg. 2.  hide = true: the same walk for the computation-bound objective (least Y
+// subject to X <= Y): it ends, for every communication, at the first vector with X <= Y, which is kept.
+int priority(const std::vector<Ladder>& L, lagom_profile_fn profile, void* user, lagom_cfg* out_cfgs, lagom_trace* tr, bool hide) {
     const int N = (int)L.size();
     const double nan = std::numeric_limits<double>::quiet_NaN();
     const double inf = std::numeric_limits<double>::infinity();
@@ -102,7 +104,7 @@ int priority(const std::vector<Ladder>& L, lagom_profile_fn profile, void* user,
     int rc = measure(profile, user, L, lev, scratch, &cur);
     if (rc) { emit(L, lev, nullptr, calls, out_cfgs, tr); return lagom::fail(rc, "baseline profile failed"); }
     calls = 1;
-    if (cur.X < cur.Y) {                       // optimality condition 1: minimum resources already hide X
+    if (hide ? cur.X <= cur.Y : cur.X < cur.Y) {   // optimality condition 1: minimum resources already hide X
         for (int j = 0; j < N; ++j) done[j] = 1;
         ndone = N;
     }
@@ -122,7 +124,11 @@ int priority(const std::vector<Ladder>& L, lagom_profile_fn profile, void* user,
         bool accepted;
         if (trial.x[j] - cur.x[j] > 0.0) {     // Alg. 2: the communication itself got slower
             done[j] = 1; accepted = false;
-        } else if (trial.X < trial.Y) {        // Alg. 2: all communication is hidden
+        } else if (hide && trial.X <= trial.Y) {   // hidden: keep it; nothing else needs raising
+            accepted = true;
+            for (int i = 0; i < N; ++i) done[i] = 1;
+            ndone = N - 1;                          // the step's own bookkeeping below adds the last one
+        } else if (!hide && trial.X < trial.Y) {   // Alg. 2: all communication is hidden
             done[j] = 1; accepted = trial.Z < cur.Z;
         } else {
             accepted = true;
@@ -141,16 +147,17 @@ int priority(const std::vector<Ladder>& L, lagom_profile_fn profile, void* user,
     return LAGOM_OK;
 }
 
-int exhaustive(const std::vector<Ladder>& L, lagom_profile_fn profile, void* user, lagom_cfg* out_cfgs, lagom_trace* tr) {
+// hide = true: among the vectors with X <= Y the smallest Y wins; the smallest Z only if there is none.
+int exhaustive(const std::vector<Ladder>& L, lagom_profile_fn profile, void* user, lagom_cfg* out_cfgs, lagom_trace* tr, bool hide) {
     const int N = (int)L.size();
     double total = 1.0;
     for (const Ladder& l : L) total *= l.K;
     if (total > 1048576.0) return lagom::fail(LAGOM_EINVAL, "exhaustive search over %.0f vectors refused", total);
-    std::vector<int> lev(N, 0), best_lev(N, 0);
+    std::vector<int> lev(N, 0), best_lev(N, 0), hid_lev(N, 0);
     std::vector<lagom_cfg> scratch(N);
-    Measurement m, best;
-    long best_sum = 0;
-    bool have = false;
+    Measurement m, best, hid;
+    long best_sum = 0, hid_sum = 0;
+    bool have = false, have_hid = false;
     int calls = 0;
     for (;;) {                                  // lexicographic order, last index fastest
         int rc = measure(profile, user, L, lev, scratch, &m);
@@ -160,11 +167,13 @@ int exhaustive(const std::vector<Ladder>& L, lagom_profile_fn profile, void* use
         for (int v : lev) sum += v;
         // visiting order is lexicographic, so "strictly better" keeps the lexicographically smallest on full ties
         if (!have || m.Z < best.Z || (m.Z == best.Z && sum < best_sum)) { best = m; best_lev = lev; best_sum = sum; have = true; }
+        if (hide && m.X <= m.Y && (!have_hid || m.Y < hid.Y || (m.Y == hid.Y && sum < hid_sum))) { hid = m; hid_lev = lev; hid_sum = sum; have_hid = true; }
         int d = N - 1;
         while (d >= 0 && ++lev[d] == L[d].K) lev[d--] = 0;
         if (d < 0) break;
     }
-    emit(L, best_lev, &best, calls, out_cfgs, tr);
+    if (have_hid) emit(L, hid_lev, &hid, calls, out_cfgs, tr);
+    else emit(L, best_lev, &best, calls, out_cfgs, tr);
     return LAGOM_OK;
 }
 
@@ -242,7 +251,7 @@ extern "C" int lagom_tune(const lagom_tune_space* spaces, int ncomm, lagom_profi
                           int mode, lagom_cfg* out_cfgs, lagom_trace* trace) {
     if (!spaces || !profile || !out_cfgs) return lagom::fail(LAGOM_EINVAL, "null argument");
     if (ncomm < 1 || ncomm > LAGOM_MAX_COMMS) return lagom::fail(LAGOM_EINVAL, "ncomm=%d outside 1..%d", ncomm, LAGOM_MAX_COMMS);
-    if (mode != LAGOM_PRIORITY && mode != LAGOM_EXHAUSTIVE && mode != LAGOM_COMM_OPTIMAL) return lagom::fail(LAGOM_EINVAL, "unknown mode %d", mode);
+    if (mode < LAGOM_PRIORITY || mode > LAGOM_EXHAUSTIVE_HIDE) return lagom::fail(LAGOM_EINVAL, "unknown mode %d", mode);
     std::vector<Ladder> L(ncomm);
     for (int j = 0; j < ncomm; ++j) {
         const lagom_tune_space& s = spaces[j];
@@ -255,7 +264,39 @@ extern "C" int lagom_tune(const lagom_tune_space* spaces, int ncomm, lagom_profi
         trace->n = 0; trace->calls = 0;
         if (trace->steps && trace->capacity < 0) return lagom::fail(LAGOM_EINVAL, "negative trace capacity");
     }
-    if (mode == LAGOM_PRIORITY) return priority(L, profile, user, out_cfgs, trace);
-    if (mode == LAGOM_EXHAUSTIVE) return exhaustive(L, profile, user, out_cfgs, trace);
+    if (mode == LAGOM_PRIORITY || mode == LAGOM_HIDE_COMM) return priority(L, profile, user, out_cfgs, trace, mode == LAGOM_HIDE_COMM);
+    if (mode == LAGOM_EXHAUSTIVE || mode == LAGOM_EXHAUSTIVE_HIDE) return exhaustive(L, profile, user, out_cfgs, trace, mode == LAGOM_EXHAUSTIVE_HIDE);
     return comm_optimal(L, profile, user, out_cfgs, trace);
+}
+
+extern "C" int lagom_ladder_chunks(const int64_t* chunk_grid, int n_chunk, int32_t nc_max, int32_t nt_ref, int64_t bytes_per_source,
+                                   int kind, const lagom_sweep_point* pts, int npts, int64_t* out_chunks, int32_t* out_n) {
+    if (!out_chunks || !out_n) return lagom::fail(LAGOM_EINVAL, "null output");
+    if (!ascending(chunk_grid, n_chunk)) return lagom::fail(LAGOM_EINVAL, "the chunk grid must be non-empty and strictly ascending");
+    if (nc_max < 1 || bytes_per_source < 0) return lagom::fail(LAGOM_EINVAL, "nc_max >= 1 and bytes_per_source >= 0 required");
+    int n = 0;
+    if (kind == LAGOM_LADDER_FULL) {
+        for (int i = 0; i < n_chunk; ++i) out_chunks[n++] = chunk_grid[i];
+    } else if (kind == LAGOM_LADDER_CUT) {
+        for (int i = 0; i < n_chunk; ++i)
+            if (chunk_grid[i] * (int64_t)nc_max <= bytes_per_source) out_chunks[n++] = chunk_grid[i];
+        if (n == 0) out_chunks[n++] = chunk_grid[0];
+    } else if (kind == LAGOM_LADDER_FIXED_CHUNK) {
+        if (!pts || npts < 1) return lagom::fail(LAGOM_EINVAL, "a fixed-chunk ladder needs sweep points");
+        bool have = false;
+        double best = 0.0;
+        for (int i = 0; i < n_chunk; ++i)
+            for (int p = 0; p < npts; ++p) {
+                const lagom_sweep_point& s = pts[p];
+                if (s.cfg.nc != nc_max || s.cfg.nt != nt_ref || s.cfg.chunk_bytes != chunk_grid[i]) continue;
+                if (!have || s.comm_alone_us < best) { best = s.comm_alone_us; out_chunks[0] = chunk_grid[i]; have = true; }
+                break;
+            }
+        if (!have) return lagom::fail(LAGOM_EINVAL, "no sweep point at nc=%d, nt=%d", nc_max, nt_ref);
+        n = 1;
+    } else {
+        return lagom::fail(LAGOM_EINVAL, "unknown ladder kind %d", kind);
+    }
+    *out_n = n;
+    return LAGOM_OK;
 }

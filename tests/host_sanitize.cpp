@@ -64,8 +64,8 @@ int main() {
         std::vector<lagom_cfg> out(N);
         std::vector<lagom_trace_step> steps(8 * N + 4);
         std::vector<int32_t> lev(N);
-        for (int mode : {LAGOM_PRIORITY, LAGOM_COMM_OPTIMAL, LAGOM_EXHAUSTIVE}) {
-            if (mode == LAGOM_EXHAUSTIVE && N > 3) continue;
+        for (int mode : {LAGOM_PRIORITY, LAGOM_COMM_OPTIMAL, LAGOM_EXHAUSTIVE, LAGOM_HIDE_COMM, LAGOM_EXHAUSTIVE_HIDE}) {
+            if ((mode == LAGOM_EXHAUSTIVE || mode == LAGOM_EXHAUSTIVE_HIDE) && N > 3) continue;
             int calls = 0;
             lagom_trace tr{steps.data(), (int32_t)steps.size(), 0, 0, 0, 0, 0, lev.data()};
             if (lagom_tune(sp.data(), N, profile_cb, &calls, mode, out.data(), &tr) != LAGOM_OK) { std::printf("tune mode %d failed: %s\n", mode, lagom_last_error()); ++bad; }
@@ -81,6 +81,41 @@ int main() {
         if (lagom_tune(sp.data(), N, failing_cb, nullptr, LAGOM_PRIORITY, out.data(), nullptr) != LAGOM_ECALLBACK) ++bad;
         if (lagom_tune(sp.data(), 0, profile_cb, &calls, LAGOM_PRIORITY, out.data(), nullptr) != LAGOM_EINVAL) ++bad;
         if (lagom_tune(sp.data(), N, profile_cb, &calls, 9, out.data(), nullptr) != LAGOM_EINVAL) ++bad;
+
+        // model fill, calibration and the ladder helper on a synthetic sweep over the same grids
+        std::vector<lagom_sweep_point> pts;
+        for (int32_t a : nc) for (int32_t b : nt) for (int64_t c : ch)
+            pts.push_back(lagom_sweep_point{lagom_cfg{a, b, c}, 5.0 + rng() % 300, 5.0 + rng() % 300, 100.0 + rng() % 500, 100.0 + rng() % 700,
+                                            100.0 + rng() % 900, (double)(rng() % 9000000), (double)(rng() % 9000000)});
+        const int P = (int)pts.size();
+        std::vector<uint8_t> held(P);
+        for (int i = 0; i < P; ++i) held[i] = i & 1;
+        std::vector<double> nbytes(N);
+        for (auto& b : nbytes) b = 1.0 + rng() % 100000000;
+        lagom_fill_desc fd{256, 8.0e6, (int64_t)(1 + rng() % 3000), (int32_t)(1 + rng() % 2), (double)(rng() % 5000000), M, N, nbytes.data(), 0.0};
+        std::vector<lagom_table_entry> fe((size_t)N * P);
+        std::vector<lagom_comm_table> ft(N);
+        std::vector<lagom_comp_model> fc(M);
+        double t_alone = 0.0;
+        if (lagom_model_fill(pts.data(), P, held.data(), &fd, fe.data(), ft.data(), fc.data(), &t_alone) != LAGOM_OK) { std::printf("fill failed: %s\n", lagom_last_error()); ++bad; }
+        if (lagom_model_fill(pts.data(), P, nullptr, &fd, fe.data(), ft.data(), fc.data(), nullptr) != LAGOM_OK) ++bad;
+        lagom_model fm{256, 8.0e6, fc.data(), M, ft.data(), N, nullptr, nullptr, 0.25};
+        if (lagom_tune(sp.data(), N, lagom_model_profile, &fm, LAGOM_HIDE_COMM, out.data(), nullptr) != LAGOM_OK) ++bad;
+        const double sig[3] = {0.0, 0.5, 1.0};
+        lagom_calibration cal{};
+        if (lagom_model_calibrate(pts.data(), P, held.data(), &fd, dep ? cac.data() : nullptr, dep ? cap.data() : nullptr, sig, 3, &cal) != LAGOM_OK) { std::printf("calibrate failed: %s\n", lagom_last_error()); ++bad; }
+        if (cal.n_fit + cal.n_held != P) ++bad;
+        if (lagom_model_calibrate(pts.data(), P, held.data(), &fd, nullptr, nullptr, sig, 0, &cal) != LAGOM_EINVAL) ++bad;
+        std::vector<uint8_t> all_held(P, 1);
+        if (lagom_model_fill(pts.data(), P, all_held.data(), &fd, fe.data(), ft.data(), fc.data(), nullptr) != LAGOM_EINVAL) ++bad;
+        if (lagom_model_fill(pts.data(), 0, nullptr, &fd, fe.data(), ft.data(), fc.data(), nullptr) != LAGOM_EINVAL) ++bad;
+        std::vector<int64_t> lc(ch.size());
+        int32_t ln = 0;
+        for (int kind : {LAGOM_LADDER_FULL, LAGOM_LADDER_CUT, LAGOM_LADDER_FIXED_CHUNK}) {
+            if (lagom_ladder_chunks(ch.data(), (int)ch.size(), nc.back(), nt[0], (int64_t)(rng() % 4000000), kind, pts.data(), P, lc.data(), &ln) != LAGOM_OK) ++bad;
+            if (ln < 1 || ln > (int32_t)ch.size()) ++bad;
+        }
+        if (lagom_ladder_chunks(ch.data(), (int)ch.size(), 77, nt[0], 100, LAGOM_LADDER_FIXED_CHUNK, pts.data(), P, lc.data(), &ln) != LAGOM_EINVAL) ++bad;
     }
     std::printf("host sanitize driver: %d problems\n", bad);
     return bad ? 1 : 0;

@@ -9,7 +9,7 @@ import subprocess
 import numpy as np
 import pytest
 
-from oracle import cost_model as ocm, search as osr
+from oracle import cost_model as ocm, model_fill as omf, search as osr
 from paper_2602_20656_amd import binding as lg
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -318,3 +318,136 @@ def test_dependent_cost_model_equals_oracle_bit_for_bit(golden_dir):
     with pytest.raises(lg.LagomError) as e:
         lg.lagom_cost_model(cyc, [(2, 64, 64)])
     assert e.value.code == lg.LAGOM_EINVAL
+
+
+# ------------------------------------------------- computation-bound objective, ladder helper
+def test_hide_modes_equal_oracle_result_and_trace(golden_dir):
+    rng = np.random.default_rng(41)
+    hidden = 0
+    for _ in range(300):
+        N = int(rng.integers(1, 9))
+        so, sl, profile = _random_chain(rng, N)
+        ro = osr.hide_search(so, profile)
+        rl = lg.lagom_tune(sl, profile, lg.LAGOM_HIDE_COMM)
+        assert rl.cfgs == ro.cfgs and rl.levels == ro.levels and rl.calls == ro.calls
+        assert (rl.X, rl.Y, rl.Z) == (ro.X, ro.Y, ro.Z)
+        _same_trace(rl.trace, ro.trace)
+        hidden += ro.X <= ro.Y
+    assert 30 < hidden < 300
+    for _ in range(60):
+        N = int(rng.integers(1, 4))
+        so, sl, profile = _random_chain(rng, N)
+        ro = osr.brute_force_hide(so, profile)
+        rl = lg.lagom_tune(sl, profile, lg.LAGOM_EXHAUSTIVE_HIDE)
+        assert rl.cfgs == ro.cfgs and rl.levels == ro.levels and rl.calls == ro.calls and (rl.X, rl.Y, rl.Z) == (ro.X, ro.Y, ro.Z)
+    fx = json.load(open(os.path.join(golden_dir, "hide_worked.json")))
+    for case in fx["cases"]:
+        so = [osr.Space(**sp) for sp in case["spaces"]]
+        sl = [lg.Space(**sp) for sp in case["spaces"]]
+        xs, coef = case["x_by_level"], case["Y_coef"]
+
+        def profile(cfgs):
+            lv = [[so[j].cfg(l) for l in range(so[j].K)].index(tuple(c)) for j, c in enumerate(cfgs)]
+            return [xs[j][l] for j, l in enumerate(lv)], coef[0] + sum(coef[1 + j] * l for j, l in enumerate(lv))
+        r = lg.lagom_tune(sl, profile, lg.LAGOM_HIDE_COMM)
+        assert r.levels == case["final_levels"] and r.Y == case["final_Y"] and r.calls == case["calls"]
+        for got, want in zip(r.trace, case["trace"]):
+            assert (got.comm, got.level_from, got.level_to, got.accepted, got.done) == \
+                (want["comm"], want["from"], want["to"], want["accepted"], want["done"])
+        b = lg.lagom_tune(sl, profile, lg.LAGOM_EXHAUSTIVE_HIDE)
+        assert b.levels == case["brute_levels"] and b.Y == case["brute_Y"]
+    with pytest.raises(lg.LagomError):
+        lg.lagom_tune([lg.Space([1], [64], [16])], lambda c: ([1.0], 1.0), 5)
+
+
+def _sweep_points(rng, cfgs):
+    return [lg.SweepPoint(c, float(rng.uniform(5, 500)), float(rng.uniform(5, 500)), float(rng.uniform(100, 900)),
+                          float(rng.uniform(100, 1200)), float(rng.uniform(100, 1500)), float(rng.uniform(1e4, 9e6)),
+                          float(rng.uniform(1e4, 9e6))) for c in cfgs]
+
+
+def test_ladder_chunks_equals_oracle():
+    rng = np.random.default_rng(43)
+    for _ in range(200):
+        grid = sorted(set(int(16 * v) for v in rng.integers(1, 300000, size=rng.integers(1, 9))))
+        nc_max, nt_ref = int(rng.choice([1, 4, 32, 256])), int(rng.choice([128, 256]))
+        per_src = int(rng.integers(0, 1 << 25))
+        cfgs = [(nc, nt, c) for nc in (nc_max, 2 * nc_max) for nt in (128, 256) for c in grid]
+        pts = _sweep_points(rng, cfgs)
+        alone = {p.cfg: p.comm_alone_us for p in pts}
+        for kind in (lg.LAGOM_LADDER_FULL, lg.LAGOM_LADDER_CUT, lg.LAGOM_LADDER_FIXED_CHUNK):
+            assert lg.lagom_ladder_chunks(grid, nc_max, nt_ref, per_src, kind, pts) == osr.ladder_chunks(grid, nc_max, nt_ref, per_src, kind, alone)
+    with pytest.raises(lg.LagomError):
+        lg.lagom_ladder_chunks([32, 16], 4, 256, 100, lg.LAGOM_LADDER_CUT)
+    with pytest.raises(lg.LagomError):
+        lg.lagom_ladder_chunks([16, 32], 4, 256, 100, lg.LAGOM_LADDER_FIXED_CHUNK, None)
+    with pytest.raises(lg.LagomError):
+        lg.lagom_ladder_chunks([16, 32], 4, 256, 100, 9)
+
+
+# ------------------------------------------------------------ model fill and calibration
+def _fill_case(rng):
+    lam = int(rng.choice([8, 64, 256]))
+    bw = float(rng.uniform(1e5, 8e6))
+    geo = omf.Geometry(int(rng.integers(1, 3000)), int(rng.integers(1, 3)), float(rng.uniform(1e3, 5e6)))
+    ncomp, ncomm = int(rng.integers(1, 5)), int(rng.integers(1, 4))
+    nbytes = [float(rng.integers(1, 1 << 28)) for _ in range(ncomm)]
+    cfgs = [(nc, nt, c) for nc in (1, 4, 7) if nc < lam for nt in (128, 256) for c in (4096, 65536)]
+    pts = _sweep_points(rng, cfgs)
+    opts = [omf.SweepPoint(p.cfg, p.comm_corun_us, p.comp_alone_us, p.comp_corun_us, p.v_corun) for p in pts]
+    return lam, bw, geo, ncomp, nbytes, pts, opts
+
+
+def test_model_fill_equals_oracle_bit_for_bit():
+    rng = np.random.default_rng(47)
+    for _ in range(200):
+        lam, bw, geo, ncomp, nbytes, pts, opts = _fill_case(rng)
+        held = [bool(rng.integers(0, 2)) for _ in pts]
+        held[int(rng.integers(0, len(pts)))] = False
+        ml, t_alone = lg.lagom_model_fill(pts, lam, bw, geo.mu, geo.tb, geo.d_bytes, ncomp, nbytes, held)
+        fit = [p for p, h in zip(opts, held) if not h]
+        mo = omf.fill(opts, geo, ncomp, nbytes, lam, bw, theta_points=fit)
+        assert t_alone == omf.t_alone(fit, ncomp)
+        assert [c.theta_us for c in ml.comps] == [c.theta for c in mo.comps]
+        assert [(c.mu, c.tb, c.d_bytes) for c in ml.comps] == [(c.mu, c.tb, c.d_bytes) for c in mo.comps]
+        assert ml.tables == mo.tables
+    # the pencil-worked numbers of tests/test_oracle_model_fill.py through the library
+    pts = [lg.SweepPoint((2, 64, 16), 0.0, 40.0, a, 350.0, 0.0, 0.0, v) for a, v in ((330.0, 10.0), (300.0, 10.0), (360.0, 10.0))]
+    pts[1].cfg, pts[2].cfg, pts[2].v_corun, pts[2].comm_corun_us = (4, 64, 32), (8, 64, 32), 120.0, 20.0
+    m, t_alone = lg.lagom_model_fill(pts, 4, 100.0, 20, 2, 1000.0, 1, [300.0, 100.0])
+    assert t_alone == 330.0 and m.comps[0].theta_us == 30.0
+    assert m.tables[0][(2, 64, 16)] == (30.0, 10.0) and m.tables[1][(2, 64, 16)] == (10.0, 10.0)
+    assert m.tables[0][(8, 64, 32)] == (15.0, 99.0)
+    for bad in [dict(mu=0), dict(tb=0), dict(ncomp=0), dict(comm_bytes=[0.0, 0.0]), dict(lam=0), dict(v_cap_frac=1.0)]:
+        kw = dict(lam=4, bw_peak=100.0, mu=20, tb=2, d_bytes=1000.0, ncomp=1, comm_bytes=[300.0, 100.0])
+        kw.update(bad)
+        with pytest.raises(lg.LagomError) as e:
+            lg.lagom_model_fill(pts, **kw)
+        assert e.value.code == lg.LAGOM_EINVAL
+    with pytest.raises(lg.LagomError):
+        lg.lagom_model_fill(pts, 4, 100.0, 20, 2, 1000.0, 1, [1.0], held_out=[True, True, True])
+
+
+def test_model_calibrate_equals_oracle_bit_for_bit():
+    rng = np.random.default_rng(53)
+    sigmas = [i / 8 for i in range(9)]
+    for trial in range(120):
+        lam, bw, geo, ncomp, nbytes, pts, opts = _fill_case(rng)
+        held = [i % 2 == 1 for i in range(len(pts))] if trial % 3 else None
+        cac = cap = None
+        if trial % 4 == 0:                                   # with cross-stream dependencies
+            cac = [int(rng.integers(-1, min(i + 1, len(nbytes)))) for i in range(ncomp)]
+            cap = [int(rng.integers(-1, min(j, ncomp))) if j > 0 else -1 for j in range(len(nbytes))]
+        co = omf.calibrate(opts, held, geo, ncomp, nbytes, lam, bw, sigmas, cac, cap)
+        cl = lg.lagom_model_calibrate(pts, lam, bw, geo.mu, geo.tb, geo.d_bytes, ncomp, nbytes, sigmas, held,
+                                      comp_after_comm=cac, comm_after_comp=cap)
+        assert (cl.sigma, cl.fit_mean, cl.fit_max, cl.held_mean, cl.held_max, cl.n_fit, cl.n_held) == \
+            (co.sigma, co.fit_mean, co.fit_max, co.held_mean, co.held_max, co.n_fit, co.n_held)
+    # the pencil-worked case
+    fit = lg.SweepPoint((2, 64, 16), 0.0, 1000.0, 330.0, 400.0, 0.0, 0.0, 10.0)
+    held = lg.SweepPoint((1, 64, 16), 0.0, 1000.0, 500.0, 350.0, 0.0, 0.0, 20.0)
+    c = lg.lagom_model_calibrate([fit, held], 4, 100.0, 20, 2, 1000.0, 1, [4000.0], [0.0, 0.5, 1.0], [False, True])
+    assert c.sigma == 0.5 and c.theta_us == 30.0 and c.fit_mean == pytest.approx(1 / 30, rel=1e-12)
+    assert c.held_mean == pytest.approx(2.5 / 350, rel=1e-12)
+    with pytest.raises(lg.LagomError):
+        lg.lagom_model_calibrate([fit], 4, 100.0, 20, 2, 1000.0, 1, [4000.0], [1.5])

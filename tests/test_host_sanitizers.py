@@ -1,4 +1,4 @@
-"""The host-only translation units (errors, cost model, tuner) built with AddressSanitizer and
+"""The host-only translation units (errors, cost model, tuner, model fill) built with AddressSanitizer and
 UndefinedBehaviorSanitizer and driven through every mode and error path by tests/host_sanitize.cpp."""
 import os
 import shutil
@@ -16,7 +16,7 @@ def test_host_code_is_clean_under_asan_and_ubsan(tmp_path):
     cmd = ["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-static-libasan", "-static-libubsan", "-fno-sanitize-recover=all", "-ffp-contract=off",
            "-I", os.path.join(ROOT, "include"), "-I", CSRC,
            os.path.join(ROOT, "tests", "host_sanitize.cpp"),
-           os.path.join(CSRC, "errors.cpp"), os.path.join(CSRC, "cost_model.cpp"), os.path.join(CSRC, "tune.cpp"), "-o", exe]
+           os.path.join(CSRC, "errors.cpp"), os.path.join(CSRC, "cost_model.cpp"), os.path.join(CSRC, "tune.cpp"), os.path.join(CSRC, "model_fill.cpp"), "-o", exe]
     subprocess.check_call(cmd)
     env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0")
     r = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=300)
