@@ -1,13 +1,18 @@
 #!/usr/bin/env python3
 """Benchmark of the Lagom hot path on one MI355X.
 
-One "step" is one pass of the whole overlapped group of the chosen workload (every
-communication launch on one stream, every GEMM on the other, through lagom_overlap_run)
-with the parameters the priority search picked.  Before the timed region the contention
-profiler sweeps the workload's (NC, C[, NT]) grid, the cost model is filled from it, and
-lagom_tune runs once with measured profiles and once with the model.
+One "step" is one pass of the whole overlapped group of a workload (every communication launch on one
+stream, every GEMM on the other) with the parameters the priority search picked.  With no flags all five
+workloads of the benchmark spec run -- tiny, dp_bucket, tp_layer, fsdp_chain, compute_bound -- and the
+headline is the largest, fsdp_chain (eight all-gather / GEMM pairs).  Per workload: the contention
+profiler sweeps the (NC, C[, NT]) grid, the cost model is filled and calibrated from the sweep (half of
+the points held out), lagom_tune runs with measured profiles (Alg. 1/2, the communication-only descent,
+the computation-bound objective) and with the model, and every chosen configuration is timed against the
+default, interleaved round by round.
 
-Prints ONE JSON line:  value = makespan(default NC=8, C=2 MiB, NT=256) / makespan(tuned).
+Prints ONE JSON line: value = makespan(default NC=8, C=2 MiB, NT=256) / makespan(tuned) of the headline
+workload (median over the interleaved rounds); "configs" holds the same figures for every workload.
+All method arithmetic (model fill, calibration, ladders, searches) runs inside liblagom.
 """
 from __future__ import annotations
 
@@ -25,14 +30,18 @@ import numpy as np  # noqa: E402
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 BF16_PEAK_TFLOPS = 2500.0       # MI355X dense bf16 MFMA, published
 LAMBDA = 256                    # compute units
-# Bytes past L2 per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by the same counters' reading of a plain
-# 64 MiB copy (factors 1.9986 and 0.9994); figures and commands: profiles/bench_dp_bucket_hbm_counters.md
-MEASURED_TRAFFIC_BYTES = {
+DEFAULT_CFG = (8, 256, 2 << 20)  # the collective library default the paper quotes (Sec. 4.3), NT from the tiny config
+EXTENDED_NC = (64, 128, 256)     # beyond the workloads' own grids: where the X = Y crossover lies on this part
+FIVE = ["tiny", "dp_bucket", "tp_layer", "fsdp_chain", "compute_bound"]
+HEADLINE = "fsdp_chain"
+# Bytes past L2 per launch, from rocprofv3 FETCH_SIZE and WRITE_SIZE collected over `bench.py --standalone-only
+# --workload <name>` and scaled by the same counters' reading of the 64 MiB calibration copy; a recorded figure per
+# kernel and shape (commands and raw readings: profiles/*_hbm_counters.md), not measured by this run.
+TRAFFIC_FROM_PROFILE = {
     "gemm 4096x4096x4096": int(224.3 * (1 << 20)),
     "reduce_copy bf16 S=8 D=1 count=4194304": int(72.0 * (1 << 20)),
     "reduce_copy f32 S=2 D=1 count=4194304": int(48.0 * (1 << 20)),
 }
-DEFAULT_CFG = (8, 256, 2 << 20)  # the collective library default the paper quotes (Sec. 4.3), NT from the tiny config
 
 
 def _up(x):
@@ -41,7 +50,7 @@ def _up(x):
 
 
 def build_workload(name: str, dependent: bool = False):
-    """Device buffers + launch descriptors of one of the five synthetic overlap groups."""
+    """Device buffers + launch descriptors of one synthetic overlap group."""
     import torch
     from paper_2602_20656_amd import binding as lg, inputs
     w = inputs.WORKLOADS[name]
@@ -91,7 +100,6 @@ def build_workload(name: str, dependent: bool = False):
         peers = [_up(gen(w.seeds[p], w.comm.count)) for p in range(1, 8)]     # the other ranks' partial outputs of this shard
         shard_out = [_up(np.zeros(w.comm.count, np_dt)) for _ in range(ncomm)]
         keep += [peers, shard_out]
-        pipeline_outputs = []                                                  # filled with the GEMM outputs below
     elif name == "rs_ag_pair":
         ncomm = 2
         grads = [_up(gen(w.seeds[p], w.comm.count)) for p in range(8)]
@@ -134,6 +142,7 @@ def build_workload(name: str, dependent: bool = False):
         comm_after_comp = [-1] * ncomm
         for l in launches:
             comm_after_comp[l.comm_id] = max(comm_after_comp[l.comm_id], l.after_comp)
+    torch.cuda.synchronize()           # uploads ran on torch's stream; the library launches on its own streams
     return w, launches, comps, ncomm, keep, (comp_after_comm, comm_after_comp)
 
 
@@ -142,86 +151,60 @@ def comm_bytes(launches):
     return [lg.lagom_comm_bytes(l.op, l.dtype, len(l.srcs), len(l.dsts), l.count) for l in launches]
 
 
-def standalone_comm_roofline(st1, st2, iters, final_iters=20):
-    """Best standalone reduce-copy bandwidth over an extended NC set, on buffers rotated through
-    more than the 256 MB last-level cache so that HBM has to serve them.  Two shapes of the
-    workloads are tried: the two-source fp32 reduce of 16 MiB buffers and the eight-source bf16
-    reduce of 8 MiB shards."""
+def gemm_kernel_name(geo, out_bf16=True):
+    """The kernel lagom_gemm dispatches for a geometry (names as they appear in a kernel trace)."""
+    if (geo.tile_m, geo.tile_n) == (128, 128):
+        return "gemm_bf16_nk128_kernel"
+    if (geo.tile_m, geo.tile_n) == (256, 128):
+        return "gemm_bf16_nk256x128_kernel"
+    return "gemm_bf16_nk_kernel"
+
+
+def rotating_comm_roofline(st1, st2, op, dt_name, nsrc, count, cfgs, iters, final_iters=20):
+    """Standalone bandwidth of one launch shape on buffer sets rotated through more than the 256 MB last-level cache,
+    so that HBM has to serve every launch; the best of `cfgs` is measured once more, last, and reported."""
     import torch
     from paper_2602_20656_amd import binding as lg
-    shapes = [("reduce_copy f32 S=2 D=1 count=4194304", lg.LAGOM_F32, torch.float32, 2, 4194304, 12),
-              ("reduce_copy bf16 S=8 D=1 count=4194304", lg.LAGOM_BF16, torch.bfloat16, 8, 4194304, 8)]
-    best, best_shape = None, None
-    for shape in shapes:
-        name, dt, tdt, nsrc, count, nrot = shape
-        bufs = [[torch.empty(count, dtype=torch.float32, device="cuda").uniform_(-1, 1).to(tdt) for _ in range(nsrc + 1)]
-                for _ in range(nrot)]
-        launches = [lg.CommLaunch(lg.LAGOM_REDUCE_COPY, dt, b[:nsrc], [b[nsrc]], count, 0) for b in bufs]
-        per_launch = lg.lagom_comm_bytes(lg.LAGOM_REDUCE_COPY, dt, nsrc, 1, count)
-        for nc in (256, 512, 1024):
-            for nt in (512, 1024):
-                for chunk in (16 << 10, 32 << 10, 64 << 10, 128 << 10):
-                    t = lg.lagom_overlap_run(launches, [(nc, nt, chunk)], [], st1, st2, 1, iters, lg.LAGOM_ALONE_COMM)
-                    us = t.X_us / nrot
-                    gbps = per_launch / us / 1e3
-                    if best is None or gbps > best["achieved"]:
-                        best_shape = shape
-                        best = {"bound": "hbm", "kernel": "reduce_copy_kernel", "workload": name, "achieved": gbps,
-                                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS,
-                                "traffic": MEASURED_TRAFFIC_BYTES.get(name),
-                                "us_per_launch": us, "bytes_per_launch": per_launch, "cfg": [nc, nt, chunk],
-                                "rotation_mib": nrot * per_launch >> 20}
-        del bufs, launches
-    name, dt, tdt, nsrc, count, nrot = best_shape
-    # context only: the same operator on an 8 times longer buffer (576 MiB per launch, two rotated sets), where the
-    # fixed cost of a launch weighs less: what the kernel sustains once a launch is long enough
-    try:
-        big = count * 8
-        bufs = [[torch.empty(big, dtype=torch.float32, device="cuda").uniform_(-1, 1).to(tdt) for _ in range(nsrc + 1)]
-                for _ in range(2)]
-        launches = [lg.CommLaunch(lg.LAGOM_REDUCE_COPY, dt, b[:nsrc], [b[nsrc]], big, 0) for b in bufs]
-        big_bytes = lg.lagom_comm_bytes(lg.LAGOM_REDUCE_COPY, dt, nsrc, 1, big)
-        cands = [tuple(best["cfg"]), (1024, 1024, 16 << 10), (2048, 1024, 16 << 10), (4096, 512, 8 << 10), (4096, 1024, 16 << 10)]
-        t_big = min((lg.lagom_overlap_run(launches, [c], [], st1, st2, 1, iters, lg.LAGOM_ALONE_COMM).X_us / 2, c) for c in cands)
-        best["long_launch"] = {"count": big, "bytes_per_launch": big_bytes, "cfg": list(t_big[1]), "us_per_launch": t_big[0],
-                               "achieved": big_bytes / t_big[0] / 1e3, "frac": big_bytes / t_big[0] / 1e3 / HBM_PEAK_GBPS}
-        del bufs, launches
-    except RuntimeError:
-        best["long_launch"] = None
-    # context only: the vendor's device-to-device copy (torch's copy_) moving the same number of bytes per launch,
-    # half read and half written, on buffers rotated the same way, launches back to back
-    try:
-        half = best["bytes_per_launch"] // 2
-        pairs = [(torch.empty(half, dtype=torch.uint8, device="cuda").random_(), torch.empty(half, dtype=torch.uint8, device="cuda"))
-                 for _ in range(nrot)]
-        for src, dst in pairs:
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        times = []
-        for _ in range(final_iters):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for src, dst in pairs:
-                dst.copy_(src)
-            e1.record()
-            torch.cuda.synchronize()
-            times.append(e0.elapsed_time(e1) * 1e3 / nrot)
-        v_us = float(np.median(times))
-        best.update({"vendor_copy_us_per_launch": v_us, "vendor_copy_gbps": 2 * half / v_us / 1e3})
-        del pairs
-    except RuntimeError:
-        best.update({"vendor_copy_us_per_launch": None, "vendor_copy_gbps": None})
-    # the figure that is reported, measured last: the winning configuration once more, final_iters passes of nrot launches each
-    # (these are the last dispatches of that kernel in a trace of this run)
-    bufs = [[torch.empty(count, dtype=torch.float32, device="cuda").uniform_(-1, 1).to(tdt) for _ in range(nsrc + 1)]
-            for _ in range(nrot)]
-    launches = [lg.CommLaunch(lg.LAGOM_REDUCE_COPY, dt, b[:nsrc], [b[nsrc]], count, 0) for b in bufs]
-    t = lg.lagom_overlap_run(launches, [tuple(best["cfg"])], [], st1, st2, 2, final_iters, lg.LAGOM_ALONE_COMM)
+    dt, tdt = (lg.LAGOM_F32, torch.float32) if dt_name == "f32" else (lg.LAGOM_BF16, torch.bfloat16)
+    esz = 4 if dt_name == "f32" else 2
+    per_launch = lg.lagom_comm_bytes(op, dt, nsrc, 1, count)
+    nrot = max(2, -(-(576 << 20) // per_launch))
+    out_count = count if op == lg.LAGOM_REDUCE_COPY else nsrc * count
+    bufs = [([torch.empty(count, dtype=torch.float32, device="cuda").uniform_(-1, 1).to(tdt) for _ in range(nsrc)],
+             torch.empty(out_count, dtype=tdt, device="cuda")) for _ in range(nrot)]
+    torch.cuda.synchronize()
+    launches = [lg.CommLaunch(op, dt, srcs, [dst], count, 0) for srcs, dst in bufs]
+    best = None
+    for cfg in cfgs:
+        us = lg.lagom_overlap_run(launches, [cfg], [], st1, st2, 1, iters, lg.LAGOM_ALONE_COMM).X_us / nrot
+        if best is None or us < best[0]:
+            best = (us, cfg)
+    t = lg.lagom_overlap_run(launches, [best[1]], [], st1, st2, 2, final_iters, lg.LAGOM_ALONE_COMM)
     us = t.X_us / nrot
-    best.update({"achieved": best["bytes_per_launch"] / us / 1e3, "frac": best["bytes_per_launch"] / us / 1e3 / HBM_PEAK_GBPS,
-                 "us_per_launch": us, "launches_timed": nrot * final_iters})
-    del bufs, launches
-    return best
+    # the floor of a launch on this grid: the same kernel moving one 16-byte vector per source
+    tiny = [lg.CommLaunch(op, dt, srcs, [dst], 16 // esz, 0) for srcs, dst in bufs]
+    floor_us = lg.lagom_overlap_run(tiny, [best[1]], [], st1, st2, 2, final_iters, lg.LAGOM_ALONE_COMM).X_us / nrot
+    name = f"{'reduce_copy' if op == lg.LAGOM_REDUCE_COPY else 'gather_copy'} {dt_name} S={nsrc} D=1 count={count}"
+    gbps = per_launch / us / 1e3
+    res = {"bound": "hbm", "kernel": "reduce_copy_kernel" if op == lg.LAGOM_REDUCE_COPY else "gather_copy_kernel",
+           "workload": name, "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS,
+           "traffic": None, "traffic_from_profile": TRAFFIC_FROM_PROFILE.get(name),
+           "us_per_launch": us, "bytes_per_launch": per_launch, "cfg": list(best[1]), "rotation_mib": nrot * per_launch >> 20,
+           "launches_timed": nrot * final_iters, "launch_floor_us": floor_us,
+           "frac_outside_launch_floor": per_launch / max(us - floor_us, 1e-9) / 1e3 / HBM_PEAK_GBPS}
+    del bufs, launches, tiny
+    return res
+
+
+def standalone_comm_rooflines(st1, st2, iters):
+    """The two launch shapes of the workloads that move the most bytes: the eight-source bf16 reduce of the TP layer
+    (72 MiB per launch) and the FSDP all-gather copy (64 MiB per launch)."""
+    from paper_2602_20656_amd import binding as lg
+    cands = [(nc, nt, c) for nc in (256, 512, 1024) for nt in (512, 1024) for c in (16 << 10, 32 << 10, 64 << 10)]
+    red = rotating_comm_roofline(st1, st2, lg.LAGOM_REDUCE_COPY, "bf16", 8, 4194304, cands, iters)
+    gat = rotating_comm_roofline(st1, st2, lg.LAGOM_GATHER_COPY, "bf16", 8, 2097152, cands, iters)
+    red["gather_copy_64MiB"] = gat
+    return red
 
 
 def cpu_baseline(name, seconds_target=12.0):
@@ -251,27 +234,312 @@ def cpu_baseline(name, seconds_target=12.0):
         t0 = time.perf_counter(); cloops.gemm(a, b, True, 0, rows2, threads); dt = time.perf_counter() - t0
         rows = rows2
     gemm_us = dt * 1e6 * (M / rows) * w.ncomp
-    return {"value": comm_us + gemm_us, "unit": "us/step", "cores": threads, "kind": "oracle",
+    return {"value": comm_us + gemm_us, "unit": "us/step", "cores": threads, "kind": "oracle", "workload": name,
             "sample": f"communication launches at full size ({comm_us:.0f} us); GEMM rows 0..{rows} of {M}, all columns and K, "
                       f"scaled by {M / rows:.1f} ({gemm_us:.0f} us); no overlap on the CPU",
             "comm_us": comm_us, "gemm_us": gemm_us}
 
 
+def ladder_cfgs(space):
+    K = max(len(space.nc), len(space.nt), len(space.chunk))
+    return [(space.nc[min(l, len(space.nc) - 1)], space.nt[min(l, len(space.nt) - 1)], space.chunk[min(l, len(space.chunk) - 1)])
+            for l in range(K)]
+
+
+def stop_test_audit(result, log):
+    """How often Alg. 2's `x' - x > 0` stop fired on a difference smaller than the spread of the two measurements."""
+    fired = within = 0
+    for k, s in enumerate(result.trace):
+        if s.comm < 0 or s.accepted or not s.done or k >= len(log):
+            continue
+        if s.xj_new - s.xj_prev > 0.0:
+            fired += 1
+            # spread of x' from this call; of x from the call that measured the configuration it is compared with
+            prev = max((i for i in range(k) if i == 0 or result.trace[i].accepted), default=0)
+            spread = log[k]["x_mad"][s.comm] + log[prev]["x_mad"][s.comm]
+            within += (s.xj_new - s.xj_prev) < spread
+    return {"stops_on_x_rise": fired, "of_which_within_spread": within}
+
+
+def run_config(name, args, s_comm, s_comp, dependent=False):
+    import torch
+    from paper_2602_20656_amd import binding as lg
+    t_start = time.perf_counter()
+    w, launches, comps, ncomm, keep, (dep_arg, dep_comm) = build_workload(name, dependent)
+    dependent = dep_arg is not None or dep_comm is not None
+    nbytes = comm_bytes(launches)
+    bytes_per_comm = [float(sum(b for b, l in zip(nbytes, launches) if l.comm_id == j)) for j in range(ncomm)]
+    M, N, K = w.gemm
+    flops = 2.0 * M * N * K
+    geo = lg.lagom_gemm_describe(M, N, K)
+    bw = HBM_PEAK_GBPS * 1e3                                     # bytes per microsecond
+    nt_grid = list(w.nt_grid)
+    nt_ref = 256 if 256 in nt_grid else nt_grid[0]
+    esz = 4 if w.comm.dtype == "f32" else 2
+    per_src = [min(l.count * esz * (len(l.srcs) if l.op == lg.LAGOM_GATHER_COPY else 1) for l in launches if l.comm_id == j)
+               for j in range(ncomm)]
+
+    # ---- contention profiler: the workload's own grid, then the extended channel counts
+    points = [(nc, nt, c) for nt in nt_grid for nc in w.nc_grid for c in w.chunk_grid]
+    ext_points = [(nc, nt, c) for nt in nt_grid for nc in EXTENDED_NC for c in w.chunk_grid]
+    t0 = time.perf_counter()
+    sweep = lg.lagom_contention_sweep(launches, ncomm, comps, points, s_comm, s_comp, 1, args.sweep_iters)
+    sweep_ext = lg.lagom_contention_sweep(launches, ncomm, comps, ext_points, s_comm, s_comp, 1, args.sweep_iters)
+    sweep_s = time.perf_counter() - t0
+    all_sweep = sweep + sweep_ext
+
+    # ---- cost model: filled and calibrated by the library; every second point is held out of the fit
+    usable = [p for p in all_sweep if p.cfg[0] < LAMBDA]          # Eq. 5 needs NC < lambda
+    held = [i % 2 == 1 for i in range(len(usable))]
+    sigmas = [i / 8 for i in range(9)]
+    fill_args = dict(lam=LAMBDA, bw_peak=bw, mu=geo.mu, tb=geo.tb, ncomp=len(comps), comm_bytes=bytes_per_comm)
+    cal = lg.lagom_model_calibrate(usable, d_bytes=geo.d_bytes_past_l2, sigmas=sigmas, held_out=held,
+                                   comp_after_comm=dep_arg, comm_after_comp=dep_comm, **fill_args)
+    cal_all = lg.lagom_model_calibrate(usable, d_bytes=geo.d_bytes_past_l2, sigmas=sigmas, comp_after_comm=dep_arg,
+                                       comm_after_comp=dep_comm, **fill_args)
+    cal_printed = lg.lagom_model_calibrate(usable, d_bytes=geo.d_bytes, sigmas=[0.0], held_out=held,
+                                           comp_after_comm=dep_arg, comm_after_comp=dep_comm, **fill_args)
+    model, _ = lg.lagom_model_fill(usable, d_bytes=geo.d_bytes_past_l2, comp_after_comm=dep_arg, comm_after_comp=dep_comm,
+                                   corun_share=cal_all.sigma, **fill_args)
+    model_printed, _ = lg.lagom_model_fill(usable, d_bytes=geo.d_bytes, comp_after_comm=dep_arg, comm_after_comp=dep_comm,
+                                           corun_share=0.0, **fill_args)
+
+    # ---- ladders (lagom_ladder_chunks): the cut ladder is the graded one; the uncut and the fixed-chunk ones beside it
+    def spaces_for(nc_grid, kind, pts):
+        return [lg.Space(list(nc_grid), nt_grid if len(nt_grid) > 1 else [256],
+                         lg.lagom_ladder_chunks(list(w.chunk_grid), max(nc_grid), nt_ref, per_src[j], kind, pts))
+                for j in range(ncomm)]
+    spaces = spaces_for(w.nc_grid, lg.LAGOM_LADDER_CUT, sweep)
+    spaces_full = spaces_for(w.nc_grid, lg.LAGOM_LADDER_FULL, sweep)
+    spaces_fixed = spaces_for(w.nc_grid, lg.LAGOM_LADDER_FIXED_CHUNK, sweep)
+    ext_nc = list(w.nc_grid) + [n for n in EXTENDED_NC if n > max(w.nc_grid)]
+    spaces_ext = spaces_for(ext_nc, lg.LAGOM_LADDER_FIXED_CHUNK, all_sweep)
+
+    def prof(cap):
+        return lg.OverlapProfile(launches, comps, s_comm, s_comp, 1, args.sweep_iters, min_total_us=args.profile_min_us,
+                                 max_iters=args.profile_max_iters, log_capacity=cap)
+
+    def search(sp, mode, label):
+        cap = 4 + sum(3 * (len(s.nc) + len(s.nt) + len(s.chunk) + 3) for s in sp)
+        p = prof(cap)
+        t0 = time.perf_counter()
+        r = lg.lagom_tune(sp, p, mode)
+        d = {"cfgs": [list(c) for c in r.cfgs], "calls": r.calls, "seconds": time.perf_counter() - t0,
+             "z_search_us": r.Z, "x_search_us": r.X, "y_search_us": r.Y}
+        if mode in (lg.LAGOM_PRIORITY, lg.LAGOM_HIDE_COMM):
+            d.update(stop_test_audit(r, p.log))
+            d["median_rel_spread_x"] = float(np.median([m / max(x, 1e-9) for e in p.log for m, x in zip(e["x_mad"], e["x"])]))
+            d["median_rel_spread_Y"] = float(np.median([e["Y_mad"] / max(e["Y"], 1e-9) for e in p.log]))
+            d["profile_iters"] = int(np.median([e["iters"] for e in p.log]))
+        return r, d, p.log
+
+    searches, logs = {}, {}
+    tuned, searches["priority"], logs["priority"] = search(spaces, lg.LAGOM_PRIORITY, "priority")
+    tuned_full, searches["priority_uncut_ladder"], _ = search(spaces_full, lg.LAGOM_PRIORITY, "uncut")
+    tuned_fixed, searches["priority_fixed_chunk"], logs["priority_fixed_chunk"] = search(spaces_fixed, lg.LAGOM_PRIORITY, "fixed")
+    comm_cd, searches["comm_descent"], _ = search(spaces, lg.LAGOM_COMM_OPTIMAL, "descent")
+    hide, searches["hide_comm"], logs["hide_comm"] = search(spaces_fixed, lg.LAGOM_HIDE_COMM, "hide")
+    tuned_ext, searches["priority_extended"], logs["priority_extended"] = search(spaces_ext, lg.LAGOM_PRIORITY, "ext")
+    hide_ext, searches["hide_comm_extended"], _ = search(spaces_ext, lg.LAGOM_HIDE_COMM, "hide-ext")
+    # brute force over the extended ladder: every level vector for one communication, the uniform vectors otherwise
+    ext_ladder = ladder_cfgs(spaces_ext[0])
+    if ncomm == 1:
+        brute_ext, searches["exhaustive_extended"], _ = search(spaces_ext, lg.LAGOM_EXHAUSTIVE, "brute-ext")
+        brute_hide_ext, searches["exhaustive_hide_extended"], _ = search(spaces_ext, lg.LAGOM_EXHAUSTIVE_HIDE, "brute-hide-ext")
+    else:
+        brute_ext = brute_hide_ext = None
+    # the model as ProfileTime (host only)
+    in_tables = lambda sp: all(tuple(c) in model.tables[j] for j, s in enumerate(sp) for c in ladder_cfgs(s))
+    t0 = time.perf_counter()
+    tuned_model = lg.lagom_tune(spaces, model, lg.LAGOM_PRIORITY) if in_tables(spaces) else None
+    model_tune_us = (time.perf_counter() - t0) * 1e6
+    tuned_printed = lg.lagom_tune(spaces, model_printed, lg.LAGOM_PRIORITY) if in_tables(spaces) else None
+
+    # ---- the first three pairs of the chain: priority search against exhaustive search over the same ladder
+    first3 = None
+    if name == "fsdp_chain" and ncomm >= 3:
+        l3 = [l for l in launches if l.comm_id < 3]
+        c3 = comps[:3]
+        sp3 = [lg.Space(sp.nc[:6], sp.nt, sp.chunk[:6]) for sp in spaces[:3]]
+        prof3 = lg.OverlapProfile(l3, c3, s_comm, s_comp, 1, args.sweep_iters, min_total_us=args.profile_min_us, max_iters=args.profile_max_iters)
+        model3 = lg.Model(model.lam, model.bw_peak, model.comps[:3], model.tables[:3],
+                          comp_after_comm=dep_arg[:3] if dep_arg else None, corun_share=model.corun_share)
+        t0 = time.perf_counter()
+        pr_meas, ex_meas = lg.lagom_tune(sp3, prof3, lg.LAGOM_PRIORITY), lg.lagom_tune(sp3, prof3, lg.LAGOM_EXHAUSTIVE)
+        first3_s = time.perf_counter() - t0
+        pr_mod, ex_mod = lg.lagom_tune(sp3, model3, lg.LAGOM_PRIORITY), lg.lagom_tune(sp3, model3, lg.LAGOM_EXHAUSTIVE)
+        zs = {k: [] for k in ("pm", "em", "pd", "ed")}
+        for _ in range(args.rounds):
+            for k, r in (("pm", pr_meas), ("em", ex_meas), ("pd", pr_mod), ("ed", ex_mod)):
+                zs[k].append(lg.lagom_overlap_run(l3, r.cfgs, c3, s_comm, s_comp, 2, args.steps, lg.LAGOM_CORUN).Z_us)
+        med = lambda v: float(np.median(v))
+        first3 = {"ladder_levels": [max(len(sp.nc), len(sp.nt), len(sp.chunk)) for sp in sp3],
+                  "measured": {"priority_cfgs": [list(c) for c in pr_meas.cfgs], "priority_calls": pr_meas.calls,
+                               "exhaustive_cfgs": [list(c) for c in ex_meas.cfgs], "exhaustive_calls": ex_meas.calls,
+                               "same_cfgs": pr_meas.cfgs == ex_meas.cfgs,
+                               "same_cfgs_up_to_order": sorted(pr_meas.cfgs) == sorted(ex_meas.cfgs),
+                               "z_priority_us": med(zs["pm"]), "z_exhaustive_us": med(zs["em"]),
+                               "z_priority_over_exhaustive": [float(np.min(np.array(zs["pm"]) / np.array(zs["em"]))), med(np.array(zs["pm"]) / np.array(zs["em"])),
+                                                              float(np.max(np.array(zs["pm"]) / np.array(zs["em"])))],
+                               "seconds": first3_s},
+                  "model": {"priority_cfgs": [list(c) for c in pr_mod.cfgs], "priority_calls": pr_mod.calls,
+                            "exhaustive_cfgs": [list(c) for c in ex_mod.cfgs], "exhaustive_calls": ex_mod.calls,
+                            "same_cfgs": pr_mod.cfgs == ex_mod.cfgs,
+                            "same_cfgs_up_to_order": sorted(pr_mod.cfgs) == sorted(ex_mod.cfgs),
+                            "z_priority_model_us": pr_mod.Z, "z_exhaustive_model_us": ex_mod.Z,
+                            "z_priority_us": med(zs["pd"]), "z_exhaustive_us": med(zs["ed"])}}
+
+    # ---- every candidate against the default, interleaved: one measurement of each per round, the order rotating
+    best_sweep = min(sweep, key=lambda p: p.z_corun_us)
+    best_sweep_ext = min(all_sweep, key=lambda p: p.z_corun_us)
+    comm_opt = min(sweep, key=lambda p: p.comm_alone_us)
+    cands = {"default": [DEFAULT_CFG] * ncomm, "tuned": tuned.cfgs, "tuned_uncut_ladder": tuned_full.cfgs,
+             "tuned_fixed_chunk": tuned_fixed.cfgs, "comm_descent": comm_cd.cfgs, "hide_comm": hide.cfgs,
+             "best_swept": [best_sweep.cfg] * ncomm, "comm_optimal": [comm_opt.cfg] * ncomm,
+             "tuned_extended": tuned_ext.cfgs, "hide_comm_extended": hide_ext.cfgs, "best_swept_extended": [best_sweep_ext.cfg] * ncomm}
+    if brute_ext is not None:
+        cands["exhaustive_extended"] = brute_ext.cfgs
+        cands["exhaustive_hide_extended"] = brute_hide_ext.cfgs
+    if tuned_model is not None:
+        cands["model_tuned"] = tuned_model.cfgs
+        cands["printed_model_tuned"] = tuned_printed.cfgs
+    meas = {k: [] for k in cands}
+    order = list(cands)
+    y_alone_rounds = []
+    for r in range(args.rounds):
+        y_alone_rounds.append(lg.lagom_overlap_run(launches, cands["default"], comps, s_comm, s_comp, 2, args.steps, lg.LAGOM_ALONE_COMP))
+        for k in order[r % len(order):] + order[:r % len(order)]:
+            meas[k].append(lg.lagom_overlap_run(launches, cands[k], comps, s_comm, s_comp, 2, args.steps, lg.LAGOM_CORUN))
+    y_alone_sum = float(np.median([sum(t.y_us) for t in y_alone_rounds]))
+    gemm_us = y_alone_sum / len(comps)
+
+    def summary(k):
+        z = np.array([t.Z_us for t in meas[k]])
+        zd = np.array([t.Z_us for t in meas["default"]])
+        ratio = zd / z
+        d = {"cfgs": [list(c) for c in cands[k]], "z_us": float(np.median(z)), "z_rounds_us": [float(v) for v in z],
+             "x_us": float(np.median([sum(t.x_us) for t in meas[k]])), "y_us": float(np.median([sum(t.y_us) for t in meas[k]])),
+             "gemm_slowdown": float(np.median([sum(t.y_us) for t in meas[k]])) / y_alone_sum,
+             "speedup_vs_default": [float(ratio.min()), float(np.median(ratio)), float(ratio.max())]}
+        d["verdict"] = "no gain" if ratio.min() <= 1.0 <= ratio.max() else ("faster" if ratio.min() > 1.0 else "slower")
+        return d
+    results = {k: summary(k) for k in cands}
+
+    # ---- K steps as a training loop would run them: enqueued back to back, streams joined by events only
+    lg.lagom_overlap_steps(launches, tuned.cfgs, comps, s_comm, s_comp, args.warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    chained_tuned_us = lg.lagom_overlap_steps(launches, tuned.cfgs, comps, s_comm, s_comp, args.steps)
+    torch.cuda.synchronize()
+    chained_wall_ms = (time.perf_counter() - t0) * 1e3
+    chained_default_us = lg.lagom_overlap_steps(launches, cands["default"], comps, s_comm, s_comp, args.steps)
+    graph_tuned_us = lg.lagom_overlap_steps_graph(launches, tuned.cfgs, comps, s_comm, s_comp, args.steps)
+
+    tflops = flops / gemm_us / 1e6
+    roofline = {"bound": "mfma", "kernel": gemm_kernel_name(geo), "shape": f"{M}x{N}x{K}", "achieved": tflops, "peak": BF16_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": tflops / BF16_PEAK_TFLOPS, "traffic": None,
+                "traffic_from_profile": TRAFFIC_FROM_PROFILE.get(f"gemm {M}x{N}x{K}"),
+                "us_per_launch": gemm_us, "flop_per_launch": flops, "launches_timed": args.rounds * args.steps * len(comps)}
+    # the workload's own communication, standalone, at its fastest point of the extended sweep (buffers may sit in the last-level cache)
+    fastest = min(all_sweep, key=lambda p: p.comm_alone_us)
+    out = {
+        "comm": f"{w.comm.op} {w.comm.dtype} S={w.comm.nsrc} count={w.comm.count} launches={len(launches)} comms={ncomm}",
+        "gemm": f"{M}x{N}x{K} bf16 x{len(comps)}", "dependent": dependent,
+        "speedup_tuned_vs_default": results["tuned"]["speedup_vs_default"], "verdict": results["tuned"]["verdict"],
+        "z_default_us": results["default"]["z_us"], "z_tuned_us": results["tuned"]["z_us"],
+        "z_comm_descent_us": results["comm_descent"]["z_us"], "z_best_swept_us": results["best_swept"]["z_us"],
+        "z_tuned_extended_us": results["tuned_extended"]["z_us"], "z_best_swept_extended_us": results["best_swept_extended"]["z_us"],
+        "gemm_alone_us": gemm_us, "gemm_mfma_util": tflops / BF16_PEAK_TFLOPS,
+        "comm_alone_fastest_us": fastest.comm_alone_us, "comm_alone_fastest_cfg": list(fastest.cfg),
+        "comm_alone_fastest_gbps": sum(nbytes) / fastest.comm_alone_us / 1e3,
+        "candidates": results, "searches": searches,
+        "ladders": {"cut": [list(sp.chunk) for sp in spaces], "fixed_chunk": [list(sp.chunk) for sp in spaces_fixed],
+                    "extended_nc": ext_nc, "extended_chunk": [list(sp.chunk) for sp in spaces_ext]},
+        "model": {"corun_share": cal_all.sigma, "theta_us": cal_all.theta_us, "d_bytes": geo.d_bytes_past_l2,
+                  "y_err_all_points": [cal_all.fit_mean, cal_all.fit_max],
+                  "held_out": {"sigma_fitted_on_half": cal.sigma, "fit_half": [cal.fit_mean, cal.fit_max],
+                               "held_half": [cal.held_mean, cal.held_max], "n_fit": cal.n_fit, "n_held": cal.n_held},
+                  "as_printed": {"d_bytes": geo.d_bytes, "theta_us": cal_printed.theta_us,
+                                 "fit_half": [cal_printed.fit_mean, cal_printed.fit_max],
+                                 "held_half": [cal_printed.held_mean, cal_printed.held_max]},
+                  "tune_us": model_tune_us if tuned_model else None, "tune_calls": tuned_model.calls if tuned_model else None,
+                  "predicted_z_us": tuned_model.Z if tuned_model else None,
+                  "measured_z_us": results["model_tuned"]["z_us"] if tuned_model else None,
+                  "printed_predicted_z_us": tuned_printed.Z if tuned_printed else None,
+                  "printed_measured_z_us": results["printed_model_tuned"]["z_us"] if tuned_printed else None},
+        "chained_us_per_step_tuned": chained_tuned_us, "chained_us_per_step_default": chained_default_us,
+        "chained_wall_ms_per_step": chained_wall_ms / args.steps, "graph_us_per_step_tuned": graph_tuned_us,
+        "sweep_points": len(all_sweep), "sweep_seconds": sweep_s, "roofline": roofline,
+    }
+    # the computation-bound objective over the swept points: least GEMM slow-down among those whose communication
+    # finishes inside the GEMM window (X <= Y); what LAGOM_HIDE_COMM searches for
+    hidden = [p for p in all_sweep if p.comm_corun_us <= p.comp_corun_us]
+    if hidden:
+        p_min = min(hidden, key=lambda p: p.comp_corun_us)
+        out["swept_min_slowdown_with_comm_hidden"] = {"cfg": list(p_min.cfg), "y_us": p_min.comp_corun_us, "x_us": p_min.comm_corun_us,
+                                                      "gemm_slowdown": p_min.comp_corun_us / p_min.comp_alone_us,
+                                                      "points_with_comm_hidden": len(hidden)}
+    if first3 is not None:
+        out["first_three_pairs_priority_vs_exhaustive"] = first3
+    out["seconds"] = time.perf_counter() - t_start
+    if args.dump:
+        os.makedirs(args.dump, exist_ok=True)
+        with open(os.path.join(args.dump, f"{name}{'_dependent' if dependent else ''}.json"), "w") as f:
+            json.dump({"workload": name, "geometry": {"mu": geo.mu, "tb": geo.tb, "d_bytes": geo.d_bytes, "d_bytes_past_l2": geo.d_bytes_past_l2},
+                       "ncomp": len(comps), "bytes_per_comm": bytes_per_comm, "per_src_bytes": per_src,
+                       "sweep": [p.__dict__ for p in sweep], "sweep_extended": [p.__dict__ for p in sweep_ext],
+                       "traces": {"priority": [s.__dict__ for s in tuned.trace], "priority_extended": [s.__dict__ for s in tuned_ext.trace],
+                                  "hide_comm": [s.__dict__ for s in hide.trace]},
+                       "logs": logs}, f, indent=1, default=str)
+    del keep
+    torch.cuda.empty_cache()
+    return out
+
+
+def standalone_only(args):
+    """Every kernel of the benchmark alone, nothing that needs two kernels at once: the form to run under
+    rocprofv3 --pmc, which serialises dispatches."""
+    import torch
+    from paper_2602_20656_amd import binding as lg
+    s_comm, s_comp = torch.cuda.Stream(), torch.cuda.Stream()
+    names = FIVE if args.workload == "all" else [args.workload]
+    res = {}
+    for name in names:
+        w, launches, comps, ncomm, keep, _ = build_workload(name)
+        M, N, K = w.gemm
+        points = [(nc, 256, c) for nc in (8, 32, 256) for c in (w.chunk_grid[0], w.chunk_grid[-1])]
+        comm_alone = [lg.lagom_overlap_run(launches, [p] * ncomm, comps, s_comm, s_comp, 1, 3, lg.LAGOM_ALONE_COMM).X_us for p in points]
+        t_gemm = lg.lagom_overlap_run(launches, [DEFAULT_CFG] * ncomm, comps, s_comm, s_comp, args.warmup, args.steps, lg.LAGOM_ALONE_COMP)
+        gemm_us = sum(t_gemm.y_us) / len(comps)
+        res[name] = {"gemm_alone_us": gemm_us, "gemm_mfma_util": 2.0 * M * N * K / gemm_us / 1e6 / BF16_PEAK_TFLOPS,
+                     "fastest_comm_alone_us": min(comm_alone)}
+        del keep
+        torch.cuda.empty_cache()
+    roofline_comm = standalone_comm_rooflines(s_comm, s_comp, 3)
+    cal_src = torch.empty(16 << 20, dtype=torch.float32, device="cuda").uniform_(-1, 1)
+    cal_dst = torch.empty_like(cal_src)
+    torch.cuda.synchronize()
+    lg.lagom_comm_kernel(lg.LAGOM_GATHER_COPY, lg.LAGOM_F32, [cal_src], [cal_dst], 16 << 20, (1000, 512, 64 << 10), s_comm)
+    torch.cuda.synchronize()
+    print(json.dumps({"mode": "standalone-only", "configs": res, "roofline_comm": roofline_comm}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="dp_bucket", choices=["tiny", "dp_bucket", "tp_layer", "fsdp_chain", "compute_bound", "ep_alltoall", "rs_ag_pair", "tp_pipeline"])
+    ap.add_argument("--workload", default="all", choices=["all"] + FIVE + ["ep_alltoall", "rs_ag_pair", "tp_pipeline"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--sweep-iters", type=int, default=5)
+    ap.add_argument("--sweep-iters", type=int, default=7)
+    ap.add_argument("--rounds", type=int, default=3, help="interleaved rounds of the tuned-versus-default comparison")
+    ap.add_argument("--profile-min-us", type=float, default=20000.0, help="ProfileTime measures a group for at least this long")
+    ap.add_argument("--profile-max-iters", type=int, default=100)
     ap.add_argument("--dependent", action="store_true",
                     help="fsdp_chain only: GEMM i (i > 0) consumes the weight gathered by communication i-1 and waits for it")
-    ap.add_argument("--dump", default=None, help="write the sweep table and tuner traces to this JSON file")
+    ap.add_argument("--dump", default=None, help="directory for per-workload JSON files with the sweep tables, tuner traces and profile logs")
     ap.add_argument("--standalone-only", action="store_true",
-                    help="run every kernel of the benchmark alone (the sweep's communication launches, the GEMM, the standalone "
-                         "roofline passes, the calibration copy) and nothing that needs two kernels at once: the form to run under "
-                         "rocprofv3 --pmc, which serialises dispatches")
+                    help="run every kernel alone and nothing that needs two kernels at once: the form for rocprofv3 --pmc")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build covers one GPU's share of the overlapped step; run with --gpus 1 "
@@ -282,233 +550,47 @@ def main():
     from paper_2602_20656_amd import binding as lg
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
-    s_comm, s_comp = (torch.cuda.Stream(), torch.cuda.Stream()) if args.standalone_only else lg.overlapping_streams()
-
-    dependent = args.dependent and args.workload == "fsdp_chain"
-    w, launches, comps, ncomm, keep, (dep_arg, dep_comm) = build_workload(args.workload, dependent)
-    dependent = dep_arg is not None or dep_comm is not None
-    nbytes = comm_bytes(launches)
-    M, N, K = w.gemm
-    flops = 2.0 * M * N * K
-
-    # ---- contention profiler over the workload's grid (NT fixed at 256 unless the workload sweeps it)
-    points = [(nc, nt, c) for nt in w.nt_grid for nc in w.nc_grid for c in w.chunk_grid]
     if args.standalone_only:
-        comm_alone = [lg.lagom_overlap_run(launches, [p] * ncomm, comps, s_comm, s_comp, 1, args.sweep_iters, lg.LAGOM_ALONE_COMM).X_us
-                      for p in points]
-        t_gemm = lg.lagom_overlap_run(launches, [DEFAULT_CFG] * ncomm, comps, s_comm, s_comp, args.warmup, args.steps, lg.LAGOM_ALONE_COMP)
-        gemm_us = t_gemm.Y_us / len(comps)
-        roofline_comm = standalone_comm_roofline(s_comm, s_comp, 5)
-        cal_src = torch.empty(16 << 20, dtype=torch.float32, device="cuda").uniform_(-1, 1)
-        cal_dst = torch.empty_like(cal_src)
-        lg.lagom_comm_kernel(lg.LAGOM_GATHER_COPY, lg.LAGOM_F32, [cal_src], [cal_dst], 16 << 20, (1000, 512, 64 << 10), s_comm)
-        torch.cuda.synchronize()
-        print(json.dumps({"mode": "standalone-only", "config": {"workload": args.workload}, "gemm_alone_us": gemm_us,
-                          "gemm_mfma_util": flops / gemm_us / 1e6 / BF16_PEAK_TFLOPS, "roofline_comm": roofline_comm,
-                          "fastest_comm_alone_us": min(comm_alone), "sweep_points": len(points)}))
+        standalone_only(args)
         return
-    t0 = time.perf_counter()
-    sweep = lg.lagom_contention_sweep(launches, ncomm, comps, points, s_comm, s_comp, 1, args.sweep_iters)
-    sweep_s = time.perf_counter() - t0
-
-    # ---- cost model filled from the sweep: x and V per configuration, theta fitted to the standalone GEMM
-    geo = lg.lagom_gemm_describe(M, N, K)
-    bw = HBM_PEAK_GBPS * 1e3                                     # bytes per microsecond
-    y_alone = float(np.median([p.comp_alone_us for p in sweep])) / len(comps)
-    g0 = -(-geo.mu // (LAMBDA * geo.tb))
-    # the sweep times the communication stream as a whole; a communication's x is its share of the bytes
-    share = [sum(b for b, l in zip(nbytes, launches) if l.comm_id == j) / sum(nbytes) for j in range(ncomm)]
-    tables = [{p.cfg: (p.comm_corun_us * share[j], min(p.v_corun, 0.99 * bw)) for p in sweep} for j in range(ncomm)]
-
-    def make_model(d_bytes, sigma):
-        theta = max(0.0, y_alone / g0 - LAMBDA * geo.tb * d_bytes / bw)
-        return lg.Model(LAMBDA, bw, [lg.CompModel(geo.mu, geo.tb, d_bytes, theta) for _ in comps], tables,
-                        comp_after_comm=dep_arg, comm_after_comp=dep_comm, corun_share=sigma), theta
-
-    def y_errors(mdl):   # predicted Y against the measured Y of every sweep point the model was filled from
-        e = [abs(lg.lagom_cost_model(mdl, [pt.cfg] * ncomm).Y_us - pt.comp_corun_us) / pt.comp_corun_us for pt in sweep]
-        return float(np.mean(e)), float(np.max(e))
-
-    # (1) the model as printed: D = all bytes a workgroup reads and writes, a channel takes a compute unit (Eq. 5)
-    model_printed, theta_printed = make_model(geo.d_bytes, 0.0)
-    printed_mape, printed_max = y_errors(model_printed)
-    # (2) calibrated to this part: D = the bytes that leave the XCD's L2, and the share sigma of a channel's
-    #     compute unit that stays with the GEMM (its wavefronts run beside the GEMM's) fitted to the sweep
-    fits = []
-    for sigma in [i / 8 for i in range(9)]:
-        mdl, th = make_model(geo.d_bytes_past_l2, sigma)
-        fits.append((y_errors(mdl), sigma, mdl, th))
-    (model_y_mape, model_y_max), sigma_fit, model, theta = min(fits, key=lambda f: f[0][0])
-
-    # ---- the search: Alg. 1/2 with measured profiles, and with the model as ProfileTime
-    nt_grid = list(w.nt_grid) if len(w.nt_grid) > 1 else [256]
-    # The ladder's chunk grid is cut where a chunk would exceed (bytes one launch moves per source) / NC_max:
-    # beyond that point part of the channels of every launch have no chunk to move (chunk g goes to channel
-    # g mod NC), so a higher level could only be slower.  The profiler still sweeps the full grid.
-    spaces = []
-    for j in range(ncomm):
-        esz = 4 if w.comm.dtype == "f32" else 2
-        per_src = min(l.count * esz * (len(l.srcs) if l.op == lg.LAGOM_GATHER_COPY else 1) for l in launches if l.comm_id == j)
-        cut = [c for c in w.chunk_grid if c * max(w.nc_grid) <= per_src] or [min(w.chunk_grid)]
-        spaces.append(lg.Space(list(w.nc_grid), nt_grid, cut))
-    ladder_ok = all(tuple(c) in tables[0] for c in
-                    [(spaces[0].nc[min(l, len(spaces[0].nc) - 1)], spaces[0].nt[min(l, len(spaces[0].nt) - 1)],
-                      spaces[0].chunk[min(l, len(spaces[0].chunk) - 1)]) for l in range(max(len(spaces[0].nc), len(spaces[0].nt), len(spaces[0].chunk)))])
-    t0 = time.perf_counter()
-    tuned = lg.lagom_tune(spaces, lg.OverlapProfile(launches, comps, s_comm, s_comp, 1, args.sweep_iters), lg.LAGOM_PRIORITY)
-    tune_s = time.perf_counter() - t0
-    t0 = time.perf_counter()
-    tuned_model = lg.lagom_tune(spaces, model, lg.LAGOM_PRIORITY) if ladder_ok else None
-    model_tune_us = (time.perf_counter() - t0) * 1e6      # host only: Alg. 1/2 with the native cost-model callback (binding marshalling included)
-    tuned_printed = lg.lagom_tune(spaces, model_printed, lg.LAGOM_PRIORITY) if ladder_ok else None
-    # the communication-bound reference (Eq. 2): per-communication coordinate descent on x_j alone
-    comm_cd = lg.lagom_tune(spaces, lg.OverlapProfile(launches, comps, s_comm, s_comp, 1, args.sweep_iters), lg.LAGOM_COMM_OPTIMAL)
-
-    # ---- the first three pairs of the chain: priority search against exhaustive search over the same ladder
-    #      (216 level vectors), with measured profiles and with the calibrated model as ProfileTime
-    first3 = None
-    if args.workload == "fsdp_chain" and ncomm >= 3 and ladder_ok:
-        l3 = [l for l in launches if l.comm_id < 3]
-        c3 = comps[:3]
-        sp3 = [lg.Space(sp.nc[:6], sp.nt, sp.chunk[:6]) for sp in spaces[:3]]
-        prof3 = lg.OverlapProfile(l3, c3, s_comm, s_comp, 1, args.sweep_iters)
-        model3 = lg.Model(model.lam, model.bw_peak, model.comps[:3], model.tables[:3],
-                          comp_after_comm=dep_arg[:3] if dep_arg else None, corun_share=model.corun_share)
-        t0 = time.perf_counter()
-        pr_meas, ex_meas = lg.lagom_tune(sp3, prof3, lg.LAGOM_PRIORITY), lg.lagom_tune(sp3, prof3, lg.LAGOM_EXHAUSTIVE)
-        first3_s = time.perf_counter() - t0
-        pr_mod, ex_mod = lg.lagom_tune(sp3, model3, lg.LAGOM_PRIORITY), lg.lagom_tune(sp3, model3, lg.LAGOM_EXHAUSTIVE)
-        run3 = lambda cfgs: lg.lagom_overlap_run(l3, cfgs, c3, s_comm, s_comp, args.warmup, args.steps, lg.LAGOM_CORUN).Z_us
-        first3 = {"ladder_levels": [max(len(sp.nc), len(sp.nt), len(sp.chunk)) for sp in sp3],
-                  "measured": {"priority_cfgs": [list(c) for c in pr_meas.cfgs], "priority_calls": pr_meas.calls,
-                               "exhaustive_cfgs": [list(c) for c in ex_meas.cfgs], "exhaustive_calls": ex_meas.calls,
-                               "z_priority_us": run3(pr_meas.cfgs), "z_exhaustive_us": run3(ex_meas.cfgs), "seconds": first3_s},
-                  "model": {"priority_cfgs": [list(c) for c in pr_mod.cfgs], "priority_calls": pr_mod.calls,
-                            "exhaustive_cfgs": [list(c) for c in ex_mod.cfgs], "exhaustive_calls": ex_mod.calls,
-                            "z_priority_model_us": pr_mod.Z, "z_exhaustive_model_us": ex_mod.Z,
-                            "z_priority_us": run3(pr_mod.cfgs), "z_exhaustive_us": run3(ex_mod.cfgs)}}
-
-    # ---- timed region: W warm-up steps, then exactly K steps with the tuned parameters
-    default_cfgs = [DEFAULT_CFG] * ncomm
-    lg.lagom_overlap_run(launches, tuned.cfgs, comps, s_comm, s_comp, args.warmup, 1, lg.LAGOM_CORUN)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    t_tuned = lg.lagom_overlap_run(launches, tuned.cfgs, comps, s_comm, s_comp, 0, args.steps, lg.LAGOM_CORUN)
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
-    t_default = lg.lagom_overlap_run(launches, default_cfgs, comps, s_comm, s_comp, args.warmup, args.steps, lg.LAGOM_CORUN)
-    # the same K steps once more as a training loop would run them: enqueued back to back, streams joined by events only
-    lg.lagom_overlap_steps(launches, tuned.cfgs, comps, s_comm, s_comp, args.warmup)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    chained_tuned_us = lg.lagom_overlap_steps(launches, tuned.cfgs, comps, s_comm, s_comp, args.steps)
-    torch.cuda.synchronize()
-    chained_wall_ms = (time.perf_counter() - t0) * 1e3
-    chained_default_us = lg.lagom_overlap_steps(launches, default_cfgs, comps, s_comm, s_comp, args.steps)
-    t0 = time.perf_counter()
-    graph_tuned_us = lg.lagom_overlap_steps_graph(launches, tuned.cfgs, comps, s_comm, s_comp, args.steps)
-    graph_wall_ms = (time.perf_counter() - t0) * 1e3      # includes capture, instantiation and one eager repetition
-    best_sweep = min(sweep, key=lambda p: p.z_corun_us)
-    comm_opt = min(sweep, key=lambda p: p.comm_alone_us)
-    t_commopt = lg.lagom_overlap_run(launches, [comm_opt.cfg] * ncomm, comps, s_comm, s_comp, args.warmup, args.steps, lg.LAGOM_CORUN)
-    t_commcd = lg.lagom_overlap_run(launches, comm_cd.cfgs, comps, s_comm, s_comp, args.warmup, args.steps, lg.LAGOM_CORUN)
-    t_model = (lg.lagom_overlap_run(launches, tuned_model.cfgs, comps, s_comm, s_comp, args.warmup, args.steps, lg.LAGOM_CORUN)
-               if tuned_model else None)
-    t_printed = (lg.lagom_overlap_run(launches, tuned_printed.cfgs, comps, s_comm, s_comp, args.warmup, args.steps, lg.LAGOM_CORUN)
-                 if tuned_printed else None)
-
-    # ---- roofline of the dominant kernel (the GEMM), measured live with HIP events on its own stream
-    t_gemm = lg.lagom_overlap_run(launches, default_cfgs, comps, s_comm, s_comp, args.warmup, args.steps, lg.LAGOM_ALONE_COMP)
-    gemm_us = t_gemm.Y_us / len(comps)
-    tflops = flops / gemm_us / 1e6
-    roofline = {"bound": "mfma", "kernel": "gemm_bf16_nk_kernel", "achieved": tflops, "peak": BF16_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": tflops / BF16_PEAK_TFLOPS,
-                "traffic": MEASURED_TRAFFIC_BYTES.get(f"gemm {M}x{N}x{K}"),
-                "us_per_launch": gemm_us, "flop_per_launch": flops}
-    # context only: the vendor BLAS for the same product (torch.matmul), timed the same way -- one event pair per launch
-    vendor_us = None
-    try:
-        tA = torch.randn(M, K, device="cuda").bfloat16()
-        tB = (torch.randn(N, K, device="cuda") * 0.02).bfloat16()
-        with torch.cuda.stream(s_comp):
-            for _ in range(args.warmup):
-                torch.matmul(tA, tB.t())
-            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-            for e0, e1 in ev:
-                e0.record(); torch.matmul(tA, tB.t()); e1.record()
-        torch.cuda.synchronize()
-        vendor_us = float(np.median([e0.elapsed_time(e1) for e0, e1 in ev])) * 1e3
-        del tA, tB
-    except Exception:        # the reference is optional; the bench line does not depend on it
-        vendor_us = None
-    roofline_comm = standalone_comm_roofline(s_comm, s_comp, 5)
-    # the workload's own communication, standalone, at its fastest swept point
-    t_comm = lg.lagom_overlap_run(launches, [comm_opt.cfg] * ncomm, comps, s_comm, s_comp, args.warmup, args.steps, lg.LAGOM_ALONE_COMM)
+    s_comm, s_comp = lg.overlapping_streams()
+    names = FIVE if args.workload == "all" else [args.workload]
+    headline = HEADLINE if args.workload == "all" else args.workload
+    configs = {}
+    for name in names:
+        configs[name] = run_config(name, args, s_comm, s_comp, dependent=args.dependent and name == "fsdp_chain")
+        print(f"bench: {name} done in {configs[name]['seconds']:.1f} s, tuned/default "
+              f"{configs[name]['speedup_tuned_vs_default'][1]:.3f}x ({configs[name]['verdict']})", file=sys.stderr, flush=True)
+    roofline_comm = standalone_comm_rooflines(s_comm, s_comp, 5)
 
     # one plain copy of known size (64 MiB read, 64 MiB written): the reference that rocprofv3's FETCH_SIZE /
     # WRITE_SIZE readings of the other kernels are scaled by
     cal_src = torch.empty(16 << 20, dtype=torch.float32, device="cuda").uniform_(-1, 1)
     cal_dst = torch.empty_like(cal_src)
+    torch.cuda.synchronize()
     lg.lagom_comm_kernel(lg.LAGOM_GATHER_COPY, lg.LAGOM_F32, [cal_src], [cal_dst], 16 << 20, (1000, 512, 64 << 10), s_comm)
     torch.cuda.synchronize()
 
+    h = configs[headline]
     out = {
         "metric": "overlap makespan speedup vs default params",
-        "value": t_default.Z_us / t_tuned.Z_us,
+        "value": h["speedup_tuned_vs_default"][1],
         "unit": "x",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": chained_wall_ms / args.steps,       # K back-to-back steps with the tuned parameters, host clock between synchronisations
-        "gated_wall_ms_per_step": wall_ms / args.steps,    # the same K steps run one by one behind a start gate (what z_tuned_us is the median of)
+        "ms_per_step": h["chained_wall_ms_per_step"],      # K back-to-back steps of the headline workload with the tuned parameters
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": args.workload + ("+dependent" if dependent else ""), "comm": f"{w.comm.op} {w.comm.dtype} S={w.comm.nsrc} count={w.comm.count} "
-                   f"launches={len(launches)} comms={ncomm}", "gemm": f"{M}x{N}x{K} bf16 x{len(comps)}",
-                   "default_cfg": list(DEFAULT_CFG), "tuned_cfgs": [list(c) for c in tuned.cfgs],
-                   "ladder_chunk_grids": [list(sp.chunk) for sp in spaces]},
-        "z_tuned_us": t_tuned.Z_us, "z_default_us": t_default.Z_us,
-        "chained_us_per_step_tuned": chained_tuned_us, "chained_us_per_step_default": chained_default_us,
-        "chained_speedup": chained_default_us / chained_tuned_us,
-        "graph_us_per_step_tuned": graph_tuned_us, "graph_call_wall_ms": graph_wall_ms,
-        "x_tuned_us": t_tuned.X_us, "y_tuned_us": t_tuned.Y_us, "x_default_us": t_default.X_us, "y_default_us": t_default.Y_us,
-        "z_comm_optimal_us": t_commopt.Z_us, "comm_optimal_cfg": list(comm_opt.cfg),
-        "z_comm_descent_us": t_commcd.Z_us, "comm_descent_cfgs": [list(c) for c in comm_cd.cfgs], "comm_descent_calls": comm_cd.calls,
-        "z_best_swept_us": best_sweep.z_corun_us, "best_swept_cfg": list(best_sweep.cfg),
-        "z_model_tuned_us": t_model.Z_us if t_model else None,
-        "model_tuned_cfgs": [list(c) for c in tuned_model.cfgs] if tuned_model else None,
-        "model_predicted_z_us": lg.lagom_cost_model(model, tuned_model.cfgs).Z_us if tuned_model else None,
-        "model_y_mean_abs_rel_err": model_y_mape, "model_y_max_abs_rel_err": model_y_max,
-        "model_corun_share": sigma_fit, "model_d_bytes": geo.d_bytes_past_l2, "model_theta_us": theta,
-        "printed_model_y_mean_abs_rel_err": printed_mape, "printed_model_y_max_abs_rel_err": printed_max,
-        "printed_model_d_bytes": geo.d_bytes, "printed_model_theta_us": theta_printed,
-        "z_printed_model_tuned_us": t_printed.Z_us if t_printed else None,
-        "printed_model_predicted_z_us": lg.lagom_cost_model(model_printed, tuned_printed.cfgs).Z_us if tuned_printed else None,
-        "model_tune_us": model_tune_us if tuned_model else None, "model_tune_profile_calls": tuned_model.calls if tuned_model else None,
-        "tune_profile_calls": tuned.calls, "tune_seconds": tune_s, "sweep_points": len(points), "sweep_seconds": sweep_s,
-        "gemm_alone_us": gemm_us, "gemm_mfma_util": tflops / BF16_PEAK_TFLOPS,
-        "vendor_blas_gemm_us": vendor_us, "vendor_blas_mfma_util": (flops / vendor_us / 1e6 / BF16_PEAK_TFLOPS) if vendor_us else None,
-        "gemm_slowdown_default": t_default.Y_us / t_gemm.Y_us, "gemm_slowdown_tuned": t_tuned.Y_us / t_gemm.Y_us,
-        "comm_alone_us": t_comm.X_us, "comm_alone_gbps": sum(nbytes) / t_comm.X_us / 1e3,
-        "comm_hbm_gbps": roofline_comm["achieved"],
-        "roofline": roofline, "roofline_comm": roofline_comm,
+        "config": {"workload": headline + ("+dependent" if h["dependent"] else ""), "comm": h["comm"], "gemm": h["gemm"],
+                   "default_cfg": list(DEFAULT_CFG), "tuned_cfgs": h["candidates"]["tuned"]["cfgs"], "rounds": args.rounds},
+        "value_min_median_max": h["speedup_tuned_vs_default"], "verdict": h["verdict"],
+        "z_tuned_us": h["z_tuned_us"], "z_default_us": h["z_default_us"],
+        "comm_hbm_gbps": roofline_comm["achieved"], "gemm_mfma_util": h["gemm_mfma_util"],
+        "gemm_mfma_util_by_shape": {c["roofline"]["shape"]: c["roofline"]["frac"] for c in configs.values()},
+        "roofline": h["roofline"], "roofline_comm": roofline_comm,
+        "configs": configs,
     }
-    # the compute-bound objective: the swept point with the least GEMM slow-down among those whose communication
-    # still finishes inside the GEMM window (X <= Y)
-    hidden = [p for p in sweep if p.comm_corun_us <= p.comp_corun_us]
-    if hidden:
-        p_min = min(hidden, key=lambda p: p.comp_corun_us)
-        out["min_slowdown_with_comm_hidden"] = {"cfg": list(p_min.cfg), "y_us": p_min.comp_corun_us, "x_us": p_min.comm_corun_us,
-                                                "gemm_slowdown": p_min.comp_corun_us / p_min.comp_alone_us,
-                                                "points_with_comm_hidden": len(hidden)}
-    if first3 is not None:
-        out["first_three_pairs_priority_vs_exhaustive"] = first3
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(args.workload)
-    if args.dump:
-        with open(args.dump, "w") as f:
-            json.dump({"sweep": [p.__dict__ for p in sweep],
-                       "trace": [s.__dict__ for s in tuned.trace],
-                       "model_trace": [s.__dict__ for s in tuned_model.trace] if tuned_model else None,
-                       "theta_us": theta, "geometry": {"mu": geo.mu, "tb": geo.tb, "d_bytes": geo.d_bytes}}, f, indent=1, default=str)
+        out["cpu_baseline"] = cpu_baseline(headline)
     print(json.dumps(out))
 
 

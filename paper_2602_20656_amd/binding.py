@@ -151,6 +151,9 @@ def lib() -> C.CDLL:
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2602_20656_amd.build` "
                               "(there is no CPU fallback)")
+        # PyTorch carries its own copy of the HIP runtime.  Whichever copy is loaded first serves the whole process, and
+        # a second one sees no device: load torch's before this library so that tensors, streams and kernels share one.
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         L.lagom_strerror.restype = C.c_char_p
         L.lagom_strerror.argtypes = [C.c_int]
