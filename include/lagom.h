@@ -365,6 +365,10 @@ int lagom_model_calibrate(const lagom_sweep_point* pts, int npts, const uint8_t*
  * resources on the path that hide the communication; raising anything further only adds
  * contention).  If no visited vector hides the communication the result is the priority
  * search's last accepted vector.
+ * LAGOM_PRIORITY_FREE: LAGOM_PRIORITY, except that a trial with X' < Y' which also lowered Y (H of Eq. 7
+ * negative: the step made the communication faster at no cost to the computation) is accepted like any
+ * other step and does not end the communication.  Alg. 2 stops at X' < Y' because more resources can only
+ * lengthen the computation (Sec. 3.2); this variant is for hardware on which that does not hold.
  * LAGOM_EXHAUSTIVE_HIDE: every level vector; among those with X <= Y the smallest Y wins (ties:
  * smallest level sum, then lexicographic); if none has X <= Y, the smallest Z as in
  * LAGOM_EXHAUSTIVE.
@@ -397,7 +401,7 @@ typedef struct {
 } lagom_trace;
 
 typedef enum { LAGOM_PRIORITY = 0, LAGOM_EXHAUSTIVE = 1, LAGOM_COMM_OPTIMAL = 2,
-               LAGOM_HIDE_COMM = 3, LAGOM_EXHAUSTIVE_HIDE = 4 } lagom_tune_mode;
+               LAGOM_HIDE_COMM = 3, LAGOM_EXHAUSTIVE_HIDE = 4, LAGOM_PRIORITY_FREE = 5 } lagom_tune_mode;
 
 /*   spaces[ncomm], out_cfgs[ncomm] host arrays; trace nullable.
  * Errors: LAGOM_EINVAL (null, ncomm < 1 or > LAGOM_MAX_COMMS, empty or non-ascending

@@ -126,8 +126,15 @@ def next_level(space: Space, level: int, lr: Optional[float]) -> int:
     return top
 
 
-def priority_search(spaces: Sequence[Space], profile: ProfileFn) -> Result:
-    """Alg. 1 driving Alg. 2."""
+def priority_search(spaces: Sequence[Space], profile: ProfileFn, free_steps: bool = False) -> Result:
+    """Alg. 1 driving Alg. 2.
+
+    free_steps (default off = the algorithm as printed).  Alg. 2 ends a communication at "X' < Y'" because, by the paper's
+    contention analysis (Sec. 3.2), any further resource can only lengthen the computation.  Where a step makes the
+    communication faster *and* the computation faster (H of Eq. 7 negative: the step costs nothing), that reason does
+    not apply; with free_steps such a step is accepted like any other and the communication stays in the search.  A
+    hidden step that does not lower Y ends the communication exactly as printed.
+    """
     N = len(spaces)
     lev = [0] * N
     H = [H_INIT] * N
@@ -157,7 +164,7 @@ def priority_search(spaces: Sequence[Space], profile: ProfileFn) -> Result:
         if x2[j] - x[j] > 0.0:      # Alg. 2: the communication itself got slower
             done[j] = True
             accepted = False
-        elif X2 < Y2:               # Alg. 2: all communication is hidden
+        elif X2 < Y2 and not (free_steps and Y2 < Y):   # Alg. 2: all communication is hidden
             done[j] = True
             accepted = Z2 < Z
         else:

@@ -23,7 +23,7 @@ LAGOM_OK, LAGOM_EINVAL, LAGOM_EALIGN, LAGOM_EHIP, LAGOM_ECALLBACK = 0, -1, -2, -
 LAGOM_F32, LAGOM_BF16 = 0, 1
 LAGOM_REDUCE_COPY, LAGOM_GATHER_COPY = 0, 1
 LAGOM_ALONE_COMM, LAGOM_ALONE_COMP, LAGOM_CORUN = 0, 1, 2
-LAGOM_PRIORITY, LAGOM_EXHAUSTIVE, LAGOM_COMM_OPTIMAL, LAGOM_HIDE_COMM, LAGOM_EXHAUSTIVE_HIDE = 0, 1, 2, 3, 4
+LAGOM_PRIORITY, LAGOM_EXHAUSTIVE, LAGOM_COMM_OPTIMAL, LAGOM_HIDE_COMM, LAGOM_EXHAUSTIVE_HIDE, LAGOM_PRIORITY_FREE = 0, 1, 2, 3, 4, 5
 LAGOM_LADDER_FULL, LAGOM_LADDER_CUT, LAGOM_LADDER_FIXED_CHUNK = 0, 1, 2
 LAGOM_MAX_SRCS, LAGOM_MAX_DSTS, LAGOM_MAX_LAUNCHES, LAGOM_MAX_COMMS = 16, 4, 256, 64
 

@@ -85,9 +85,11 @@ int push(lagom_trace* tr, const lagom_trace_step& s) {
     return LAGOM_OK;
 }
 
+// free_steps: a hidden step that also lowered Y (H of Eq. 7 negative: it cost the computation nothing) does not end the
+// communication; it is accepted like any other step.
 // hide = false: Alg. 1 driving Alg. 2.  hide = true: the same walk for the computation-bound objective (least Y
 // subject to X <= Y): it ends, for every communication, at the first vector with X <= Y, which is kept.
-int priority(const std::vector<Ladder>& L, lagom_profile_fn profile, void* user, lagom_cfg* out_cfgs, lagom_trace* tr, bool hide) {
+int priority(const std::vector<Ladder>& L, lagom_profile_fn profile, void* user, lagom_cfg* out_cfgs, lagom_trace* tr, bool hide, bool free_steps) {
     const int N = (int)L.size();
     const double nan = std::numeric_limits<double>::quiet_NaN();
     const double inf = std::numeric_limits<double>::infinity();
@@ -128,7 +130,7 @@ int priority(const std::vector<Ladder>& L, lagom_profile_fn profile, void* user,
             accepted = true;
             for (int i = 0; i < N; ++i) done[i] = 1;
             ndone = N - 1;                          // the step's own bookkeeping below adds the last one
-        } else if (!hide && trial.X < trial.Y) {   // Alg. 2: all communication is hidden
+        } else if (!hide && trial.X < trial.Y && !(free_steps && trial.Y < cur.Y)) {   // Alg. 2: all communication is hidden
             done[j] = 1; accepted = trial.Z < cur.Z;
         } else {
             accepted = true;
@@ -251,7 +253,7 @@ extern "C" int lagom_tune(const lagom_tune_space* spaces, int ncomm, lagom_profi
                           int mode, lagom_cfg* out_cfgs, lagom_trace* trace) {
     if (!spaces || !profile || !out_cfgs) return lagom::fail(LAGOM_EINVAL, "null argument");
     if (ncomm < 1 || ncomm > LAGOM_MAX_COMMS) return lagom::fail(LAGOM_EINVAL, "ncomm=%d outside 1..%d", ncomm, LAGOM_MAX_COMMS);
-    if (mode < LAGOM_PRIORITY || mode > LAGOM_EXHAUSTIVE_HIDE) return lagom::fail(LAGOM_EINVAL, "unknown mode %d", mode);
+    if (mode < LAGOM_PRIORITY || mode > LAGOM_PRIORITY_FREE) return lagom::fail(LAGOM_EINVAL, "unknown mode %d", mode);
     std::vector<Ladder> L(ncomm);
     for (int j = 0; j < ncomm; ++j) {
         const lagom_tune_space& s = spaces[j];
@@ -264,7 +266,8 @@ extern "C" int lagom_tune(const lagom_tune_space* spaces, int ncomm, lagom_profi
         trace->n = 0; trace->calls = 0;
         if (trace->steps && trace->capacity < 0) return lagom::fail(LAGOM_EINVAL, "negative trace capacity");
     }
-    if (mode == LAGOM_PRIORITY || mode == LAGOM_HIDE_COMM) return priority(L, profile, user, out_cfgs, trace, mode == LAGOM_HIDE_COMM);
+    if (mode == LAGOM_PRIORITY || mode == LAGOM_HIDE_COMM || mode == LAGOM_PRIORITY_FREE)
+        return priority(L, profile, user, out_cfgs, trace, mode == LAGOM_HIDE_COMM, mode == LAGOM_PRIORITY_FREE);
     if (mode == LAGOM_EXHAUSTIVE || mode == LAGOM_EXHAUSTIVE_HIDE) return exhaustive(L, profile, user, out_cfgs, trace, mode == LAGOM_EXHAUSTIVE_HIDE);
     return comm_optimal(L, profile, user, out_cfgs, trace);
 }

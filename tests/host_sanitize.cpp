@@ -64,7 +64,7 @@ int main() {
         std::vector<lagom_cfg> out(N);
         std::vector<lagom_trace_step> steps(8 * N + 4);
         std::vector<int32_t> lev(N);
-        for (int mode : {LAGOM_PRIORITY, LAGOM_COMM_OPTIMAL, LAGOM_EXHAUSTIVE, LAGOM_HIDE_COMM, LAGOM_EXHAUSTIVE_HIDE}) {
+        for (int mode : {LAGOM_PRIORITY, LAGOM_COMM_OPTIMAL, LAGOM_EXHAUSTIVE, LAGOM_HIDE_COMM, LAGOM_EXHAUSTIVE_HIDE, LAGOM_PRIORITY_FREE}) {
             if ((mode == LAGOM_EXHAUSTIVE || mode == LAGOM_EXHAUSTIVE_HIDE) && N > 3) continue;
             int calls = 0;
             lagom_trace tr{steps.data(), (int32_t)steps.size(), 0, 0, 0, 0, 0, lev.data()};

@@ -1,0 +1,83 @@
+"""The tuner's choice against brute force on the first three pairs of the FSDP chain, driven by the cost model filled
+from a recorded sweep of that chain (tests/golden/fsdp_chain_sweep.json: timings, input data).  Library and oracle are
+run side by side from the same table; the comparison with brute force is asserted where it holds and bounded and
+printed where it does not (the search is a heuristic for N >= 2: Sec. 3.3-3.4 make no optimality claim beyond "can find
+the optimal configuration", Sec. 4.4)."""
+import json
+import os
+
+import pytest
+
+from oracle import cost_model as ocm, model_fill as omf, search as osr
+from paper_2602_20656_amd import binding as lg
+
+
+@pytest.fixture(scope="module")
+def table(golden_dir):
+    t = json.load(open(os.path.join(golden_dir, "fsdp_chain_sweep.json")))
+    total = float(sum(t["bytes_per_comm"]))
+    for p in t["points"]:
+        p["v_corun"] = total / p["comm_corun_us"]
+        p["v_alone"] = total / p["comm_alone_us"]
+    return t
+
+
+def _models(t, d_key, sigmas):
+    geo, lam, bw = t["geometry"], t["lambda"], t["bw_peak_bytes_per_us"]
+    usable = [p for p in t["points"] if p["cfg"][0] < lam]
+    lpts = [lg.SweepPoint(tuple(p["cfg"]), p["comm_alone_us"], p["comm_corun_us"], p["comp_alone_us"], p["comp_corun_us"],
+                          p["z_corun_us"], p["v_alone"], p["v_corun"]) for p in usable]
+    opts = [omf.SweepPoint(tuple(p["cfg"]), p["comm_corun_us"], p["comp_alone_us"], p["comp_corun_us"], p["v_corun"]) for p in usable]
+    ogeo = omf.Geometry(geo["mu"], geo["tb"], geo[d_key])
+    cl = lg.lagom_model_calibrate(lpts, lam, bw, geo["mu"], geo["tb"], geo[d_key], t["ncomp"], t["bytes_per_comm"], sigmas)
+    co = omf.calibrate(opts, None, ogeo, t["ncomp"], t["bytes_per_comm"], lam, bw, sigmas)
+    assert (cl.sigma, cl.fit_mean, cl.fit_max) == (co.sigma, co.fit_mean, co.fit_max)
+    ml, _ = lg.lagom_model_fill(lpts, lam, bw, geo["mu"], geo["tb"], geo[d_key], t["ncomp"], t["bytes_per_comm"], corun_share=cl.sigma)
+    mo = omf.fill(opts, ogeo, t["ncomp"], t["bytes_per_comm"], lam, bw, co.sigma)
+    assert ml.tables == mo.tables
+    # the first three pairs
+    ml3 = lg.Model(ml.lam, ml.bw_peak, ml.comps[:3], ml.tables[:3], corun_share=ml.corun_share)
+    mo3 = ocm.Model(mo.lam, mo.bw_peak, mo.comps[:3], mo.tables[:3], corun_share=mo.corun_share)
+    return ml3, mo3, cl
+
+
+def _ladder(t):
+    per_src = t["per_src_bytes"][0]
+    chunks = lg.lagom_ladder_chunks(t["chunk_grid"], max(t["nc_grid"]), 256, per_src, lg.LAGOM_LADDER_CUT)
+    assert chunks == osr.ladder_chunks(t["chunk_grid"], max(t["nc_grid"]), 256, per_src, osr.LADDER_CUT)
+    return t["nc_grid"][:6], chunks[:6]
+
+
+@pytest.mark.parametrize("which", ["calibrated", "as_printed"])
+def test_priority_against_brute_force_on_the_first_three_pairs(table, which):
+    sigmas = [i / 8 for i in range(9)] if which == "calibrated" else [0.0]
+    ml3, mo3, cal = _models(table, "d_bytes_past_l2" if which == "calibrated" else "d_bytes", sigmas)
+    nc, chunks = _ladder(table)
+    sl = [lg.Space(nc, [256], chunks) for _ in range(3)]
+    so = [osr.Space(nc, [256], chunks) for _ in range(3)]
+    oprof = lambda cfgs: (lambda p: (p.x, p.Y))(ocm.predict(mo3, cfgs))
+    res = {}
+    for name, mode, fn in [("priority", lg.LAGOM_PRIORITY, osr.priority_search), ("exhaustive", lg.LAGOM_EXHAUSTIVE, osr.brute_force),
+                           ("priority_free", lg.LAGOM_PRIORITY_FREE, lambda s, p: osr.priority_search(s, p, free_steps=True))]:
+        rl, ro = lg.lagom_tune(sl, ml3, mode), fn(so, oprof)
+        # Gates 1 and 2 on real data: the library's search is the oracle's search
+        assert rl.cfgs == ro.cfgs and rl.levels == ro.levels and rl.calls == ro.calls and (rl.X, rl.Y, rl.Z) == (ro.X, ro.Y, ro.Z)
+        res[name] = rl
+    pr, ex, fr = res["priority"], res["exhaustive"], res["priority_free"]
+    assert ex.calls == 6 ** 3 and pr.calls <= 1 + 3 * 6 and fr.calls <= 1 + 3 * 6
+    assert ex.Z <= pr.Z and ex.Z <= fr.Z                       # brute force is the lower bound
+    gap, gap_free = pr.Z / ex.Z - 1.0, fr.Z / ex.Z - 1.0
+    same = sorted(pr.cfgs) == sorted(ex.cfgs)                  # the three pairs are identical: order is immaterial
+    print(f"\n[{which}, sigma {cal.sigma}] priority {pr.cfgs} Z={pr.Z:.2f} us ({pr.calls} calls) | exhaustive {ex.cfgs} "
+          f"Z={ex.Z:.2f} us ({ex.calls} calls) | gap {100 * gap:.2f} % | same up to order: {same} | "
+          f"free steps {fr.cfgs} Z={fr.Z:.2f} us, gap {100 * gap_free:.2f} %")
+    # Gate 3 on this chain is not an identity: under the model filled from the recorded sweep the heuristic stops as soon
+    # as the communication is hidden, while the model (like the hardware it was filled from) still rewards faster
+    # communication with a shorter computation.  What holds with the calibrated model, and is asserted: it ends within
+    # 2 % of the optimum with at most 19 of 216 calls.  With the model as printed (every byte of a workgroup charged to
+    # HBM, a channel taking a whole compute unit) the predicted computation is so long that the walk stops almost at
+    # once; the gap (30 % on the recorded table) is printed, not gated.
+    if which == "calibrated":
+        assert gap <= 0.02 and gap_free <= 0.02
+    if gap == 0.0:
+        assert same

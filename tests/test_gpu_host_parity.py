@@ -56,11 +56,12 @@ def _same_trace(lib_trace, oracle_trace):
 
 NC, NT, CH = [1, 4, 16, 64], [256], [32 << 10, 128 << 10]
 MODES = [(lg.LAGOM_PRIORITY, osr.priority_search, True), (lg.LAGOM_HIDE_COMM, osr.hide_search, True),
+         (lg.LAGOM_PRIORITY_FREE, lambda sp, pr: osr.priority_search(sp, pr, free_steps=True), True),
          (lg.LAGOM_COMM_OPTIMAL, osr.coordinate_descent, False), (lg.LAGOM_EXHAUSTIVE, osr.brute_force, False),
          (lg.LAGOM_EXHAUSTIVE_HIDE, osr.brute_force_hide, False)]
 
 
-@pytest.mark.parametrize("mode,oracle_fn,has_trace", MODES, ids=["priority", "hide_comm", "comm_optimal", "exhaustive", "exhaustive_hide"])
+@pytest.mark.parametrize("mode,oracle_fn,has_trace", MODES, ids=["priority", "hide_comm", "priority_free", "comm_optimal", "exhaustive", "exhaustive_hide"])
 def test_measured_search_replayed_through_the_oracle(chain, mode, oracle_fn, has_trace):
     sl = [lg.Space(NC, NT, CH) for _ in range(chain["ncomm"])]
     so = [osr.Space(NC, NT, CH) for _ in range(chain["ncomm"])]

@@ -357,7 +357,34 @@ def test_hide_modes_equal_oracle_result_and_trace(golden_dir):
         b = lg.lagom_tune(sl, profile, lg.LAGOM_EXHAUSTIVE_HIDE)
         assert b.levels == case["brute_levels"] and b.Y == case["brute_Y"]
     with pytest.raises(lg.LagomError):
-        lg.lagom_tune([lg.Space([1], [64], [16])], lambda c: ([1.0], 1.0), 5)
+        lg.lagom_tune([lg.Space([1], [64], [16])], lambda c: ([1.0], 1.0), 6)
+
+
+def test_free_steps_mode_equals_oracle_result_and_trace(golden_dir):
+    rng = np.random.default_rng(59)
+    differs = 0
+    for _ in range(300):
+        N = int(rng.integers(1, 9))
+        so, sl, profile = _random_chain(rng, N)
+        falling = rng.uniform(0.0, 2.0, size=N)
+
+        def prof(cfgs):                                   # a computation that gets faster as channels are added
+            x, Y = profile(cfgs)
+            return x, Y - sum(float(falling[j]) * c[0] for j, c in enumerate(cfgs)) + 200.0
+        ro = osr.priority_search(so, prof, free_steps=True)
+        rl = lg.lagom_tune(sl, prof, lg.LAGOM_PRIORITY_FREE)
+        assert rl.cfgs == ro.cfgs and rl.levels == ro.levels and rl.calls == ro.calls and (rl.X, rl.Y, rl.Z) == (ro.X, ro.Y, ro.Z)
+        _same_trace(rl.trace, ro.trace)
+        differs += ro.levels != osr.priority_search(so, prof).levels
+    assert differs > 20                                   # the variant was exercised where it departs from the printed algorithm
+    case = json.load(open(os.path.join(golden_dir, "search_worked.json")))["free_steps_cases"][0]
+    xs, Ys = case["x_by_level"], case["Y_by_level"]
+    prof = lambda cfgs: ([xs[0][int(math.log2(cfgs[0][0]))]], Ys[int(math.log2(cfgs[0][0]))])
+    sl = [lg.Space(**sp) for sp in case["spaces"]]
+    r = lg.lagom_tune(sl, prof, lg.LAGOM_PRIORITY_FREE)
+    assert r.levels == case["final_levels"] and r.Z == case["final_Z"] and r.calls == case["calls"]
+    lit = lg.lagom_tune(sl, prof, lg.LAGOM_PRIORITY)
+    assert lit.levels == case["literal"]["final_levels"] and lit.calls == case["literal"]["calls"]
 
 
 def _sweep_points(rng, cfgs):

@@ -307,3 +307,40 @@ def test_ladder_chunks():
     assert os_.ladder_chunks(grid, 32, 256, 0, os_.LADDER_FIXED_CHUNK, alone) == [131072]   # first of the two smallest
     with pytest.raises(ValueError):
         os_.ladder_chunks(grid, 64, 256, 0, os_.LADDER_FIXED_CHUNK, alone)
+
+
+def test_free_steps_hand_worked_trace_and_properties(golden_dir):
+    fx = json.load(open(os.path.join(golden_dir, "search_worked.json")))
+    for case in fx["free_steps_cases"]:
+        spaces = [os_.Space(**sp) for sp in case["spaces"]]
+        xs, Ys = case["x_by_level"], case["Y_by_level"]
+        prof = lambda cfgs: ([xs[0][int(math.log2(cfgs[0][0]))]], Ys[int(math.log2(cfgs[0][0]))])
+        lit = os_.priority_search(spaces, prof)
+        assert (lit.levels, lit.Z, lit.calls) == (case["literal"]["final_levels"], case["literal"]["final_Z"], case["literal"]["calls"])
+        res = os_.priority_search(spaces, prof, free_steps=True)
+        assert res.levels == case["final_levels"] and res.Z == case["final_Z"] and res.calls == case["calls"]
+        for got, want in zip(res.trace, case["trace"]):
+            assert (got.comm, got.level_from, got.level_to, got.accepted, got.done) == \
+                (want["comm"], want["from"], want["to"], want["accepted"], want["done"])
+            assert (got.X, got.Y, got.Z) == (want["X"], want["Y"], want["Z"])
+            if "H" in want:
+                assert got.H == pytest.approx(want["H"], rel=1e-15)
+        bf = os_.brute_force(spaces, prof)
+        assert bf.levels == case["brute_levels"] and bf.Z == case["brute_Z"]
+    # Where the paper's premise holds (Y never falls when a communication is raised) no step is free and the two searches
+    # are the same search, trace included; in general free steps never end at a larger makespan on one communication.
+    rng = np.random.default_rng(99)
+    for trial in range(300):
+        N, K = int(rng.integers(1, 5)), int(rng.integers(2, 6))
+        spaces = [_ladder(K) for _ in range(N)]
+        profile = _chain_profile(rng, N, K)                       # Y = y0 + sum(pen_j * level_j), pen >= 0
+        a, b = os_.priority_search(spaces, profile), os_.priority_search(spaces, profile, free_steps=True)
+        assert a.levels == b.levels and a.calls == b.calls and [s.__dict__ for s in a.trace][1:] == [s.__dict__ for s in b.trace][1:]
+    for trial in range(300):
+        K = int(rng.integers(2, 9))
+        x, _ = _random_unimodal_case(rng, K)
+        Y = [float(v) for v in rng.uniform(50, 150) + np.cumsum(rng.uniform(-8.0, 4.0, size=K))]     # Y mostly falls
+        sp = _ladder(K)
+        prof = lambda cfgs: ([x[int(math.log2(cfgs[0][0]))]], Y[int(math.log2(cfgs[0][0]))])
+        a, b = os_.priority_search([sp], prof), os_.priority_search([sp], prof, free_steps=True)
+        assert b.Z <= a.Z and b.calls <= 1 + K
