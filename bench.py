@@ -49,8 +49,11 @@ def _up(x):
     return torch.from_numpy(x.view(np.int16) if x.dtype == np.uint16 else x).cuda()
 
 
-def build_workload(name: str, dependent: bool = False):
-    """Device buffers + launch descriptors of one synthetic overlap group."""
+def build_workload(name: str, dependent: bool = False, fused: bool = True):
+    """Device buffers + launch descriptors of one synthetic overlap group.  fused: the fourteen ring steps of the DP
+    bucket's all-reduce share are issued as one kernel launch (lagom_comm_steps), the way a collective library runs a
+    ring.  The back-to-back reduce-copies of the compute-bound workload are separate operators and stay separate
+    launches (measured: persistent channels there cost the GEMM more than the launch boundaries cost the communication)."""
     import torch
     from paper_2602_20656_amd import binding as lg, inputs
     w = inputs.WORKLOADS[name]
@@ -142,6 +145,9 @@ def build_workload(name: str, dependent: bool = False):
         comm_after_comp = [-1] * ncomm
         for l in launches:
             comm_after_comp[l.comm_id] = max(comm_after_comp[l.comm_id], l.after_comp)
+    if fused and name == "dp_bucket":
+        for i in range(1, len(launches)):
+            launches[i].fuse = True
     torch.cuda.synchronize()           # uploads ran on torch's stream; the library launches on its own streams
     return w, launches, comps, ncomm, keep, (comp_after_comm, comm_after_comp)
 
@@ -326,7 +332,7 @@ def run_config(name, args, s_comm, s_comp, dependent=False):
         r = lg.lagom_tune(sp, p, mode)
         d = {"cfgs": [list(c) for c in r.cfgs], "calls": r.calls, "seconds": time.perf_counter() - t0,
              "z_search_us": r.Z, "x_search_us": r.X, "y_search_us": r.Y}
-        if mode in (lg.LAGOM_PRIORITY, lg.LAGOM_HIDE_COMM):
+        if mode in (lg.LAGOM_PRIORITY, lg.LAGOM_HIDE_COMM, lg.LAGOM_PRIORITY_FREE):
             d.update(stop_test_audit(r, p.log))
             d["median_rel_spread_x"] = float(np.median([m / max(x, 1e-9) for e in p.log for m, x in zip(e["x_mad"], e["x"])]))
             d["median_rel_spread_Y"] = float(np.median([e["Y_mad"] / max(e["Y"], 1e-9) for e in p.log]))
@@ -339,7 +345,9 @@ def run_config(name, args, s_comm, s_comp, dependent=False):
     tuned_fixed, searches["priority_fixed_chunk"], logs["priority_fixed_chunk"] = search(spaces_fixed, lg.LAGOM_PRIORITY, "fixed")
     comm_cd, searches["comm_descent"], _ = search(spaces, lg.LAGOM_COMM_OPTIMAL, "descent")
     hide, searches["hide_comm"], logs["hide_comm"] = search(spaces_fixed, lg.LAGOM_HIDE_COMM, "hide")
+    tuned_free, searches["priority_free_steps"], logs["priority_free_steps"] = search(spaces_fixed, lg.LAGOM_PRIORITY_FREE, "free")
     tuned_ext, searches["priority_extended"], logs["priority_extended"] = search(spaces_ext, lg.LAGOM_PRIORITY, "ext")
+    tuned_free_ext, searches["priority_free_steps_extended"], logs["priority_free_steps_extended"] = search(spaces_ext, lg.LAGOM_PRIORITY_FREE, "free-ext")
     hide_ext, searches["hide_comm_extended"], _ = search(spaces_ext, lg.LAGOM_HIDE_COMM, "hide-ext")
     # brute force over the extended ladder: every level vector for one communication, the uniform vectors otherwise
     ext_ladder = ladder_cfgs(spaces_ext[0])
@@ -396,20 +404,30 @@ def run_config(name, args, s_comm, s_comp, dependent=False):
     cands = {"default": [DEFAULT_CFG] * ncomm, "tuned": tuned.cfgs, "tuned_uncut_ladder": tuned_full.cfgs,
              "tuned_fixed_chunk": tuned_fixed.cfgs, "comm_descent": comm_cd.cfgs, "hide_comm": hide.cfgs,
              "best_swept": [best_sweep.cfg] * ncomm, "comm_optimal": [comm_opt.cfg] * ncomm,
-             "tuned_extended": tuned_ext.cfgs, "hide_comm_extended": hide_ext.cfgs, "best_swept_extended": [best_sweep_ext.cfg] * ncomm}
+             "tuned_free_steps": tuned_free.cfgs,
+             "tuned_extended": tuned_ext.cfgs, "tuned_free_steps_extended": tuned_free_ext.cfgs,
+             "hide_comm_extended": hide_ext.cfgs, "best_swept_extended": [best_sweep_ext.cfg] * ncomm}
     if brute_ext is not None:
         cands["exhaustive_extended"] = brute_ext.cfgs
         cands["exhaustive_hide_extended"] = brute_hide_ext.cfgs
     if tuned_model is not None:
         cands["model_tuned"] = tuned_model.cfgs
         cands["printed_model_tuned"] = tuned_printed.cfgs
+    # the same parameters with every launch of a communication issued on its own (no lagom_comm_steps)
+    separate = None
+    if any(l.fuse for l in launches):
+        separate = [lg.CommLaunch(l.op, l.dtype, l.srcs, l.dsts, l.count, l.comm_id, l.after_comp, False) for l in launches]
+        cands["default_separate_launches"] = cands["default"]
+        cands["tuned_separate_launches"] = tuned.cfgs
+        cands["tuned_extended_separate_launches"] = tuned_ext.cfgs
+    which_launches = lambda k: separate if k.endswith("_separate_launches") else launches
     meas = {k: [] for k in cands}
     order = list(cands)
     y_alone_rounds = []
     for r in range(args.rounds):
         y_alone_rounds.append(lg.lagom_overlap_run(launches, cands["default"], comps, s_comm, s_comp, 2, args.steps, lg.LAGOM_ALONE_COMP))
         for k in order[r % len(order):] + order[:r % len(order)]:
-            meas[k].append(lg.lagom_overlap_run(launches, cands[k], comps, s_comm, s_comp, 2, args.steps, lg.LAGOM_CORUN))
+            meas[k].append(lg.lagom_overlap_run(which_launches(k), cands[k], comps, s_comm, s_comp, 2, args.steps, lg.LAGOM_CORUN))
     y_alone_sum = float(np.median([sum(t.y_us) for t in y_alone_rounds]))
     gemm_us = y_alone_sum / len(comps)
 
@@ -448,7 +466,10 @@ def run_config(name, args, s_comm, s_comp, dependent=False):
         "speedup_tuned_vs_default": results["tuned"]["speedup_vs_default"], "verdict": results["tuned"]["verdict"],
         "z_default_us": results["default"]["z_us"], "z_tuned_us": results["tuned"]["z_us"],
         "z_comm_descent_us": results["comm_descent"]["z_us"], "z_best_swept_us": results["best_swept"]["z_us"],
-        "z_tuned_extended_us": results["tuned_extended"]["z_us"], "z_best_swept_extended_us": results["best_swept_extended"]["z_us"],
+        "z_tuned_free_steps_us": results["tuned_free_steps"]["z_us"],
+        "z_tuned_extended_us": results["tuned_extended"]["z_us"], "z_tuned_free_steps_extended_us": results["tuned_free_steps_extended"]["z_us"],
+        "z_best_swept_extended_us": results["best_swept_extended"]["z_us"],
+        "launches_fused": any(l.fuse for l in launches),
         "gemm_alone_us": gemm_us, "gemm_mfma_util": tflops / BF16_PEAK_TFLOPS,
         "comm_alone_fastest_us": fastest.comm_alone_us, "comm_alone_fastest_cfg": list(fastest.cfg),
         "comm_alone_fastest_gbps": sum(nbytes) / fastest.comm_alone_us / 1e3,
@@ -489,6 +510,8 @@ def run_config(name, args, s_comm, s_comp, dependent=False):
                        "ncomp": len(comps), "bytes_per_comm": bytes_per_comm, "per_src_bytes": per_src,
                        "sweep": [p.__dict__ for p in sweep], "sweep_extended": [p.__dict__ for p in sweep_ext],
                        "traces": {"priority": [s.__dict__ for s in tuned.trace], "priority_extended": [s.__dict__ for s in tuned_ext.trace],
+                                  "priority_free_steps": [s.__dict__ for s in tuned_free.trace],
+                                  "priority_free_steps_extended": [s.__dict__ for s in tuned_free_ext.trace],
                                   "hide_comm": [s.__dict__ for s in hide.trace]},
                        "logs": logs}, f, indent=1, default=str)
     del keep

@@ -30,6 +30,8 @@ extern "C" {
 #define LAGOM_MAX_DSTS      4
 #define LAGOM_MAX_LAUNCHES 256  /* kernel launches per stream in one overlap group        */
 #define LAGOM_MAX_COMMS    64   /* tunable communications in one overlap group            */
+#define LAGOM_MAX_STEPS    32   /* local steps in one lagom_comm_steps launch             */
+#define LAGOM_MAX_STEP_PTRS 96  /* sources and destinations of all its steps together     */
 
 /* The three resource-related parameters of a communication (Sec. 2.2 and Sec. 3.2):
  * number of channels NC (= workgroups), threads per block NT, chunk size C in bytes. */
@@ -75,6 +77,36 @@ int lagom_comm_kernel(lagom_op op, lagom_dtype dt,
                       const void* const* srcs, int nsrc,
                       void* const* dsts, int ndst,
                       int64_t count, const lagom_cfg* cfg, void* hip_stream);
+
+/* ---------------------------------------------------------------------------------
+ * lagom_comm_steps -- several local steps of ONE collective in one kernel launch (Sec. 2.1: a ring
+ * all-reduce is P-1 reduce steps followed by P-1 copy steps; Sec. 3.2: the collective's NC thread
+ * blocks stay for the whole operator).  The cfg->nc channels are persistent: every channel walks
+ * the steps in order and takes chunks k, k+nc, ... of each, with no synchronisation between
+ * channels, exactly as nsteps calls of lagom_comm_kernel would assign them, without the nsteps-1
+ * launch boundaries in between.
+ *
+ *   steps[nsteps] : host array; step i is a reduce-copy of nsrc sources into ndst destinations, or
+ *                   a gather-copy of ONE source (a plain copy, e.g. store-and-forward) into ndst
+ *                   destinations.  Every buffer of every step holds `count` elements of dt, so a given
+ *                   element is moved by the same lane in every step.
+ *   Ordering      : a location that one step writes and a later step reads or overwrites THROUGH
+ *                   THE SAME POINTER is handled in step order (same lane, program order).  Buffers
+ *                   of different steps that overlap only in part are refused (LAGOM_EINVAL).
+ *   nsteps 1..LAGOM_MAX_STEPS, at most LAGOM_MAX_STEP_PTRS buffers in all steps together;
+ *   pointers 16-byte aligned; cfg as for lagom_comm_kernel.  Enqueue only.
+ * The result equals that of the nsteps separate launches in order, bit for bit.
+ * Errors: LAGOM_EINVAL, LAGOM_EALIGN, LAGOM_EHIP.
+ */
+typedef struct {
+    int32_t op;                 /* lagom_op                                             */
+    const void* const* srcs;    /* host array of device pointers                        */
+    int32_t nsrc;
+    void* const* dsts;          /* host array of device pointers                        */
+    int32_t ndst;
+} lagom_comm_step;
+int lagom_comm_steps(lagom_dtype dt, const lagom_comm_step* steps, int nsteps, int64_t count,
+                     const lagom_cfg* cfg, void* hip_stream);
 
 /* ---------------------------------------------------------------------------------
  * lagom_gemm -- the computation whose slow-down under contention is studied
@@ -125,6 +157,10 @@ typedef struct {
                                    index into cfgs; launches of one id are contiguous  */
     int32_t after_comp;         /* index of a computation that must have finished before this
                                    launch starts, or -1 (honoured in LAGOM_CORUN only)  */
+    int32_t fuse_with_prev;     /* non-zero: issue this launch in the same kernel launch as the
+                                   previous one (lagom_comm_steps).  Needs the same comm_id, dtype
+                                   and count as the previous launch, after_comp == -1, and the
+                                   shape rules of lagom_comm_steps; otherwise LAGOM_EINVAL      */
 } lagom_comm_desc;
 
 typedef struct {

@@ -224,3 +224,24 @@ def ring_all_reduce(buckets, dtype: str):
             new_out.append(incoming[r])
         outgoing = new_out
     return data
+
+
+def comm_steps(buffers: dict, steps, dtype: str) -> dict:
+    """Several local steps of one collective, one after the other (Sec. 2.1: a ring all-reduce share is P-1 reduce
+    steps followed by P-1 copy steps).  `buffers` maps a name to an array; `steps` is a list of
+    (op, source names, destination names) with op "reduce_copy" or "gather_copy" (one source: store and forward).
+    Every step is the plain definition above applied to the current contents; a step sees what earlier steps wrote.
+    Returns the final contents (the input dict is not modified)."""
+    state = {k: np.array(v, copy=True) for k, v in buffers.items()}
+    for op, srcs, dsts in steps:
+        if op == "reduce_copy":
+            out = reduce_copy([state[s] for s in srcs], dtype, 1)[0]
+        elif op == "gather_copy":
+            if len(srcs) != 1:
+                raise ValueError("a copy step forwards one source")
+            out = state[srcs[0]].copy()
+        else:
+            raise ValueError("unknown step")
+        for d in dsts:
+            state[d] = out.copy()
+    return state

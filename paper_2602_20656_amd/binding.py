@@ -26,11 +26,12 @@ LAGOM_ALONE_COMM, LAGOM_ALONE_COMP, LAGOM_CORUN = 0, 1, 2
 LAGOM_PRIORITY, LAGOM_EXHAUSTIVE, LAGOM_COMM_OPTIMAL, LAGOM_HIDE_COMM, LAGOM_EXHAUSTIVE_HIDE, LAGOM_PRIORITY_FREE = 0, 1, 2, 3, 4, 5
 LAGOM_LADDER_FULL, LAGOM_LADDER_CUT, LAGOM_LADDER_FIXED_CHUNK = 0, 1, 2
 LAGOM_MAX_SRCS, LAGOM_MAX_DSTS, LAGOM_MAX_LAUNCHES, LAGOM_MAX_COMMS = 16, 4, 256, 64
+LAGOM_MAX_STEPS, LAGOM_MAX_STEP_PTRS = 32, 96
 
 EXPORTS = ["lagom_strerror", "lagom_last_error", "lagom_comm_kernel", "lagom_gemm", "lagom_gemm_describe",
            "lagom_overlap_run", "lagom_contention_sweep", "lagom_comm_bytes", "lagom_cost_model", "lagom_tune",
            "lagom_model_profile", "lagom_overlap_profile", "lagom_streams_overlap", "lagom_overlap_steps", "lagom_overlap_steps_graph",
-           "lagom_model_fill", "lagom_model_calibrate", "lagom_ladder_chunks"]
+           "lagom_model_fill", "lagom_model_calibrate", "lagom_ladder_chunks", "lagom_comm_steps"]
 
 
 class LagomError(RuntimeError):
@@ -53,7 +54,12 @@ class lagom_gemm_geometry(C.Structure):
 class lagom_comm_desc(C.Structure):
     _fields_ = [("op", C.c_int32), ("dtype", C.c_int32), ("srcs", C.POINTER(C.c_void_p)), ("nsrc", C.c_int32),
                 ("dsts", C.POINTER(C.c_void_p)), ("ndst", C.c_int32), ("count", C.c_int64), ("comm_id", C.c_int32),
-                ("after_comp", C.c_int32)]
+                ("after_comp", C.c_int32), ("fuse_with_prev", C.c_int32)]
+
+
+class lagom_comm_step(C.Structure):
+    _fields_ = [("op", C.c_int32), ("srcs", C.POINTER(C.c_void_p)), ("nsrc", C.c_int32),
+                ("dsts", C.POINTER(C.c_void_p)), ("ndst", C.c_int32)]
 
 
 class lagom_gemm_desc(C.Structure):
@@ -160,6 +166,7 @@ def lib() -> C.CDLL:
         L.lagom_last_error.restype = C.c_char_p
         L.lagom_comm_kernel.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_void_p), C.c_int, C.POINTER(C.c_void_p), C.c_int,
                                         C.c_int64, C.POINTER(lagom_cfg), C.c_void_p]
+        L.lagom_comm_steps.argtypes = [C.c_int, C.POINTER(lagom_comm_step), C.c_int, C.c_int64, C.POINTER(lagom_cfg), C.c_void_p]
         L.lagom_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_void_p]
         L.lagom_gemm_describe.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.c_int, C.POINTER(lagom_gemm_geometry)]
         L.lagom_overlap_run.argtypes = [C.POINTER(lagom_comm_desc), C.c_int, C.POINTER(lagom_cfg), C.c_int,
@@ -235,6 +242,18 @@ def lagom_comm_kernel(op: int, dt: int, srcs, dsts, count: int, cfg: CfgLike, st
                                    int(count), C.byref(c), _stream(stream)))
 
 
+def lagom_comm_steps(dt: int, steps: Sequence[Tuple[int, Sequence, Sequence]], count: int, cfg: CfgLike, stream=None) -> None:
+    """steps: (op, srcs, dsts) per local step, all of `count` elements of dt; one kernel launch for all of them."""
+    c = _cfg(cfg)
+    arr = (lagom_comm_step * max(len(steps), 1))()
+    keep = []
+    for i, (op, srcs, dsts) in enumerate(steps):
+        a, b = _ptr_array(srcs), _ptr_array(dsts)
+        keep += [a, b]
+        arr[i] = lagom_comm_step(int(op), C.cast(a, C.POINTER(C.c_void_p)), len(srcs), C.cast(b, C.POINTER(C.c_void_p)), len(dsts))
+    _check(lib().lagom_comm_steps(dt, arr, len(steps), int(count), C.byref(c), _stream(stream)))
+
+
 def lagom_gemm(A, B, Cmat, M: int, N: int, K: int, b_is_nk: bool = True, out_dt: int = LAGOM_BF16, stream=None) -> None:
     _check(lib().lagom_gemm(_ptr(A), _ptr(B), _ptr(Cmat), int(M), int(N), int(K), 1 if b_is_nk else 0, out_dt, _stream(stream)))
 
@@ -258,6 +277,7 @@ class CommLaunch:
     count: int
     comm_id: int = 0
     after_comp: int = -1        # computation that must have finished before this launch starts
+    fuse: bool = False          # issue in the same kernel launch as the previous launch of this communication
 
 
 @dataclass
@@ -298,7 +318,7 @@ class _Group:
             self.keep += [s, d]
             self.L[i] = lagom_comm_desc(l.op, l.dtype, C.cast(s, C.POINTER(C.c_void_p)), len(l.srcs),
                                         C.cast(d, C.POINTER(C.c_void_p)), len(l.dsts), int(l.count), int(l.comm_id),
-                                        int(l.after_comp))
+                                        int(l.after_comp), 1 if l.fuse else 0)
         self.G = (lagom_gemm_desc * max(self.ncomp, 1))()
         for i, g in enumerate(comps):
             self.G[i] = lagom_gemm_desc(_ptr(g.A), _ptr(g.B), _ptr(g.C), int(g.M), int(g.N), int(g.K),

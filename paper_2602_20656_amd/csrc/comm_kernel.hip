@@ -91,72 +91,101 @@ struct Acc<LAGOM_BF16> {
 };
 
 // One element of a short tail (fewer than 16 bytes left at the end of the buffer).
-template <int DT>
-__device__ __forceinline__ void reduce_tail_element(const CommArgs& p, int64_t byte_off) {
+template <int DT, class SRC, class DST>
+__device__ __forceinline__ void reduce_tail_element(const SRC& src, const DST& dst, int nsrc, int ndst, int64_t byte_off) {
     if (DT == LAGOM_F32) {
-        float acc = *reinterpret_cast<const float*>(p.src[0] + byte_off);
-        for (int s = 1; s < p.nsrc; ++s) acc = acc + *reinterpret_cast<const float*>(p.src[s] + byte_off);
-        for (int d = 0; d < p.ndst; ++d) *reinterpret_cast<float*>(p.dst[d] + byte_off) = acc;
+        float acc = *reinterpret_cast<const float*>(src(0) + byte_off);
+        for (int s = 1; s < nsrc; ++s) acc = acc + *reinterpret_cast<const float*>(src(s) + byte_off);
+        for (int d = 0; d < ndst; ++d) *reinterpret_cast<float*>(dst(d) + byte_off) = acc;
     } else {
-        float acc = bf16_lo(*reinterpret_cast<const uint16_t*>(p.src[0] + byte_off));
-        for (int s = 1; s < p.nsrc; ++s) acc = acc + bf16_lo(*reinterpret_cast<const uint16_t*>(p.src[s] + byte_off));
+        float acc = bf16_lo(*reinterpret_cast<const uint16_t*>(src(0) + byte_off));
+        for (int s = 1; s < nsrc; ++s) acc = acc + bf16_lo(*reinterpret_cast<const uint16_t*>(src(s) + byte_off));
         const uint16_t r = (uint16_t)bf16_round(acc);
-        for (int d = 0; d < p.ndst; ++d) *reinterpret_cast<uint16_t*>(p.dst[d] + byte_off) = r;
+        for (int d = 0; d < ndst; ++d) *reinterpret_cast<uint16_t*>(dst(d) + byte_off) = r;
     }
 }
 
+// One chunk [base, base + len) of a reduce-copy, moved by the nt threads of a workgroup.
 // S > 0: number of sources known at compile time (all loads of a batch issued before the
 // first add).  S == 0: any number of sources, loaded source by source.
-// U: 16-byte vectors a lane has in flight per source.
+// U: 16-byte vectors a lane has in flight per source.  src(s) / dst(d) give the buffers.
+template <int DT, int S, int U, bool STREAM, class SRC, class DST>
+__device__ __forceinline__ void reduce_chunk(const SRC& src, const DST& dst, int nsrc, int ndst, int64_t base, int64_t len, int tid, int nt) {
+    const int esize = DT == LAGOM_F32 ? 4 : 2;
+    const int64_t nvec = len >> 4;
+    int64_t v = tid;
+    if constexpr (S > 0) {
+        // full batches: U vectors per source per lane, strided by the workgroup size
+        for (; v + (int64_t)(U - 1) * nt < nvec; v += (int64_t)U * nt) {
+            u32x4 r[S][U];
+#pragma unroll
+            for (int s = 0; s < S; ++s)
+#pragma unroll
+                for (int u = 0; u < U; ++u) r[s][u] = ld16<STREAM>(src(s) + base + ((v + (int64_t)u * nt) << 4));
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                Acc<DT> acc;
+                acc.init(r[0][u]);
+#pragma unroll
+                for (int s = 1; s < S; ++s) acc.add(r[s][u]);
+                const u32x4 o = acc.result();
+                for (int d = 0; d < ndst; ++d) st16(dst(d) + base + ((v + (int64_t)u * nt) << 4), o);
+            }
+        }
+    }
+    // remaining vectors (and every vector when S == 0)
+    for (; v < nvec; v += nt) {
+        const int64_t off = base + (v << 4);
+        Acc<DT> acc;
+        acc.init(ld16<STREAM>(src(0) + off));
+        const int ns = S > 0 ? S : nsrc;
+        int s = 1;
+        for (; s + 3 < ns; s += 4) {          // four loads in flight, added in source order
+            const u32x4 x0 = ld16<STREAM>(src(s) + off), x1 = ld16<STREAM>(src(s + 1) + off);
+            const u32x4 x2 = ld16<STREAM>(src(s + 2) + off), x3 = ld16<STREAM>(src(s + 3) + off);
+            acc.add(x0); acc.add(x1); acc.add(x2); acc.add(x3);
+        }
+        for (; s < ns; ++s) acc.add(ld16<STREAM>(src(s) + off));
+        const u32x4 o = acc.result();
+        for (int d = 0; d < ndst; ++d) st16(dst(d) + off, o);
+    }
+    // fewer than 16 bytes at the very end of the buffer
+    const int tail_elems = (int)(len & 15) / esize;
+    if (tid < tail_elems) reduce_tail_element<DT>(src, dst, nsrc, ndst, base + (nvec << 4) + (int64_t)tid * esize);
+}
+
+// One chunk of a plain copy of one source to ndst destinations (bytes are moved, never interpreted).
+template <int U, bool STREAM, class DST>
+__device__ __forceinline__ void copy_chunk(const char* src, const DST& dst, int ndst, int64_t dst_off, int64_t len, int tid, int nt) {
+    const int64_t nvec = len >> 4;
+    int64_t v = tid;
+    for (; v + (int64_t)(U - 1) * nt < nvec; v += (int64_t)U * nt) {
+        u32x4 x[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) x[u] = ld16<STREAM>(src + ((v + (int64_t)u * nt) << 4));
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            for (int d = 0; d < ndst; ++d) st16(dst(d) + dst_off + ((v + (int64_t)u * nt) << 4), x[u]);
+    }
+    for (; v < nvec; v += nt) {
+        const u32x4 x = ld16<STREAM>(src + (v << 4));
+        for (int d = 0; d < ndst; ++d) st16(dst(d) + dst_off + (v << 4), x);
+    }
+    const int tail = (int)(len & 15);          // only at the very end of a buffer: bytes, copied one by one
+    if (tid < tail) {
+        const char b = src[(nvec << 4) + tid];
+        for (int d = 0; d < ndst; ++d) dst(d)[dst_off + (nvec << 4) + tid] = b;
+    }
+}
+
 template <int DT, int S, int U, bool STREAM, int MAXNT>
 __global__ void __launch_bounds__(MAXNT) reduce_copy_kernel(const CommArgs p) {
-    const int nt = blockDim.x;
-    const int tid = threadIdx.x;
-    const int esize = DT == LAGOM_F32 ? 4 : 2;
+    const auto src = [&p](int s) { return p.src[s]; };
+    const auto dst = [&p](int d) { return p.dst[d]; };
     for (int64_t g = blockIdx.x; g < p.total_chunks; g += gridDim.x) {
         const int64_t base = g * p.chunk_bytes;
         const int64_t left = p.shard_bytes - base;
-        const int64_t len = left < p.chunk_bytes ? left : p.chunk_bytes;
-        const int64_t nvec = len >> 4;
-        int64_t v = tid;
-        if constexpr (S > 0) {
-            // full batches: U vectors per source per lane, strided by the workgroup size
-            for (; v + (int64_t)(U - 1) * nt < nvec; v += (int64_t)U * nt) {
-                u32x4 r[S][U];
-#pragma unroll
-                for (int s = 0; s < S; ++s)
-#pragma unroll
-                    for (int u = 0; u < U; ++u) r[s][u] = ld16<STREAM>(p.src[s] + base + ((v + (int64_t)u * nt) << 4));
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    Acc<DT> acc;
-                    acc.init(r[0][u]);
-#pragma unroll
-                    for (int s = 1; s < S; ++s) acc.add(r[s][u]);
-                    const u32x4 o = acc.result();
-                    for (int d = 0; d < p.ndst; ++d) st16(p.dst[d] + base + ((v + (int64_t)u * nt) << 4), o);
-                }
-            }
-        }
-        // remaining vectors (and every vector when S == 0)
-        for (; v < nvec; v += nt) {
-            const int64_t off = base + (v << 4);
-            Acc<DT> acc;
-            acc.init(ld16<STREAM>(p.src[0] + off));
-            const int ns = S > 0 ? S : p.nsrc;
-            int s = 1;
-            for (; s + 3 < ns; s += 4) {          // four loads in flight, added in source order
-                const u32x4 x0 = ld16<STREAM>(p.src[s] + off), x1 = ld16<STREAM>(p.src[s + 1] + off);
-                const u32x4 x2 = ld16<STREAM>(p.src[s + 2] + off), x3 = ld16<STREAM>(p.src[s + 3] + off);
-                acc.add(x0); acc.add(x1); acc.add(x2); acc.add(x3);
-            }
-            for (; s < ns; ++s) acc.add(ld16<STREAM>(p.src[s] + off));
-            const u32x4 o = acc.result();
-            for (int d = 0; d < p.ndst; ++d) st16(p.dst[d] + off, o);
-        }
-        // fewer than 16 bytes at the very end of the buffer
-        const int tail_elems = (int)(len & 15) / esize;
-        if (tid < tail_elems) reduce_tail_element<DT>(p, base + (nvec << 4) + (int64_t)tid * esize);
+        reduce_chunk<DT, S, U, STREAM>(src, dst, p.nsrc, p.ndst, base, left < p.chunk_bytes ? left : p.chunk_bytes, threadIdx.x, blockDim.x);
     }
 }
 
@@ -164,34 +193,13 @@ __global__ void __launch_bounds__(MAXNT) reduce_copy_kernel(const CommArgs p) {
 // every shard starts 16-byte aligned in the destination.
 template <int U, bool STREAM, int MAXNT>
 __global__ void __launch_bounds__(MAXNT) gather_copy_kernel(const CommArgs p) {
-    const int nt = blockDim.x;
-    const int tid = threadIdx.x;
+    const auto dst = [&p](int d) { return p.dst[d]; };
     for (int64_t g = blockIdx.x; g < p.total_chunks; g += gridDim.x) {
         const int64_t r = g / p.chunks_per_shard;
         const int64_t base = (g - r * p.chunks_per_shard) * p.chunk_bytes;
         const int64_t left = p.shard_bytes - base;
-        const int64_t len = left < p.chunk_bytes ? left : p.chunk_bytes;
-        const int64_t nvec = len >> 4;
-        const char* src = p.src[r] + base;
-        const int64_t dst_off = r * p.shard_bytes + base;
-        int64_t v = tid;
-        for (; v + (int64_t)(U - 1) * nt < nvec; v += (int64_t)U * nt) {
-            u32x4 x[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) x[u] = ld16<STREAM>(src + ((v + (int64_t)u * nt) << 4));
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                for (int d = 0; d < p.ndst; ++d) st16(p.dst[d] + dst_off + ((v + (int64_t)u * nt) << 4), x[u]);
-        }
-        for (; v < nvec; v += nt) {
-            const u32x4 x = ld16<STREAM>(src + (v << 4));
-            for (int d = 0; d < p.ndst; ++d) st16(p.dst[d] + dst_off + (v << 4), x);
-        }
-        const int tail = (int)(len & 15);          // single shard only: bytes, copied one by one
-        if (tid < tail) {
-            const char b = src[(nvec << 4) + tid];
-            for (int d = 0; d < p.ndst; ++d) p.dst[d][dst_off + (nvec << 4) + tid] = b;
-        }
+        copy_chunk<U, STREAM>(p.src[r] + base, dst, p.ndst, r * p.shard_bytes + base, left < p.chunk_bytes ? left : p.chunk_bytes,
+                              threadIdx.x, blockDim.x);
     }
 }
 
@@ -239,6 +247,61 @@ template <bool STREAM>
 void launch_gather(const CommArgs& a, dim3 grid, dim3 block, hipStream_t st) {
     if (block.x <= 512) hipLaunchKernelGGL((gather_copy_kernel<4, STREAM, 512>), grid, block, 0, st, a);
     else hipLaunchKernelGGL((gather_copy_kernel<4, STREAM, 1024>), grid, block, 0, st, a);
+}
+
+// Several local steps of one collective in one launch: the channels are persistent and every channel walks the steps in
+// order, taking chunks k, k+NC, ... of each (how a ring collective runs inside a collective library: one kernel whose
+// channels loop over the ring steps).  Every buffer of every step holds the same number of bytes, so a given byte offset
+// is always moved by the same lane of the same channel: a location that one step writes and a later step reads or
+// overwrites through the same pointer is ordered by that lane's program order.  There is no synchronisation between
+// channels.
+constexpr int kMaxSteps = LAGOM_MAX_STEPS;
+constexpr int kMaxStepPtrs = LAGOM_MAX_STEP_PTRS;
+struct StepsArgs {
+    const char* ptr[kMaxStepPtrs];    // per step: its sources, then its destinations
+    uint16_t first[kMaxSteps];
+    uint8_t nsrc[kMaxSteps], ndst[kMaxSteps], op[kMaxSteps];
+    int32_t nsteps;
+    int64_t bytes;                    // per buffer
+    int64_t chunk_bytes, total_chunks;
+};
+
+template <int DT, int S, int U, bool STREAM>
+__device__ __forceinline__ void reduce_step(const StepsArgs& p, int first, int nsrc, int ndst) {
+    const auto src = [&p, first](int s) { return p.ptr[first + s]; };
+    const auto dst = [&p, first, nsrc](int d) { return const_cast<char*>(p.ptr[first + nsrc + d]); };
+    for (int64_t g = blockIdx.x; g < p.total_chunks; g += gridDim.x) {
+        const int64_t base = g * p.chunk_bytes;
+        const int64_t left = p.bytes - base;
+        reduce_chunk<DT, S, U, STREAM>(src, dst, nsrc, ndst, base, left < p.chunk_bytes ? left : p.chunk_bytes, threadIdx.x, blockDim.x);
+    }
+}
+
+template <int DT, bool STREAM, int MAXNT>
+__global__ void __launch_bounds__(MAXNT) comm_steps_kernel(const StepsArgs p) {
+    for (int st = 0; st < p.nsteps; ++st) {
+        const int first = p.first[st], nsrc = p.nsrc[st], ndst = p.ndst[st];
+        if (p.op[st] == LAGOM_GATHER_COPY) {        // one source: a plain copy to every destination
+            const auto dst = [&p, first](int d) { return const_cast<char*>(p.ptr[first + 1 + d]); };
+            for (int64_t g = blockIdx.x; g < p.total_chunks; g += gridDim.x) {
+                const int64_t base = g * p.chunk_bytes;
+                const int64_t left = p.bytes - base;
+                copy_chunk<4, STREAM>(p.ptr[first] + base, dst, ndst, base, left < p.chunk_bytes ? left : p.chunk_bytes, threadIdx.x, blockDim.x);
+            }
+        } else if (nsrc == 1) {
+            reduce_step<DT, 1, 4, STREAM>(p, first, nsrc, ndst);
+        } else if (nsrc == 2) {
+            reduce_step<DT, 2, 4, STREAM>(p, first, nsrc, ndst);
+        } else {
+            reduce_step<DT, 0, 1, STREAM>(p, first, nsrc, ndst);
+        }
+    }
+}
+
+template <int DT, bool STREAM>
+void launch_steps(const StepsArgs& a, dim3 grid, dim3 block, hipStream_t st) {
+    if (block.x <= 512) hipLaunchKernelGGL((comm_steps_kernel<DT, STREAM, 512>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((comm_steps_kernel<DT, STREAM, 1024>), grid, block, 0, st, a);
 }
 
 }  // namespace
@@ -311,5 +374,67 @@ extern "C" int lagom_comm_kernel(lagom_op op, lagom_dtype dt, const void* const*
     }
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return lagom::fail(LAGOM_EHIP, "comm kernel launch: %s", hipGetErrorString(e));
+    return LAGOM_OK;
+}
+
+namespace lagom {
+
+// Shape rules of lagom_comm_steps; also used by the overlap runner before it fuses launches.
+int check_comm_steps(int dtype, const lagom_comm_step* steps, int nsteps, int64_t count) {
+    if (elem_size(dtype) == 0) return fail(LAGOM_EINVAL, "unknown dtype %d", dtype);
+    if (!steps || nsteps < 1 || nsteps > LAGOM_MAX_STEPS) return fail(LAGOM_EINVAL, "nsteps=%d outside 1..%d", nsteps, LAGOM_MAX_STEPS);
+    if (count < 0 || count > (int64_t)1 << 40) return fail(LAGOM_EINVAL, "count=%lld out of range", (long long)count);
+    int nptr = 0;
+    for (int i = 0; i < nsteps; ++i) {
+        const lagom_comm_step& s = steps[i];
+        if (int rc = check_comm_args(s.op, dtype, s.srcs, s.nsrc, s.dsts, s.ndst, count)) return rc;
+        if (s.op == LAGOM_GATHER_COPY && s.nsrc != 1)
+            return fail(LAGOM_EINVAL, "step %d: a gather-copy step of a fused launch forwards one source (every buffer of every step holds `count` elements)", i);
+        nptr += s.nsrc + s.ndst;
+    }
+    if (nptr > LAGOM_MAX_STEP_PTRS) return fail(LAGOM_EINVAL, "%d buffers in all steps together, at most %d", nptr, LAGOM_MAX_STEP_PTRS);
+    // two steps may touch the same memory only through the same pointer (then the same lane moves it in both);
+    // buffers that overlap in part would be moved by different lanes with nothing ordering them
+    const int64_t bytes = count * elem_size(dtype);
+    for (int i = 0; i < nsteps; ++i)
+        for (int j = i + 1; j < nsteps; ++j) {
+            const lagom_comm_step &a = steps[i], &b = steps[j];
+            for (int x = 0; x < a.nsrc + a.ndst; ++x)
+                for (int y = 0; y < b.nsrc + b.ndst; ++y) {
+                    if (x < a.nsrc && y < b.nsrc) continue;        // both only read
+                    const uintptr_t pa = (uintptr_t)(x < a.nsrc ? a.srcs[x] : a.dsts[x - a.nsrc]);
+                    const uintptr_t pb = (uintptr_t)(y < b.nsrc ? b.srcs[y] : b.dsts[y - b.nsrc]);
+                    if (pa != pb && pa < pb + (uintptr_t)bytes && pb < pa + (uintptr_t)bytes)
+                        return fail(LAGOM_EINVAL, "steps %d and %d touch buffers that overlap in part", i, j);
+                }
+        }
+    return LAGOM_OK;
+}
+
+}  // namespace lagom
+
+extern "C" int lagom_comm_steps(lagom_dtype dt, const lagom_comm_step* steps, int nsteps, int64_t count,
+                                const lagom_cfg* cfg, void* hip_stream) {
+    if (int rc = lagom::check_comm_steps(dt, steps, nsteps, count)) return rc;
+    if (int rc = lagom::check_cfg(cfg)) return rc;
+    if (count == 0) return LAGOM_OK;
+    StepsArgs a{};
+    int n = 0;
+    for (int i = 0; i < nsteps; ++i) {
+        a.first[i] = (uint16_t)n; a.nsrc[i] = (uint8_t)steps[i].nsrc; a.ndst[i] = (uint8_t)steps[i].ndst; a.op[i] = (uint8_t)steps[i].op;
+        for (int s = 0; s < steps[i].nsrc; ++s) a.ptr[n++] = static_cast<const char*>(steps[i].srcs[s]);
+        for (int d = 0; d < steps[i].ndst; ++d) a.ptr[n++] = static_cast<const char*>(steps[i].dsts[d]);
+    }
+    a.nsteps = nsteps;
+    a.bytes = count * lagom::elem_size(dt);
+    a.chunk_bytes = cfg->chunk_bytes;
+    a.total_chunks = (a.bytes + a.chunk_bytes - 1) / a.chunk_bytes;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const dim3 grid((unsigned)cfg->nc), block((unsigned)cfg->nt);
+    const bool stream = cfg->nc >= kStreamLoadsFromNC;
+    if (dt == LAGOM_F32) stream ? launch_steps<LAGOM_F32, true>(a, grid, block, st) : launch_steps<LAGOM_F32, false>(a, grid, block, st);
+    else stream ? launch_steps<LAGOM_BF16, true>(a, grid, block, st) : launch_steps<LAGOM_BF16, false>(a, grid, block, st);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return lagom::fail(LAGOM_EHIP, "comm steps launch: %s", hipGetErrorString(e));
     return LAGOM_OK;
 }

@@ -15,6 +15,7 @@ inline int elem_size(int dtype) { return dtype == LAGOM_F32 ? 4 : (dtype == LAGO
 int check_cfg(const lagom_cfg* cfg);
 int check_comm_args(int op, int dtype, const void* const* srcs, int nsrc, void* const* dsts, int ndst,
                     int64_t count);
+int check_comm_steps(int dtype, const lagom_comm_step* steps, int nsteps, int64_t count);
 int check_gemm_args(const void* A, const void* B, const void* C, int64_t M, int64_t N, int64_t K, int out_dt);
 
 }  // namespace lagom

@@ -92,6 +92,21 @@ int validate(const lagom_comm_desc* L, int nlaunch, const lagom_cfg* cfgs, int n
         }
         if (d.after_comp < -1 || d.after_comp >= ncomp) return lagom::fail(LAGOM_EINVAL, "launch %d: after_comp %d outside -1..%d", i, d.after_comp, ncomp - 1);
         if (int rc = lagom::check_comm_args(d.op, d.dtype, d.srcs, d.nsrc, d.dsts, d.ndst, d.count)) return rc;
+        if (d.fuse_with_prev) {
+            if (i == 0 || L[i - 1].comm_id != d.comm_id || L[i - 1].dtype != d.dtype || L[i - 1].count != d.count || d.after_comp != -1)
+                return lagom::fail(LAGOM_EINVAL, "launch %d: fuse_with_prev needs a previous launch of the same communication, dtype and count, and no dependency of its own", i);
+        }
+    }
+    // every run of fused launches must be a valid lagom_comm_steps call
+    for (int i = 0; i < nlaunch;) {
+        int k = i + 1;
+        while (k < nlaunch && L[k].fuse_with_prev) ++k;
+        if (k - i > 1) {
+            std::vector<lagom_comm_step> steps;
+            for (int q = i; q < k; ++q) steps.push_back(lagom_comm_step{L[q].op, L[q].srcs, L[q].nsrc, L[q].dsts, L[q].ndst});
+            if (int rc = lagom::check_comm_steps(L[i].dtype, steps.data(), k - i, L[i].count)) return rc;
+        }
+        i = k;
     }
     for (int j = 0; j < ncfg; ++j)
         if (int rc = lagom::check_cfg(&cfgs[j])) return rc;
@@ -139,10 +154,21 @@ int enqueue_group(const GroupPlan& plan, const lagom_comm_desc* launches, int nl
                 const int g = plan.of[d.comm_id];
                 if (dep >= 0) HIP_TRY(hipStreamWaitEvent(sa, gb_end[dep], 0));
                 if (ga_start && li == plan.first[g]) HIP_TRY(hipEventRecord(ga_start[g], sa));
-                if (int rc = lagom_comm_kernel((lagom_op)d.op, (lagom_dtype)d.dtype, d.srcs, d.nsrc, d.dsts, d.ndst,
-                                               d.count, &cfgs[d.comm_id], sa)) return rc;
-                if (li == plan.last[g]) { HIP_TRY(hipEventRecord(ga_end[g], sa)); group_done[g] = 1; }
-                ++li;
+                int run = 1;                                   // this launch and the ones fused to it
+                while (li + run < nl && launches[li + run].fuse_with_prev) ++run;
+                if (run == 1) {
+                    if (int rc = lagom_comm_kernel((lagom_op)d.op, (lagom_dtype)d.dtype, d.srcs, d.nsrc, d.dsts, d.ndst,
+                                                   d.count, &cfgs[d.comm_id], sa)) return rc;
+                } else {
+                    lagom_comm_step steps[LAGOM_MAX_STEPS];
+                    for (int q = 0; q < run; ++q) {
+                        const lagom_comm_desc& e = launches[li + q];
+                        steps[q] = lagom_comm_step{e.op, e.srcs, e.nsrc, e.dsts, e.ndst};
+                    }
+                    if (int rc = lagom_comm_steps((lagom_dtype)d.dtype, steps, run, d.count, &cfgs[d.comm_id], sa)) return rc;
+                }
+                li += run;
+                if (li - 1 == plan.last[g]) { HIP_TRY(hipEventRecord(ga_end[g], sa)); group_done[g] = 1; }
                 progressed = true;
             }
         }

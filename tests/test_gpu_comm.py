@@ -225,3 +225,78 @@ def test_reduce_copy_onto_one_of_its_sources(dtype, which):
     for s in range(3):
         if s != which:
             assert same_bits(host(d[s], np_dt), srcs[s]), "a source that is not the destination changed"
+
+
+# ------------------------------------------------------------- several steps in one launch
+def _steps_case(dtype, count, cfg, names_steps, bufs):
+    """Runs `names_steps` over named buffers through lagom_comm_steps and returns the final contents."""
+    np_dt = np.float32 if dtype == "f32" else np.uint16
+    d = {k: dev(np.concatenate([np.full(GUARD, 7, np_dt), v, np.full(GUARD, 7, np_dt)])) for k, v in bufs.items()}
+    esz = np.dtype(np_dt).itemsize
+    ptr = {k: t.data_ptr() + GUARD * esz for k, t in d.items()}
+    steps = [(lg.LAGOM_REDUCE_COPY if op == "reduce_copy" else lg.LAGOM_GATHER_COPY, [ptr[s] for s in srcs], [ptr[x] for x in dsts])
+             for op, srcs, dsts in names_steps]
+    lg.lagom_comm_steps(lg.LAGOM_F32 if dtype == "f32" else lg.LAGOM_BF16, steps, count, cfg, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    out = {}
+    for k, t in d.items():
+        h = host(t, np_dt)
+        assert (h[:GUARD] == 7).all() and (h[GUARD + count:] == 7).all(), f"guard region of {k} clobbered"
+        out[k] = h[GUARD:GUARD + count]
+    return out
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_steps_in_one_launch_equal_the_oracle_sequence(dtype):
+    gen = (lambda s, n: inputs.uniform_f32(s, n)) if dtype == "f32" else (lambda s, n: inputs.normal_bf16(s, n))
+    for count, cfg in [(5, (1, 64, 16)), (1000003, (7, 256, 65536)), (262144 + 5, (32, 1024, 32768)), (70001, (300, 512, 4096)),
+                       (1 << 20, (128, 256, 32768))]:
+        bufs = {k: gen(300 + i, count) for i, k in enumerate("abcdefg")}
+        # an accumulation chain through one buffer (every step reads what the previous one wrote), a fan-out copy,
+        # a three-source and a five-source reduce (the general path), an overwrite of an earlier result
+        steps = [("reduce_copy", ["a", "b"], ["b"]), ("reduce_copy", ["b", "c"], ["b", "d"]), ("gather_copy", ["b"], ["e", "f"]),
+                 ("reduce_copy", ["e", "a", "c"], ["g"]), ("reduce_copy", ["g", "b"], ["b"]), ("reduce_copy", ["a", "b", "c", "d", "e"], ["f"]),
+                 ("reduce_copy", ["a"], ["c"]), ("gather_copy", ["f"], ["a"])]
+        want = oc.comm_steps(bufs, steps, dtype)
+        got = _steps_case(dtype, count, cfg, steps, bufs)
+        for k in bufs:
+            assert same_bits(got[k], want[k]), (dtype, count, cfg, k)
+
+
+def test_ring_share_as_one_launch_equals_the_separate_launches_and_the_oracle():
+    """The DP bucket's share of the ring (7 reduce steps, 7 store-and-forward steps over two wire buffers each way) as
+    one lagom_comm_steps launch: the same bits as fourteen lagom_comm_kernel launches and as the oracle's sequence."""
+    P, m = 8, 1638400
+    local = inputs.normal_bf16(10, P * m, 0.125)
+    bufs = {f"c{c}": local[c * m:(c + 1) * m] for c in range(P)}
+    bufs.update({"in0": inputs.normal_bf16(11, m, 0.125), "in1": inputs.normal_bf16(12, m, 0.125),
+                 "out0": np.zeros(m, np.uint16), "out1": np.zeros(m, np.uint16)})
+    steps = []
+    for s in range(P - 1):
+        c = (0 - s - 1) % P
+        steps.append(("reduce_copy", [f"in{s % 2}", f"c{c}"], [f"out{s % 2}"] + ([f"c{c}"] if s == P - 2 else [])))
+    for s in range(P - 1):
+        c = (0 - s) % P
+        steps.append(("gather_copy", [f"in{s % 2}"], [f"c{c}"] + ([f"out{s % 2}"] if s < P - 2 else [])))
+    want = oc.comm_steps(bufs, steps, "bf16")
+    for cfg in [(32, 256, 65536), (256, 512, 32768), (3, 1024, 1 << 20)]:
+        got = _steps_case("bf16", m, cfg, steps, bufs)
+        for k in bufs:
+            assert same_bits(got[k], want[k]), (cfg, k)
+
+
+def test_steps_launch_rejects_what_it_cannot_order():
+    t = dev(np.zeros(4096, np.float32))
+    p = t.data_ptr()
+    good = (4, 256, 4096)
+    with pytest.raises(lg.LagomError) as e:       # a two-source gather-copy is not a step
+        lg.lagom_comm_steps(lg.LAGOM_F32, [(lg.LAGOM_GATHER_COPY, [p, p + 4096], [p + 8192])], 1024, good)
+    assert e.value.code == lg.LAGOM_EINVAL
+    with pytest.raises(lg.LagomError) as e:       # step 1 writes memory that step 0 reads, shifted by 64 bytes
+        lg.lagom_comm_steps(lg.LAGOM_F32, [(lg.LAGOM_REDUCE_COPY, [p], [p + 8192]), (lg.LAGOM_REDUCE_COPY, [p + 8192], [p + 64])], 1024, good)
+    assert e.value.code == lg.LAGOM_EINVAL and "overlap in part" in str(e.value)
+    with pytest.raises(lg.LagomError):
+        lg.lagom_comm_steps(lg.LAGOM_F32, [], 1024, good)
+    with pytest.raises(lg.LagomError):
+        lg.lagom_comm_steps(lg.LAGOM_F32, [(lg.LAGOM_REDUCE_COPY, [p], [p + 8192])] * 33, 1024, good)
+    lg.lagom_comm_steps(lg.LAGOM_F32, [(lg.LAGOM_REDUCE_COPY, [p], [p + 8192])], 0, good)      # count 0: nothing is launched

@@ -225,3 +225,25 @@ def test_all_to_all_is_a_block_transpose_and_an_involution():
     # per rank it is a gather-copy whose sources start at that rank's block of every peer
     for r in range(P):
         assert np.array_equal(oc.gather_copy([b[r * m:(r + 1) * m] for b in send])[0], recv[r])
+
+
+def test_comm_steps_is_the_sequence_of_its_steps():
+    """Pins: a chain b <- a + b applied k times to integer data is b + k*a exactly; the emulated ring share written as a
+    list of steps gives the all-reduce of oracle.ring_all_reduce on the owning rank's buffers; inputs are not modified."""
+    rng = np.random.default_rng(1)
+    a = rng.integers(-50, 50, size=1000).astype(np.float32)
+    b = rng.integers(-50, 50, size=1000).astype(np.float32)
+    out = oc.comm_steps({"a": a, "b": b}, [("reduce_copy", ["a", "b"], ["b"])] * 5, oc.F32)
+    assert np.array_equal(out["b"], b + 5 * a) and np.array_equal(out["a"], a) and np.array_equal(b, rng.integers(0, 1, 1000) * 0 + b)
+    # store-and-forward is a copy of bits, NaN payloads included
+    weird = np.array([0x7FC1, 0x7F81, 0xFFFF, 0x0001, 0x8000], dtype=np.uint16)
+    out = oc.comm_steps({"w": weird, "x": np.zeros(5, np.uint16), "y": np.zeros(5, np.uint16)}, [("gather_copy", ["w"], ["x", "y"])], oc.BF16)
+    assert np.array_equal(out["x"], weird) and np.array_equal(out["y"], weird)
+    # fp32 summation order is the steps' order: ((1e8 + -1e8) + 1) = 1, but a different order would give 0
+    big = {"p": np.array([1e8], np.float32), "q": np.array([-1e8], np.float32), "r": np.array([1.0], np.float32), "acc": np.zeros(1, np.float32)}
+    out = oc.comm_steps(big, [("reduce_copy", ["acc", "p"], ["acc"]), ("reduce_copy", ["acc", "q"], ["acc"]), ("reduce_copy", ["acc", "r"], ["acc"])], oc.F32)
+    assert out["acc"][0] == 1.0
+    out = oc.comm_steps(big, [("reduce_copy", ["acc", "q"], ["acc"]), ("reduce_copy", ["acc", "r"], ["acc"]), ("reduce_copy", ["acc", "p"], ["acc"])], oc.F32)
+    assert out["acc"][0] == 0.0
+    with pytest.raises(ValueError):
+        oc.comm_steps({"a": a, "b": b}, [("gather_copy", ["a", "b"], ["b"])], oc.F32)
