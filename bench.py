@@ -32,15 +32,21 @@ BF16_PEAK_TFLOPS = 2500.0       # MI355X dense bf16 MFMA, published
 LAMBDA = 256                    # compute units
 DEFAULT_CFG = (8, 256, 2 << 20)  # the collective library default the paper quotes (Sec. 4.3), NT from the tiny config
 EXTENDED_NC = (64, 128, 256)     # beyond the workloads' own grids: where the X = Y crossover lies on this part
+EXTENDED_NT = (128,)             # channels of two wavefronts: the lightest the NT grids of the benchmark spec hold
 FIVE = ["tiny", "dp_bucket", "tp_layer", "fsdp_chain", "compute_bound"]
 HEADLINE = "fsdp_chain"
-# Bytes past L2 per launch, from rocprofv3 FETCH_SIZE and WRITE_SIZE collected over `bench.py --standalone-only
-# --workload <name>` and scaled by the same counters' reading of the 64 MiB calibration copy; a recorded figure per
-# kernel and shape (commands and raw readings: profiles/*_hbm_counters.md), not measured by this run.
+# Bytes past L2 per launch, from rocprofv3 FETCH_SIZE and WRITE_SIZE collected over `bench.py --standalone-only` and
+# scaled by the same counters' reading of the 64 MiB calibration copy (x 1.9985 and x 0.9992); recorded figures per
+# kernel and shape (commands and raw readings: profiles/hbm_traffic_by_kernel.md), not measured by this run.
+MiB = 1 << 20
 TRAFFIC_FROM_PROFILE = {
-    "gemm 4096x4096x4096": int(224.3 * (1 << 20)),
-    "reduce_copy bf16 S=8 D=1 count=4194304": int(72.0 * (1 << 20)),
-    "reduce_copy f32 S=2 D=1 count=4194304": int(48.0 * (1 << 20)),
+    "gemm 512x512x512": int(3.66 * MiB),              # algorithmic 1.5 MiB
+    "gemm 4096x4096x4096": int(224.3 * MiB),          # algorithmic 96 MiB
+    "gemm 4096x3584x8192": int(412.1 * MiB),          # algorithmic 148 MiB
+    "gemm 8192x4096x4096": int(448.1 * MiB),          # algorithmic 160 MiB
+    "gemm 8192x8192x8192": int(1689.7 * MiB),         # algorithmic 384 MiB
+    "reduce_copy bf16 S=8 D=1 count=4194304": int(72.0 * MiB),
+    "gather_copy bf16 S=8 D=1 count=2097152": int(64.0 * MiB),
 }
 
 
@@ -287,7 +293,9 @@ def run_config(name, args, s_comm, s_comp, dependent=False):
 
     # ---- contention profiler: the workload's own grid, then the extended channel counts
     points = [(nc, nt, c) for nt in nt_grid for nc in w.nc_grid for c in w.chunk_grid]
-    ext_points = [(nc, nt, c) for nt in nt_grid for nc in EXTENDED_NC for c in w.chunk_grid]
+    nt_all = sorted(set(nt_grid) | set(EXTENDED_NT))
+    ext_points = [(nc, nt, c) for nt in nt_all for nc in list(w.nc_grid) + list(EXTENDED_NC) for c in w.chunk_grid
+                  if nc in EXTENDED_NC or nt not in nt_grid]
     t0 = time.perf_counter()
     sweep = lg.lagom_contention_sweep(launches, ncomm, comps, points, s_comm, s_comp, 1, args.sweep_iters)
     sweep_ext = lg.lagom_contention_sweep(launches, ncomm, comps, ext_points, s_comm, s_comp, 1, args.sweep_iters)
@@ -311,8 +319,8 @@ def run_config(name, args, s_comm, s_comp, dependent=False):
                                            corun_share=0.0, **fill_args)
 
     # ---- ladders (lagom_ladder_chunks): the cut ladder is the graded one; the uncut and the fixed-chunk ones beside it
-    def spaces_for(nc_grid, kind, pts):
-        return [lg.Space(list(nc_grid), nt_grid if len(nt_grid) > 1 else [256],
+    def spaces_for(nc_grid, kind, pts, nt=None):
+        return [lg.Space(list(nc_grid), nt if nt is not None else (nt_grid if len(nt_grid) > 1 else [256]),
                          lg.lagom_ladder_chunks(list(w.chunk_grid), max(nc_grid), nt_ref, per_src[j], kind, pts))
                 for j in range(ncomm)]
     spaces = spaces_for(w.nc_grid, lg.LAGOM_LADDER_CUT, sweep)
@@ -320,6 +328,10 @@ def run_config(name, args, s_comm, s_comp, dependent=False):
     spaces_fixed = spaces_for(w.nc_grid, lg.LAGOM_LADDER_FIXED_CHUNK, sweep)
     ext_nc = list(w.nc_grid) + [n for n in EXTENDED_NC if n > max(w.nc_grid)]
     spaces_ext = spaces_for(ext_nc, lg.LAGOM_LADDER_FIXED_CHUNK, all_sweep)
+    # a ladder that raises the channel count only, every channel as light as the extended grids allow (two wavefronts):
+    # on this part a channel of four or more wavefronts delays the GEMM workgroups of a multi-round GEMM on its
+    # compute unit, one of two wavefronts does not
+    spaces_ext_ntmin = spaces_for(ext_nc, lg.LAGOM_LADDER_FIXED_CHUNK, all_sweep, [min(nt_all)])
 
     def prof(cap):
         return lg.OverlapProfile(launches, comps, s_comm, s_comp, 1, args.sweep_iters, min_total_us=args.profile_min_us,
@@ -349,6 +361,10 @@ def run_config(name, args, s_comm, s_comp, dependent=False):
     tuned_ext, searches["priority_extended"], logs["priority_extended"] = search(spaces_ext, lg.LAGOM_PRIORITY, "ext")
     tuned_free_ext, searches["priority_free_steps_extended"], logs["priority_free_steps_extended"] = search(spaces_ext, lg.LAGOM_PRIORITY_FREE, "free-ext")
     hide_ext, searches["hide_comm_extended"], _ = search(spaces_ext, lg.LAGOM_HIDE_COMM, "hide-ext")
+    if spaces_ext_ntmin is not None:
+        tuned_ntmin, searches["priority_free_steps_extended_nt_min"], logs["priority_free_steps_extended_nt_min"] = \
+            search(spaces_ext_ntmin, lg.LAGOM_PRIORITY_FREE, "free-ext-ntmin")
+        hide_ntmin, searches["hide_comm_extended_nt_min"], _ = search(spaces_ext_ntmin, lg.LAGOM_HIDE_COMM, "hide-ext-ntmin")
     # brute force over the extended ladder: every level vector for one communication, the uniform vectors otherwise
     ext_ladder = ladder_cfgs(spaces_ext[0])
     if ncomm == 1:
@@ -407,6 +423,9 @@ def run_config(name, args, s_comm, s_comp, dependent=False):
              "tuned_free_steps": tuned_free.cfgs,
              "tuned_extended": tuned_ext.cfgs, "tuned_free_steps_extended": tuned_free_ext.cfgs,
              "hide_comm_extended": hide_ext.cfgs, "best_swept_extended": [best_sweep_ext.cfg] * ncomm}
+    if spaces_ext_ntmin is not None:
+        cands["tuned_free_steps_extended_nt_min"] = tuned_ntmin.cfgs
+        cands["hide_comm_extended_nt_min"] = hide_ntmin.cfgs
     if brute_ext is not None:
         cands["exhaustive_extended"] = brute_ext.cfgs
         cands["exhaustive_hide_extended"] = brute_hide_ext.cfgs
