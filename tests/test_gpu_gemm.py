@@ -177,3 +177,23 @@ def test_gemm_full_size_sampled_rows(M, N, K):
     corners = ref[:, np.r_[0:32, N - 32:N]]
     e_max, e_fro = og.rel_errors(got[rows][:, np.r_[0:32, N - 32:N]], corners)
     assert e_max <= GATE and e_fro <= GATE
+
+
+# More 256 x 256 tiles than compute units: several rounds of workgroups, ragged in M and N.
+@pytest.mark.parametrize("M,N,K", [(4100, 4200, 128),      # 17 x 17 = 289 tiles, ragged in M and N: 33 tiles in a second round
+                                   (4352, 7704, 64),       # 17 x 31 = 527 tiles: two to three rounds, one K-step
+                                   (8192, 8200, 192)])     # 32 x 33 = 1056 tiles: four to five rounds
+@pytest.mark.parametrize("b_is_nk", [True, False])
+@pytest.mark.parametrize("out", ["bf16", "f32"])
+def test_gemm_more_tiles_than_compute_units_integer_inputs_are_exact(M, N, K, b_is_nk, out):
+    """Small integers in bf16: every product and every partial sum is exact in fp32, so any tile that is skipped, done
+    twice, mixed with its neighbour's operands or written to the wrong place shows as a wrong integer."""
+    rng = np.random.default_rng(M + N + K)
+    a = rng.integers(-4, 5, size=(M, K)).astype(np.float32)
+    b = rng.integers(-4, 5, size=(N, K) if b_is_nk else (K, N)).astype(np.float32)
+    got = _gemm(oc.f32_to_bf16(a), oc.f32_to_bf16(b), b_is_nk, out)
+    want = (a @ (b.T if b_is_nk else b)).astype(np.float32)       # exact: every partial sum is a small integer
+    if out == "bf16":                                                # one rounding at the store, the oracle's
+        want = oc.bf16_to_f32(oc.f32_to_bf16(want))
+    bad = np.argwhere(got != want)
+    assert bad.size == 0, f"{len(bad)} wrong elements, first at {bad[0]} (tile {bad[0][0] // 256}, {bad[0][1] // 256})"
