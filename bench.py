@@ -196,6 +196,10 @@ def rotating_comm_roofline(st1, st2, op, dt_name, nsrc, count, cfgs, iters, fina
     # the floor of a launch on this grid: the same kernel moving one 16-byte vector per source
     tiny = [lg.CommLaunch(op, dt, srcs, [dst], 16 // esz, 0) for srcs, dst in bufs]
     floor_us = lg.lagom_overlap_run(tiny, [best[1]], [], st1, st2, 2, final_iters, lg.LAGOM_ALONE_COMM).X_us / nrot
+    # the same launches staged through LDS (lagom_comm_kernel_lds), best of the same configurations
+    staged = [lg.CommLaunch(op, dt, srcs, [dst], count, 0, lds_staged=True) for srcs, dst in bufs]
+    lds_best = min((lg.lagom_overlap_run(staged, [cfg], [], st1, st2, 1, iters, lg.LAGOM_ALONE_COMM).X_us / nrot, cfg) for cfg in cfgs)
+    lds_us = lg.lagom_overlap_run(staged, [lds_best[1]], [], st1, st2, 2, final_iters, lg.LAGOM_ALONE_COMM).X_us / nrot
     name = f"{'reduce_copy' if op == lg.LAGOM_REDUCE_COPY else 'gather_copy'} {dt_name} S={nsrc} D=1 count={count}"
     gbps = per_launch / us / 1e3
     res = {"bound": "hbm", "kernel": "reduce_copy_kernel" if op == lg.LAGOM_REDUCE_COPY else "gather_copy_kernel",
@@ -203,8 +207,10 @@ def rotating_comm_roofline(st1, st2, op, dt_name, nsrc, count, cfgs, iters, fina
            "traffic": None, "traffic_from_profile": TRAFFIC_FROM_PROFILE.get(name),
            "us_per_launch": us, "bytes_per_launch": per_launch, "cfg": list(best[1]), "rotation_mib": nrot * per_launch >> 20,
            "launches_timed": nrot * final_iters, "launch_floor_us": floor_us,
-           "frac_outside_launch_floor": per_launch / max(us - floor_us, 1e-9) / 1e3 / HBM_PEAK_GBPS}
-    del bufs, launches, tiny
+           "frac_outside_launch_floor": per_launch / max(us - floor_us, 1e-9) / 1e3 / HBM_PEAK_GBPS,
+           "staged_through_lds": {"us_per_launch": lds_us, "achieved": per_launch / lds_us / 1e3,
+                                  "frac": per_launch / lds_us / 1e3 / HBM_PEAK_GBPS, "cfg": list(lds_best[1])}}
+    del bufs, launches, tiny, staged
     return res
 
 
@@ -439,7 +445,11 @@ def run_config(name, args, s_comm, s_comp, dependent=False):
         cands["default_separate_launches"] = cands["default"]
         cands["tuned_separate_launches"] = tuned.cfgs
         cands["tuned_extended_separate_launches"] = tuned_ext.cfgs
-    which_launches = lambda k: separate if k.endswith("_separate_launches") else launches
+    # the tuned parameters with every launch staged through LDS (such a workgroup cannot share a compute unit with a GEMM's)
+    staged = [lg.CommLaunch(l.op, l.dtype, l.srcs, l.dsts, l.count, l.comm_id, l.after_comp, False, True) for l in launches]
+    cands["default_lds_staged"] = cands["default"]
+    cands["tuned_lds_staged"] = tuned.cfgs
+    which_launches = lambda k: separate if k.endswith("_separate_launches") else (staged if k.endswith("_lds_staged") else launches)
     meas = {k: [] for k in cands}
     order = list(cands)
     y_alone_rounds = []
@@ -625,6 +635,12 @@ def main():
         "config": {"workload": headline + ("+dependent" if h["dependent"] else ""), "comm": h["comm"], "gemm": h["gemm"],
                    "default_cfg": list(DEFAULT_CFG), "tuned_cfgs": h["candidates"]["tuned"]["cfgs"], "rounds": args.rounds},
         "value_min_median_max": h["speedup_tuned_vs_default"], "verdict": h["verdict"],
+        # the same ratio for the other searches of the headline workload (min, median, max over the rounds): Alg. 1/2 with
+        # free steps on the fixed-chunk ladder of the task's grids; the same on the extended space (NC up to 256, channels of
+        # two wavefronts); the communication-only descent; the best point of the profiler's sweeps
+        "value_other_searches": {k: h["candidates"][k]["speedup_vs_default"] for k in
+                                 ("tuned_free_steps", "tuned_free_steps_extended_nt_min", "comm_descent", "best_swept", "best_swept_extended")
+                                 if k in h["candidates"]},
         "z_tuned_us": h["z_tuned_us"], "z_default_us": h["z_default_us"],
         "comm_hbm_gbps": roofline_comm["achieved"], "gemm_mfma_util": h["gemm_mfma_util"],
         "gemm_mfma_util_by_shape": {c["roofline"]["shape"]: c["roofline"]["frac"] for c in configs.values()},

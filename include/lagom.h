@@ -78,6 +78,18 @@ int lagom_comm_kernel(lagom_op op, lagom_dtype dt,
                       void* const* dsts, int ndst,
                       int64_t count, const lagom_cfg* cfg, void* hip_stream);
 
+/* lagom_comm_kernel_lds -- lagom_comm_kernel with every source vector staged through LDS: direct-to-LDS
+ * loads of 16 bytes per lane fill a ring of stages per wavefront (8 KiB per wavefront), the next stages in
+ * flight while the current one is read back and folded, in source order.  Same arguments, same result bit
+ * for bit, same chunk-to-channel assignment; a workgroup holds (nt / 64) * 8 KiB of LDS, so it shares a
+ * compute unit only with workgroups that leave that much (lagom_gemm's leave none).  A gather-copy whose
+ * shards are not multiples of 16 bytes is passed on to lagom_comm_kernel.  Slower than the register path
+ * on gfx950 (measured); kept for comparison. */
+int lagom_comm_kernel_lds(lagom_op op, lagom_dtype dt,
+                          const void* const* srcs, int nsrc,
+                          void* const* dsts, int ndst,
+                          int64_t count, const lagom_cfg* cfg, void* hip_stream);
+
 /* ---------------------------------------------------------------------------------
  * lagom_comm_steps -- several local steps of ONE collective in one kernel launch (Sec. 2.1: a ring
  * all-reduce is P-1 reduce steps followed by P-1 copy steps; Sec. 3.2: the collective's NC thread
@@ -157,6 +169,8 @@ typedef struct {
                                    index into cfgs; launches of one id are contiguous  */
     int32_t after_comp;         /* index of a computation that must have finished before this
                                    launch starts, or -1 (honoured in LAGOM_CORUN only)  */
+    int32_t lds_staged;         /* non-zero: issue this launch through lagom_comm_kernel_lds (not
+                                   together with fuse_with_prev: LAGOM_EINVAL)                  */
     int32_t fuse_with_prev;     /* non-zero: issue this launch in the same kernel launch as the
                                    previous one (lagom_comm_steps).  Needs the same comm_id, dtype
                                    and count as the previous launch, after_comp == -1, and the

@@ -31,7 +31,7 @@ LAGOM_MAX_STEPS, LAGOM_MAX_STEP_PTRS = 32, 96
 EXPORTS = ["lagom_strerror", "lagom_last_error", "lagom_comm_kernel", "lagom_gemm", "lagom_gemm_describe",
            "lagom_overlap_run", "lagom_contention_sweep", "lagom_comm_bytes", "lagom_cost_model", "lagom_tune",
            "lagom_model_profile", "lagom_overlap_profile", "lagom_streams_overlap", "lagom_overlap_steps", "lagom_overlap_steps_graph",
-           "lagom_model_fill", "lagom_model_calibrate", "lagom_ladder_chunks", "lagom_comm_steps"]
+           "lagom_model_fill", "lagom_model_calibrate", "lagom_ladder_chunks", "lagom_comm_steps", "lagom_comm_kernel_lds"]
 
 
 class LagomError(RuntimeError):
@@ -54,7 +54,7 @@ class lagom_gemm_geometry(C.Structure):
 class lagom_comm_desc(C.Structure):
     _fields_ = [("op", C.c_int32), ("dtype", C.c_int32), ("srcs", C.POINTER(C.c_void_p)), ("nsrc", C.c_int32),
                 ("dsts", C.POINTER(C.c_void_p)), ("ndst", C.c_int32), ("count", C.c_int64), ("comm_id", C.c_int32),
-                ("after_comp", C.c_int32), ("fuse_with_prev", C.c_int32)]
+                ("after_comp", C.c_int32), ("lds_staged", C.c_int32), ("fuse_with_prev", C.c_int32)]
 
 
 class lagom_comm_step(C.Structure):
@@ -166,6 +166,7 @@ def lib() -> C.CDLL:
         L.lagom_last_error.restype = C.c_char_p
         L.lagom_comm_kernel.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_void_p), C.c_int, C.POINTER(C.c_void_p), C.c_int,
                                         C.c_int64, C.POINTER(lagom_cfg), C.c_void_p]
+        L.lagom_comm_kernel_lds.argtypes = L.lagom_comm_kernel.argtypes
         L.lagom_comm_steps.argtypes = [C.c_int, C.POINTER(lagom_comm_step), C.c_int, C.c_int64, C.POINTER(lagom_cfg), C.c_void_p]
         L.lagom_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_void_p]
         L.lagom_gemm_describe.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.c_int, C.POINTER(lagom_gemm_geometry)]
@@ -242,6 +243,12 @@ def lagom_comm_kernel(op: int, dt: int, srcs, dsts, count: int, cfg: CfgLike, st
                                    int(count), C.byref(c), _stream(stream)))
 
 
+def lagom_comm_kernel_lds(op: int, dt: int, srcs, dsts, count: int, cfg: CfgLike, stream=None) -> None:
+    c = _cfg(cfg)
+    _check(lib().lagom_comm_kernel_lds(op, dt, _ptr_array(srcs), len(srcs), _ptr_array(dsts), len(dsts),
+                                       int(count), C.byref(c), _stream(stream)))
+
+
 def lagom_comm_steps(dt: int, steps: Sequence[Tuple[int, Sequence, Sequence]], count: int, cfg: CfgLike, stream=None) -> None:
     """steps: (op, srcs, dsts) per local step, all of `count` elements of dt; one kernel launch for all of them."""
     c = _cfg(cfg)
@@ -278,6 +285,7 @@ class CommLaunch:
     comm_id: int = 0
     after_comp: int = -1        # computation that must have finished before this launch starts
     fuse: bool = False          # issue in the same kernel launch as the previous launch of this communication
+    lds_staged: bool = False    # issue through lagom_comm_kernel_lds
 
 
 @dataclass
@@ -318,7 +326,7 @@ class _Group:
             self.keep += [s, d]
             self.L[i] = lagom_comm_desc(l.op, l.dtype, C.cast(s, C.POINTER(C.c_void_p)), len(l.srcs),
                                         C.cast(d, C.POINTER(C.c_void_p)), len(l.dsts), int(l.count), int(l.comm_id),
-                                        int(l.after_comp), 1 if l.fuse else 0)
+                                        int(l.after_comp), 1 if l.lds_staged else 0, 1 if l.fuse else 0)
         self.G = (lagom_gemm_desc * max(self.ncomp, 1))()
         for i, g in enumerate(comps):
             self.G[i] = lagom_gemm_desc(_ptr(g.A), _ptr(g.B), _ptr(g.C), int(g.M), int(g.N), int(g.K),

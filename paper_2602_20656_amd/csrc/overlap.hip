@@ -92,6 +92,8 @@ int validate(const lagom_comm_desc* L, int nlaunch, const lagom_cfg* cfgs, int n
         }
         if (d.after_comp < -1 || d.after_comp >= ncomp) return lagom::fail(LAGOM_EINVAL, "launch %d: after_comp %d outside -1..%d", i, d.after_comp, ncomp - 1);
         if (int rc = lagom::check_comm_args(d.op, d.dtype, d.srcs, d.nsrc, d.dsts, d.ndst, d.count)) return rc;
+        if (d.lds_staged && (d.fuse_with_prev || (i + 1 < nlaunch && L[i + 1].fuse_with_prev)))
+            return lagom::fail(LAGOM_EINVAL, "launch %d: a launch staged through LDS cannot be part of a fused run", i);
         if (d.fuse_with_prev) {
             if (i == 0 || L[i - 1].comm_id != d.comm_id || L[i - 1].dtype != d.dtype || L[i - 1].count != d.count || d.after_comp != -1)
                 return lagom::fail(LAGOM_EINVAL, "launch %d: fuse_with_prev needs a previous launch of the same communication, dtype and count, and no dependency of its own", i);
@@ -156,7 +158,10 @@ int enqueue_group(const GroupPlan& plan, const lagom_comm_desc* launches, int nl
                 if (ga_start && li == plan.first[g]) HIP_TRY(hipEventRecord(ga_start[g], sa));
                 int run = 1;                                   // this launch and the ones fused to it
                 while (li + run < nl && launches[li + run].fuse_with_prev) ++run;
-                if (run == 1) {
+                if (run == 1 && d.lds_staged) {
+                    if (int rc = lagom_comm_kernel_lds((lagom_op)d.op, (lagom_dtype)d.dtype, d.srcs, d.nsrc, d.dsts, d.ndst,
+                                                       d.count, &cfgs[d.comm_id], sa)) return rc;
+                } else if (run == 1) {
                     if (int rc = lagom_comm_kernel((lagom_op)d.op, (lagom_dtype)d.dtype, d.srcs, d.nsrc, d.dsts, d.ndst,
                                                    d.count, &cfgs[d.comm_id], sa)) return rc;
                 } else {

@@ -300,3 +300,67 @@ def test_steps_launch_rejects_what_it_cannot_order():
     with pytest.raises(lg.LagomError):
         lg.lagom_comm_steps(lg.LAGOM_F32, [(lg.LAGOM_REDUCE_COPY, [p], [p + 8192])] * 33, 1024, good)
     lg.lagom_comm_steps(lg.LAGOM_F32, [(lg.LAGOM_REDUCE_COPY, [p], [p + 8192])], 0, good)      # count 0: nothing is launched
+
+
+# ------------------------------------------------------------------ staged through LDS
+def _run_lds(op, dtype, srcs, ndst, cfg, out_len):
+    np_dt = np.float32 if dtype == "f32" else np.uint16
+    d_srcs = [dev(s) for s in srcs]
+    fill = np.full(out_len + 2 * GUARD, 0x7B if np_dt == np.uint16 else 123.0, dtype=np_dt)
+    d_dsts = [dev(fill) for _ in range(ndst)]
+    esz = np.dtype(np_dt).itemsize
+    lg.lagom_comm_kernel_lds(op, lg.LAGOM_F32 if dtype == "f32" else lg.LAGOM_BF16, d_srcs, [d.data_ptr() + GUARD * esz for d in d_dsts],
+                             len(srcs[0]), cfg, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    outs = []
+    for d in d_dsts:
+        h = host(d, np_dt)
+        assert same_bits(h[:GUARD], fill[:GUARD]) and same_bits(h[GUARD + out_len:], fill[GUARD + out_len:]), "guard region clobbered"
+        outs.append(h[GUARD:GUARD + out_len])
+    return outs
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("nsrc,ndst", [(1, 1), (2, 1), (2, 2), (3, 1), (5, 4), (8, 1), (16, 2)])
+def test_lds_staged_reduce_copy_equals_oracle(dtype, nsrc, ndst):
+    """Whole batches through LDS, the rest of every chunk through the register path, a short tail at the end; one to
+    sixteen wavefronts; chunks smaller than, equal to and larger than a workgroup's batch round."""
+    for count, cfg in [(1, (1, 64, 16)), (3, (4, 128, 4096)), (1000003, (7, 256, 65536)), (262144 + 5, (32, 1024, 32768)),
+                       (70001, (3, 512, 1 << 20)), (1 << 20, (256, 512, 16384)), (123457, (5, 64, 2048)), (40000, (2, 192, 6000 * 16))]:
+        srcs = _sources(dtype, nsrc, count, 400 + nsrc)
+        want = oc.reduce_copy(srcs, dtype, ndst)
+        got = _run_lds(lg.LAGOM_REDUCE_COPY, dtype, srcs, ndst, cfg, count)
+        for g, w in zip(got, want):
+            assert same_bits(g, w), (dtype, nsrc, ndst, count, cfg)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_lds_staged_gather_copy_equals_oracle(dtype):
+    for nsrc, ndst, count, cfg in [(8, 1, 2097152, (32, 256, 1 << 20)), (8, 2, 100000, (5, 512, 32768)), (3, 1, 70008, (256, 1024, 16384)),
+                                   (1, 3, 1000003, (9, 128, 65536)), (4, 1, 1001, (2, 64, 4096))]:     # the last: shards not 16-byte multiples
+        srcs = _sources(dtype, nsrc, count, 500 + nsrc)
+        want = oc.gather_copy(srcs, ndst)
+        got = _run_lds(lg.LAGOM_GATHER_COPY, dtype, srcs, ndst, cfg, nsrc * count)
+        for g, w in zip(got, want):
+            assert same_bits(g, w), (dtype, nsrc, ndst, count, cfg)
+
+
+def test_lds_staged_in_place_and_through_the_runner():
+    n = 1 << 20
+    a, b = inputs.uniform_f32(0, n), inputs.uniform_f32(1, n)
+    da, db = dev(a), dev(b)
+    lg.lagom_comm_kernel_lds(lg.LAGOM_REDUCE_COPY, lg.LAGOM_F32, [da, db], [db], n, (16, 512, 65536), torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    assert same_bits(host(db, np.float32), oc.reduce_copy([a, b], oc.F32)[0])          # b <- a + b, in place
+    s1, s2 = lg.overlapping_streams()
+    out = dev(np.zeros(n, np.float32))
+    db2 = dev(b)
+    A, B = inputs.normal_bf16(2, (512, 512)), inputs.normal_bf16(3, (512, 512))
+    comps = [lg.GemmDesc(dev(A), dev(B), dev(np.zeros((512, 512), np.uint16)), 512, 512, 512)]
+    launches = [lg.CommLaunch(lg.LAGOM_REDUCE_COPY, lg.LAGOM_F32, [da, db2], [out], n, 0, lds_staged=True)]
+    t = lg.lagom_overlap_run(launches, [(4, 256, 128 << 10)], comps, s1, s2, 1, 3, lg.LAGOM_CORUN)
+    torch.cuda.synchronize()
+    assert t.X_us > 0 and same_bits(host(out, np.float32), oc.reduce_copy([a, b], oc.F32)[0])
+    bad = [launches[0], lg.CommLaunch(lg.LAGOM_REDUCE_COPY, lg.LAGOM_F32, [da, db2], [out], n, 0, fuse=True, lds_staged=True)]
+    with pytest.raises(lg.LagomError):
+        lg.lagom_overlap_run(bad, [(4, 256, 128 << 10)], comps, s1, s2, 0, 1, lg.LAGOM_ALONE_COMM)
