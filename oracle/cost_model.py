@@ -37,6 +37,12 @@ Readings taken where the text leaves a choice:
   Every pin of the printed model runs with sigma = 0; the extension has pins of its own (three
   pencil-worked cases, the closed forms at both ends).
 
+* Not in the paper either (default off): Model.resident_penalty maps a thread count NT to rho >= 0.  A wave of the
+  computation that is issued while a communication with NT threads per channel is active lasts f_ij * (1 + rho(NT)).
+  Reason: on the part this build targets the computation is slowed for as long as channels are resident, by an amount that
+  depends on how heavy one channel is (its thread count) and hardly on how many there are -- neither (lambda - NC) nor
+  B - V of Eq. 5-6 can express that.  An NT without an entry has rho = 0; with an empty map the model is unchanged bit for bit.
+
 Units: time in microseconds, bandwidth in bytes per microsecond, D_i in bytes.
 """
 from __future__ import annotations
@@ -64,6 +70,7 @@ class Model:
     # one table per communication: cfg -> (x microseconds, V bytes/microsecond)
     tables: List[Dict[Cfg, Tuple[float, float]]] = field(default_factory=list)
     corun_share: float = 0.0       # sigma; 0 = Eq. 5-6 as printed
+    resident_penalty: Dict[int, float] = field(default_factory=dict)   # NT -> rho; empty = Eq. 6 as printed
 
 
 @dataclass
@@ -101,6 +108,16 @@ def wave_time(theta: float, lam: int, nc: int, tb: int, d_bytes: float, bw_peak:
     return theta + (cap * d_bytes) / (bw_peak - v)
 
 
+def penalty_factor(model: Model, nt: int) -> float:
+    """1 + rho(NT); exactly 1.0 where the map has no entry."""
+    rho = model.resident_penalty.get(int(nt))
+    if rho is None:
+        return 1.0
+    if not rho >= 0.0:
+        raise ValueError("negative resident penalty")
+    return 1.0 + rho
+
+
 def predict(model: Model, cfgs: Sequence[Cfg], comp_after_comm=None, comm_after_comp=None) -> Prediction:
     """Eq. 1 over Eq. 4-6 for the whole overlap group.
 
@@ -112,7 +129,7 @@ def predict(model: Model, cfgs: Sequence[Cfg], comp_after_comm=None, comm_after_
     N = len(model.tables)
     if len(cfgs) != N:
         raise ValueError("one configuration per communication")
-    x, v, nc = [], [], []
+    x, v, nc, pf = [], [], [], []
     for j, cfg in enumerate(cfgs):
         key = (int(cfg[0]), int(cfg[1]), int(cfg[2]))
         if key not in model.tables[j]:
@@ -122,7 +139,7 @@ def predict(model: Model, cfgs: Sequence[Cfg], comp_after_comm=None, comm_after_
             raise ValueError("NC out of range")
         if not (0.0 <= vj < model.bw_peak) or not xj >= 0.0:
             raise ValueError("table entry out of range")
-        x.append(float(xj)); v.append(float(vj)); nc.append(key[0])
+        x.append(float(xj)); v.append(float(vj)); nc.append(key[0]); pf.append(penalty_factor(model, key[1]))
     # communication j is active on [T[j], T[j+1])
     T = [0.0]
     for xj in x:
@@ -148,6 +165,8 @@ def predict(model: Model, cfgs: Sequence[Cfg], comp_after_comm=None, comm_after_
             if slot < N:
                 cap = workgroups_in_flight(model.lam, nc[slot], comp.tb, model.corun_share)
                 f[slot] = wave_time(comp.theta, model.lam, nc[slot], comp.tb, comp.d_bytes, model.bw_peak, v[slot], model.corun_share)
+                if pf[slot] != 1.0:
+                    f[slot] = f[slot] * pf[slot]
             else:
                 cap = model.lam * comp.tb
                 f[slot] = wave_time(comp.theta, model.lam, 0, comp.tb, comp.d_bytes, model.bw_peak, 0.0)
@@ -172,6 +191,7 @@ def _predict_dependent(model: Model, cfgs: Sequence[Cfg], comp_after_comm, comm_
     free = predict(model, cfgs)                       # validates the inputs; x_j do not depend on the timeline
     x = free.x
     nc = [int(c[0]) for c in cfgs]
+    pf = [penalty_factor(model, int(c[1])) for c in cfgs]
     v = [model.tables[j][(int(c[0]), int(c[1]), int(c[2]))][1] for j, c in enumerate(cfgs)]
     cac = list(comp_after_comm) if comp_after_comm is not None else [-1] * M
     cap_ = list(comm_after_comp) if comm_after_comp is not None else [-1] * N
@@ -217,6 +237,8 @@ def _predict_dependent(model: Model, cfgs: Sequence[Cfg], comp_after_comm, comm_
                     if slot < N:
                         cap = workgroups_in_flight(model.lam, nc[slot], comp.tb, model.corun_share)
                         f[slot] = wave_time(comp.theta, model.lam, nc[slot], comp.tb, comp.d_bytes, model.bw_peak, v[slot], model.corun_share)
+                        if pf[slot] != 1.0:
+                            f[slot] = f[slot] * pf[slot]
                     else:
                         cap = model.lam * comp.tb
                         f[slot] = wave_time(comp.theta, model.lam, 0, comp.tb, comp.d_bytes, model.bw_peak, 0.0)

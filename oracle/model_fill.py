@@ -21,6 +21,12 @@ theta nor how V(NC, C) is obtained.  The reading taken here, step by step:
   is reported over the held-out points.  x and V of every point stay in the tables -- they are
   measured inputs of the model (Eq. 1), not predictions.
 
+* Calibration of the resident penalty rho(NT) (the second extension of oracle.cost_model), after sigma: for every thread
+  count NT among the points that are not held out, in ascending order, every candidate rho is scored by the mean error
+  over the fitted points *with that NT* (the penalties chosen for smaller NT already in place -- they do not touch
+  these points, a point's communications all have its NT), the first smallest wins.  Errors are then reported over all
+  fitted and all held-out points with sigma and every rho in place.
+
 Every function is pinned in tests/test_oracle_model_fill.py by pencil-worked numbers, by the
 round trip "filled model without communication == t_alone", and by recovering a planted sigma.
 """
@@ -89,11 +95,12 @@ def fill_tables(points: Sequence[SweepPoint], comm_bytes: Sequence[float], bw_pe
 
 
 def fill(points: Sequence[SweepPoint], geo: Geometry, ncomp: int, comm_bytes: Sequence[float], lam: int, bw_peak: float,
-         sigma: float = 0.0, theta_points: Optional[Sequence[SweepPoint]] = None) -> cm.Model:
+         sigma: float = 0.0, theta_points: Optional[Sequence[SweepPoint]] = None, penalty=None) -> cm.Model:
     """The model of one overlap group.  theta is fitted on `theta_points` (default: all points)."""
     theta = fit_theta(t_alone(theta_points if theta_points is not None else points, ncomp), geo, lam, bw_peak)
     comps = [cm.Comp(geo.mu, geo.tb, geo.d_bytes, theta) for _ in range(ncomp)]
-    return cm.Model(lam, bw_peak, comps, fill_tables(points, comm_bytes, bw_peak), corun_share=sigma)
+    return cm.Model(lam, bw_peak, comps, fill_tables(points, comm_bytes, bw_peak), corun_share=sigma,
+                    resident_penalty=dict(penalty) if penalty else {})
 
 
 def y_errors(model: cm.Model, points: Sequence[SweepPoint], comp_after_comm=None, comm_after_comp=None) -> Tuple[float, float]:
@@ -117,11 +124,12 @@ class Calibration:
     held_max: float
     n_fit: int
     n_held: int
+    penalty: Optional[dict] = None      # NT -> rho, when rhos were given
 
 
 def calibrate(points: Sequence[SweepPoint], held_out: Optional[Sequence[bool]], geo: Geometry, ncomp: int,
               comm_bytes: Sequence[float], lam: int, bw_peak: float, sigmas: Sequence[float],
-              comp_after_comm=None, comm_after_comp=None) -> Calibration:
+              comp_after_comm=None, comm_after_comp=None, rhos: Optional[Sequence[float]] = None) -> Calibration:
     held = [bool(h) for h in held_out] if held_out is not None else [False] * len(points)
     fit_pts = [p for p, h in zip(points, held) if not h]
     held_pts = [p for p, h in zip(points, held) if h]
@@ -134,5 +142,20 @@ def calibrate(points: Sequence[SweepPoint], held_out: Optional[Sequence[bool]], 
         if best is None or mean < best[0]:
             best = (mean, worst, s, model)
     mean, worst, s, model = best
+    penalty = None
+    if rhos:
+        penalty = {}
+        for nt in sorted(set(int(p.cfg[1]) for p in fit_pts)):
+            with_nt = [p for p in fit_pts if int(p.cfg[1]) == nt]
+            pick = None
+            for rho in rhos:
+                model.resident_penalty = dict(penalty)
+                model.resident_penalty[nt] = float(rho)
+                m, _ = y_errors(model, with_nt, comp_after_comm, comm_after_comp)
+                if pick is None or m < pick[0]:
+                    pick = (m, float(rho))
+            penalty[nt] = pick[1]
+        model.resident_penalty = dict(penalty)
+        mean, worst = y_errors(model, fit_pts, comp_after_comm, comm_after_comp)
     h_mean, h_max = y_errors(model, held_pts, comp_after_comm, comm_after_comp)
-    return Calibration(s, mean, worst, h_mean, h_max, len(fit_pts), len(held_pts))
+    return Calibration(s, mean, worst, h_mean, h_max, len(fit_pts), len(held_pts), penalty)

@@ -5,6 +5,7 @@ import json
 import math
 import os
 
+import numpy as np
 import pytest
 
 from oracle import cost_model as cm
@@ -167,3 +168,36 @@ def test_corun_share_out_of_range_is_rejected():
     for bad in (-0.1, 1.5, float("nan")):
         with pytest.raises(ValueError):
             cm.predict(cm.Model(8, 100.0, [cm.Comp(10, 1, 1.0, 1.0)], [{(2, 64, 64): (1.0, 1.0)}], corun_share=bad), [(2, 64, 64)])
+
+
+def test_resident_penalty_pencil_cases_and_neutral_element(golden_dir):
+    fx = json.load(open(os.path.join(golden_dir, "cost_model_worked.json")))
+    for case in fx["resident_penalty_cases"]:
+        model, cfgs = _model(fx["lambda"], fx["bw_peak"], case["comps"], case["comms"])
+        model.corun_share = case["corun_share"]
+        model.resident_penalty = {int(k): v for k, v in case["penalty"].items()}
+        p = cm.predict(model, cfgs)
+        assert p.y == case["y"] and p.g == case["g"], case["name"]
+        assert (p.X, p.Y, p.Z) == (case["X"], case["Y"], case["Z"]), case["name"]
+    # rho = 0 and an empty map are the printed model bit for bit; Y grows with rho; waves after the last communication never pay
+    rng = np.random.default_rng(5)
+    for _ in range(100):
+        lam, bw = 64, float(rng.uniform(1e3, 1e6))
+        comps = [cm.Comp(int(rng.integers(1, 900)), 1, float(rng.uniform(1e2, 1e5)), float(rng.uniform(1, 50))) for _ in range(int(rng.integers(1, 4)))]
+        tables = [{(4, 256, 64): (float(rng.uniform(0, 300)), float(rng.uniform(0, 0.5 * bw)))} for _ in range(int(rng.integers(1, 4)))]
+        cfgs = [(4, 256, 64)] * len(tables)
+        base = cm.predict(cm.Model(lam, bw, comps, tables), cfgs)
+        zero = cm.predict(cm.Model(lam, bw, comps, tables, resident_penalty={256: 0.0}), cfgs)
+        assert (zero.y, zero.g, zero.Z) == (base.y, base.g, base.Z)
+        # under one communication that outlasts everything every wave pays: Y scales by exactly 1 + rho up to rounding.
+        # (With communications that end inside a computation Y is not monotone in rho: longer waves shift later ones
+        # past the end of a communication, where more workgroups fit in a wave.)
+        long_tables = [{(4, 256, 64): (1e12, tables[0][(4, 256, 64)][1])}]
+        b1 = cm.predict(cm.Model(lam, bw, comps, long_tables), cfgs[:1])
+        s1 = cm.predict(cm.Model(lam, bw, comps, long_tables, resident_penalty={256: 0.25}), cfgs[:1])
+        assert s1.g == b1.g and s1.Y == pytest.approx(1.25 * b1.Y, rel=1e-12)
+        never = cm.predict(cm.Model(lam, bw, comps, [{(4, 256, 64): (0.0, 0.0)} for _ in tables], resident_penalty={256: 0.25}), cfgs)
+        alone = cm.predict(cm.Model(lam, bw, comps, [{(4, 256, 64): (0.0, 0.0)} for _ in tables]), cfgs)
+        assert never.y == alone.y                      # communications of no duration: no wave is issued under one
+    with pytest.raises(ValueError):
+        cm.predict(cm.Model(64, 1e3, [cm.Comp(10, 1, 1.0, 1.0)], [{(4, 256, 64): (5.0, 1.0)}], resident_penalty={256: -0.1}), [(4, 256, 64)])

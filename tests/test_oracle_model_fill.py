@@ -113,3 +113,33 @@ def test_calibration_recovers_a_planted_share():
         assert all(cm.predict(truth, [p.cfg]).Y == pytest.approx(p.comp_corun_us, rel=1e-9) for p in pts)
         found += c.sigma == planted
     assert found >= 20                                          # distinct shares can give identical wave counts; most are identified
+
+
+def test_penalty_calibration_pencil_case_and_planted_values():
+    # The pencil case of the share calibration, continued: with sigma = 0.5 the fitted point predicts 386.667 against 400
+    # measured.  rho candidates 0, 0.05, 0.1: 386.667 -> error 1/30; 386.667 * 1.05 = 406 -> 6/400 = 0.015; * 1.1 = 425.33 ->
+    # 0.0633.  rho(64) = 0.05.  The held-out point (NT 64 too): 352.5 * 1.05 = 370.125 against 350 -> 0.0575.
+    fit = _pt((2, 64, 16), 1000.0, 330.0, 400.0, 10.0)
+    held = _pt((1, 64, 16), 1000.0, 500.0, 350.0, 20.0)
+    c = mf.calibrate([fit, held], [False, True], GEO, 1, [4000.0], LAM, BW, [0.0, 0.5, 1.0], rhos=[0.0, 0.05, 0.1])
+    assert c.sigma == 0.5 and c.penalty == {64: 0.05}
+    assert c.fit_mean == pytest.approx(6.0 / 400.0, rel=1e-9) and c.held_mean == pytest.approx(20.125 / 350.0, rel=1e-9)
+    # planted: two thread counts with different penalties, recovered exactly from points the planted model produced
+    rng = np.random.default_rng(77)
+    rhos = [i / 50 for i in range(16)]
+    for _ in range(20):
+        lam, geo, bw = 256, mf.Geometry(int(rng.integers(300, 1500)), 1, float(rng.uniform(2e5, 1e6))), 8e6
+        theta = float(rng.uniform(20.0, 100.0))
+        alone = -(-geo.mu // lam) * (theta + lam * geo.d_bytes / bw)
+        planted = {128: float(rng.choice(rhos)), 256: float(rng.choice(rhos))}
+        truth = cm.Model(lam, bw, [cm.Comp(geo.mu, 1, geo.d_bytes, theta)], [{}], corun_share=1.0, resident_penalty=planted)
+        pts = []
+        for nt in (128, 256):
+            for nc in (8, 32, 128):
+                cfg, v, xc = (nc, nt, 1 << 16), float(rng.uniform(1e5, 4e6)), 1e9
+                truth.tables[0][cfg] = (xc, v)
+                pts.append(_pt(cfg, xc, alone, cm.predict(truth, [cfg]).Y, v))
+        c = mf.calibrate(pts, [i % 3 == 2 for i in range(len(pts))], geo, 1, [1.0], lam, bw, [1.0], rhos=rhos)
+        assert c.penalty == planted and c.fit_mean <= 1e-9 and c.held_mean <= 1e-9
+    # without candidates nothing changes
+    assert mf.calibrate([fit], None, GEO, 1, [4000.0], LAM, BW, [0.5]).penalty is None
