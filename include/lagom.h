@@ -297,6 +297,7 @@ int64_t lagom_comm_bytes(int op, int dtype, int nsrc, int ndst, int64_t count);
 typedef struct { lagom_cfg cfg; double x_us; double v; } lagom_table_entry;
 typedef struct { const lagom_table_entry* entries; int32_t n; } lagom_comm_table;
 typedef struct { int64_t mu; int32_t tb; double d_bytes; double theta_us; } lagom_comp_model;
+typedef struct { int32_t nt; double rho; } lagom_penalty;
 typedef struct {
     int32_t lambda;                  /* compute units                                   */
     double  bw_peak;                 /* B, bytes per microsecond                        */
@@ -317,6 +318,13 @@ typedef struct {
      * wavefronts fit beside the GEMM's on the same compute unit (sigma near 1): the channel then
      * costs the computation bandwidth (V), not compute units.                                  */
     double corun_share;
+    /* Not in the paper either; null / 0 gives Eq. 6 exactly.  A wave of a computation issued while a
+     * communication whose channels have nt threads is active lasts f_ij * (1 + rho) for the entry with that
+     * nt (first match; no entry: rho = 0).  On this part the computation is slowed for as long as channels
+     * are resident, by an amount that depends on how heavy one channel is and hardly on how many there are:
+     * neither (lambda - NC) nor B - V can express that.                                             */
+    const lagom_penalty* penalty;    /* host [npenalty], nullable                                   */
+    int32_t npenalty;
 } lagom_model;
 typedef struct {
     double X_us, Y_us, Z_us;
@@ -328,7 +336,7 @@ typedef struct {
 
 /* Errors: LAGOM_EINVAL for a null pointer, ncomm != model ncomm, a configuration that
  * is not in its table, NC < 1 or NC >= lambda, V < 0 or V >= B, x < 0, mu < 0, TB < 1,
- * corun_share outside [0, 1]. */
+ * corun_share outside [0, 1], a negative rho. */
 int lagom_cost_model(const lagom_model* m, const lagom_cfg* cfgs, int ncomm, lagom_pred* out);
 
 /* ---------------------------------------------------------------------------------
@@ -368,16 +376,24 @@ int lagom_model_fill(const lagom_sweep_point* pts, int npts, const uint8_t* held
  * Y_measured over the points that are not held out (all communications at the point's
  * configuration), the first smallest mean wins; the same error over the held-out points is
  * reported beside it.  x and V of every point stay in the tables: they are measured inputs of
- * Eq. 1, not predictions.  comp_after_comm / comm_after_comp as in lagom_model (nullable). */
+ * Eq. 1, not predictions.  comp_after_comm / comm_after_comp as in lagom_model (nullable).
+ * With nrho > 0 the resident penalty (lagom_model.penalty) is calibrated after sigma: for every thread count
+ * among the points not held out, in ascending order, the candidate rho with the smallest mean error over the
+ * fitted points of that thread count (first smallest) is written to penalty_out; the errors reported are then
+ * those with sigma and every rho in place.  penalty_out needs room for every distinct thread count
+ * (LAGOM_EINVAL if penalty_capacity is too small). */
 typedef struct {
     double  sigma, theta_us;
     double  fit_mean, fit_max;      /* over the points not held out                         */
     double  held_mean, held_max;    /* over the held-out points (0 when there are none)     */
     int32_t n_fit, n_held;
+    int32_t npenalty;               /* entries written to penalty_out                       */
 } lagom_calibration;
 int lagom_model_calibrate(const lagom_sweep_point* pts, int npts, const uint8_t* held_out, const lagom_fill_desc* d,
                           const int32_t* comp_after_comm, const int32_t* comm_after_comp,
-                          const double* sigmas, int nsigma, lagom_calibration* out);
+                          const double* sigmas, int nsigma,
+                          const double* rhos, int nrho, lagom_penalty* penalty_out, int penalty_capacity,
+                          lagom_calibration* out);
 
 /* ---------------------------------------------------------------------------------
  * lagom_tune -- priority-based parameter search (Sec. 3.3-3.4: metric H of Eq. 7,

@@ -91,11 +91,15 @@ class lagom_comp_model(C.Structure):
     _fields_ = [("mu", C.c_int64), ("tb", C.c_int32), ("d_bytes", C.c_double), ("theta_us", C.c_double)]
 
 
+class lagom_penalty(C.Structure):
+    _fields_ = [("nt", C.c_int32), ("rho", C.c_double)]
+
+
 class lagom_model(C.Structure):
     _fields_ = [("lambda_", C.c_int32), ("bw_peak", C.c_double), ("comps", C.POINTER(lagom_comp_model)),
                 ("ncomp", C.c_int32), ("tables", C.POINTER(lagom_comm_table)), ("ncomm", C.c_int32),
                 ("comp_after_comm", C.POINTER(C.c_int32)), ("comm_after_comp", C.POINTER(C.c_int32)),
-                ("corun_share", C.c_double)]
+                ("corun_share", C.c_double), ("penalty", C.POINTER(lagom_penalty)), ("npenalty", C.c_int32)]
 
 
 class lagom_pred(C.Structure):
@@ -141,7 +145,8 @@ class lagom_fill_desc(C.Structure):
 
 class lagom_calibration(C.Structure):
     _fields_ = [("sigma", C.c_double), ("theta_us", C.c_double), ("fit_mean", C.c_double), ("fit_max", C.c_double),
-                ("held_mean", C.c_double), ("held_max", C.c_double), ("n_fit", C.c_int32), ("n_held", C.c_int32)]
+                ("held_mean", C.c_double), ("held_max", C.c_double), ("n_fit", C.c_int32), ("n_held", C.c_int32),
+                ("npenalty", C.c_int32)]
 
 
 PROFILE_FN = C.CFUNCTYPE(C.c_int, C.c_void_p, C.POINTER(lagom_cfg), C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double))
@@ -190,6 +195,7 @@ def lib() -> C.CDLL:
                                        C.POINTER(C.c_double)]
         L.lagom_model_calibrate.argtypes = [C.POINTER(lagom_sweep_point), C.c_int, C.POINTER(C.c_uint8), C.POINTER(lagom_fill_desc),
                                             C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_double), C.c_int,
+                                            C.POINTER(C.c_double), C.c_int, C.POINTER(lagom_penalty), C.c_int,
                                             C.POINTER(lagom_calibration)]
         L.lagom_ladder_chunks.argtypes = [C.POINTER(C.c_int64), C.c_int, C.c_int32, C.c_int32, C.c_int64, C.c_int,
                                           C.POINTER(lagom_sweep_point), C.c_int, C.POINTER(C.c_int64), C.POINTER(C.c_int32)]
@@ -457,6 +463,7 @@ class Model:
     comp_after_comm: Optional[Sequence[int]] = None   # per computation: communication it waits for, or -1
     comm_after_comp: Optional[Sequence[int]] = None   # per communication: computation it waits for, or -1
     corun_share: float = 0.0                          # 0 = Eq. 5-6 as printed; see lagom_model in lagom.h
+    resident_penalty: dict = field(default_factory=dict)   # NT -> rho; empty = Eq. 6 as printed
 
 
 @dataclass
@@ -485,11 +492,14 @@ class _CModel:
         self.cac = (C.c_int32 * max(len(m.comps), 1))(*[int(v) for v in m.comp_after_comm]) if m.comp_after_comm is not None else None
         self.cap = (C.c_int32 * max(len(m.tables), 1))(*[int(v) for v in m.comm_after_comp]) if m.comm_after_comp is not None else None
         null = C.POINTER(C.c_int32)()
+        pen = list(m.resident_penalty.items())
+        self.pen = (lagom_penalty * max(len(pen), 1))(*[lagom_penalty(int(nt), float(rho)) for nt, rho in pen])
         self.c = lagom_model(int(m.lam), float(m.bw_peak), C.cast(self.comps, C.POINTER(lagom_comp_model)), len(m.comps),
                              C.cast(self.tables, C.POINTER(lagom_comm_table)), len(m.tables),
                              C.cast(self.cac, C.POINTER(C.c_int32)) if self.cac is not None else null,
                              C.cast(self.cap, C.POINTER(C.c_int32)) if self.cap is not None else null,
-                             float(m.corun_share))
+                             float(m.corun_share),
+                             C.cast(self.pen, C.POINTER(lagom_penalty)) if pen else C.POINTER(lagom_penalty)(), len(pen))
 
 
 def lagom_cost_model(model: Model, cfgs: Sequence[CfgLike]) -> Pred:
@@ -506,7 +516,8 @@ def lagom_cost_model(model: Model, cfgs: Sequence[CfgLike]) -> Pred:
 
 def lagom_model_fill(points: Sequence[SweepPoint], lam: int, bw_peak: float, mu: int, tb: int, d_bytes: float, ncomp: int,
                      comm_bytes: Sequence[float], held_out: Optional[Sequence[bool]] = None, v_cap_frac: float = 0.0,
-                     comp_after_comm=None, comm_after_comp=None, corun_share: float = 0.0) -> Tuple[Model, float]:
+                     comp_after_comm=None, comm_after_comp=None, corun_share: float = 0.0,
+                     resident_penalty: Optional[dict] = None) -> Tuple[Model, float]:
     """The model of one overlap group filled from a sweep; returns (model, t_alone_us)."""
     desc, keep = _fill_desc(lam, bw_peak, mu, tb, d_bytes, ncomp, comm_bytes, v_cap_frac)
     n, ncomm = len(points), len(comm_bytes)
@@ -521,7 +532,8 @@ def lagom_model_fill(points: Sequence[SweepPoint], lam: int, bw_peak: float, mu:
         py_tables.append({(tj.entries[e].cfg.nc, tj.entries[e].cfg.nt, tj.entries[e].cfg.chunk_bytes): (tj.entries[e].x_us, tj.entries[e].v)
                           for e in range(tj.n)})
     py_comps = [CompModel(c.mu, c.tb, c.d_bytes, c.theta_us) for c in comps[:ncomp]]
-    return Model(lam, bw_peak, py_comps, py_tables, comp_after_comm, comm_after_comp, corun_share), t_alone.value
+    return Model(lam, bw_peak, py_comps, py_tables, comp_after_comm, comm_after_comp, corun_share,
+                 dict(resident_penalty) if resident_penalty else {}), t_alone.value
 
 
 @dataclass
@@ -534,19 +546,27 @@ class Calibration:
     held_max: float
     n_fit: int
     n_held: int
+    penalty: Optional[dict] = None      # NT -> rho when candidate rhos were given
 
 
 def lagom_model_calibrate(points: Sequence[SweepPoint], lam: int, bw_peak: float, mu: int, tb: int, d_bytes: float, ncomp: int,
                           comm_bytes: Sequence[float], sigmas: Sequence[float], held_out: Optional[Sequence[bool]] = None,
-                          v_cap_frac: float = 0.0, comp_after_comm=None, comm_after_comp=None) -> Calibration:
+                          v_cap_frac: float = 0.0, comp_after_comm=None, comm_after_comp=None,
+                          rhos: Optional[Sequence[float]] = None) -> Calibration:
     desc, keep = _fill_desc(lam, bw_peak, mu, tb, d_bytes, ncomp, comm_bytes, v_cap_frac)
     n = len(points)
     cac = (C.c_int32 * max(ncomp, 1))(*[int(v) for v in comp_after_comm]) if comp_after_comm is not None else None
     cap = (C.c_int32 * max(len(comm_bytes), 1))(*[int(v) for v in comm_after_comp]) if comm_after_comp is not None else None
     sg = (C.c_double * max(len(sigmas), 1))(*[float(v) for v in sigmas])
     out = lagom_calibration()
-    _check(lib().lagom_model_calibrate(_sweep_array(points), n, _mask(held_out, n), C.byref(desc), cac, cap, sg, len(sigmas), C.byref(out)))
-    return Calibration(out.sigma, out.theta_us, out.fit_mean, out.fit_max, out.held_mean, out.held_max, out.n_fit, out.n_held)
+    nrho = len(rhos) if rhos else 0
+    rh = (C.c_double * max(nrho, 1))(*[float(v) for v in (rhos or [])])
+    room = len(set(int(tuple(p.cfg)[1]) for p in points)) if nrho else 0
+    pen = (lagom_penalty * max(room, 1))()
+    _check(lib().lagom_model_calibrate(_sweep_array(points), n, _mask(held_out, n), C.byref(desc), cac, cap, sg, len(sigmas),
+                                       rh if nrho else None, nrho, pen if nrho else None, room, C.byref(out)))
+    penalty = {pen[e].nt: pen[e].rho for e in range(out.npenalty)} if nrho else None
+    return Calibration(out.sigma, out.theta_us, out.fit_mean, out.fit_max, out.held_mean, out.held_max, out.n_fit, out.n_held, penalty)
 
 
 # ------------------------------------------------------------------------ tuner (host)

@@ -7,7 +7,7 @@
 
 namespace {
 
-struct CommPoint { double x, v; int nc; };
+struct CommPoint { double x, v; int nc; double pf; };   // pf = 1 + rho of the communication's thread count
 
 int lookup(const lagom_comm_table& t, const lagom_cfg& c, int j, CommPoint* out) {
     if (t.n < 0 || (t.n > 0 && !t.entries)) return lagom::fail(LAGOM_EINVAL, "communication %d: bad table", j);
@@ -47,10 +47,16 @@ extern "C" int lagom_cost_model(const lagom_model* m, const lagom_cfg* cfgs, int
     if (m->lambda < 1 || !(m->bw_peak > 0.0)) return lagom::fail(LAGOM_EINVAL, "lambda and peak bandwidth must be positive");
     if (!(m->corun_share >= 0.0 && m->corun_share <= 1.0)) return lagom::fail(LAGOM_EINVAL, "corun_share must lie in [0, 1]");
 
+    if (m->npenalty < 0 || (m->npenalty > 0 && !m->penalty)) return lagom::fail(LAGOM_EINVAL, "bad penalty array");
+    for (int e = 0; e < m->npenalty; ++e)
+        if (!(m->penalty[e].rho >= 0.0)) return lagom::fail(LAGOM_EINVAL, "penalty %d: rho must be non-negative", e);
     const int N = ncomm;
     std::vector<CommPoint> c(N);
     for (int j = 0; j < N; ++j) {
         if (int rc = lookup(m->tables[j], cfgs[j], j, &c[j])) return rc;
+        c[j].pf = 1.0;
+        for (int e = 0; e < m->npenalty; ++e)
+            if (m->penalty[e].nt == cfgs[j].nt) { c[j].pf = 1.0 + m->penalty[e].rho; break; }
         if (c[j].nc < 1 || c[j].nc >= m->lambda)
             return lagom::fail(LAGOM_EINVAL, "communication %d: NC=%d outside 1..lambda-1", j, c[j].nc);
         if (!(c[j].v >= 0.0 && c[j].v < m->bw_peak))
@@ -87,6 +93,7 @@ extern "C" int lagom_cost_model(const lagom_model* m, const lagom_cfg* cfgs, int
                 if (slot < N) {
                     cap = in_flight(m->lambda, c[slot].nc, cp.tb, m->corun_share);
                     f[slot] = wave_time(cp.theta_us, cap, cp.d_bytes, m->bw_peak, c[slot].v);
+                    if (c[slot].pf != 1.0) f[slot] = f[slot] * c[slot].pf;
                 } else {
                     cap = (int64_t)m->lambda * cp.tb;
                     f[slot] = wave_time(cp.theta_us, cap, cp.d_bytes, m->bw_peak, 0.0);
@@ -155,6 +162,7 @@ extern "C" int lagom_cost_model(const lagom_model* m, const lagom_cfg* cfgs, int
                         if (slot < N) {
                             cap = in_flight(m->lambda, c[slot].nc, cp.tb, m->corun_share);
                             f[slot] = wave_time(cp.theta_us, cap, cp.d_bytes, m->bw_peak, c[slot].v);
+                            if (c[slot].pf != 1.0) f[slot] = f[slot] * c[slot].pf;
                         } else {
                             cap = (int64_t)m->lambda * cp.tb;
                             f[slot] = wave_time(cp.theta_us, cap, cp.d_bytes, m->bw_peak, 0.0);

@@ -79,8 +79,11 @@ extern "C" int lagom_model_fill(const lagom_sweep_point* pts, int npts, const ui
 
 extern "C" int lagom_model_calibrate(const lagom_sweep_point* pts, int npts, const uint8_t* held_out, const lagom_fill_desc* d,
                                      const int32_t* comp_after_comm, const int32_t* comm_after_comp,
-                                     const double* sigmas, int nsigma, lagom_calibration* out) {
+                                     const double* sigmas, int nsigma,
+                                     const double* rhos, int nrho, lagom_penalty* penalty_out, int penalty_capacity,
+                                     lagom_calibration* out) {
     if (!out || !sigmas || nsigma < 1) return lagom::fail(LAGOM_EINVAL, "null output or no candidate sigma");
+    if (nrho < 0 || (nrho > 0 && (!rhos || !penalty_out))) return lagom::fail(LAGOM_EINVAL, "candidate penalties without an array for them or for the result");
     if (!pts || npts < 1) return lagom::fail(LAGOM_EINVAL, "no sweep points");
     if (int rc = check_desc(d)) return rc;
     std::vector<lagom_table_entry> entries((size_t)d->ncomm * npts);
@@ -94,12 +97,14 @@ extern "C" int lagom_model_calibrate(const lagom_sweep_point* pts, int npts, con
     m.comp_after_comm = comp_after_comm; m.comm_after_comp = comm_after_comp;
     std::vector<lagom_cfg> cfgs(d->ncomm);
     // mean and maximum of |Y_model - Y_measured| / Y_measured over the points with held_out == which
-    auto errors = [&](int which, double* mean, double* worst, int* count) -> int {
+    // (and, for only_nt > 0, with that thread count)
+    auto errors = [&](int which, double* mean, double* worst, int* count, int only_nt = 0) -> int {
         double total = 0.0, w = 0.0;
         int n = 0;
         for (int p = 0; p < npts; ++p) {
             const int h = held_out && held_out[p] ? 1 : 0;
             if (h != which) continue;
+            if (only_nt > 0 && pts[p].cfg.nt != only_nt) continue;
             if (!(pts[p].comp_corun_us > 0.0)) return lagom::fail(LAGOM_EINVAL, "sweep point %d: co-run computation time must be positive", p);
             std::fill(cfgs.begin(), cfgs.end(), pts[p].cfg);
             lagom_pred pr{};
@@ -124,6 +129,34 @@ extern "C" int lagom_model_calibrate(const lagom_sweep_point* pts, int npts, con
         if (!have || mean < best.fit_mean) { best.sigma = sigmas[s]; best.fit_mean = mean; best.fit_max = worst; best.n_fit = n; have = true; }
     }
     m.corun_share = best.sigma;
+    if (nrho > 0) {
+        // the thread counts among the fitted points, ascending
+        std::vector<int> nts;
+        for (int p = 0; p < npts; ++p)
+            if (!(held_out && held_out[p])) nts.push_back(pts[p].cfg.nt);
+        std::sort(nts.begin(), nts.end());
+        nts.erase(std::unique(nts.begin(), nts.end()), nts.end());
+        if ((int)nts.size() > penalty_capacity) return lagom::fail(LAGOM_EINVAL, "%d thread counts, room for %d penalties", (int)nts.size(), penalty_capacity);
+        m.penalty = penalty_out;
+        m.npenalty = 0;
+        for (int nt : nts) {
+            const int slot = m.npenalty;
+            m.npenalty = slot + 1;
+            penalty_out[slot].nt = nt;
+            bool have_rho = false;
+            double best_mean = 0.0, best_rho = 0.0;
+            for (int r = 0; r < nrho; ++r) {
+                if (!(rhos[r] >= 0.0)) return lagom::fail(LAGOM_EINVAL, "candidate rho %d is negative", r);
+                penalty_out[slot].rho = rhos[r];
+                double mean, worst; int n;
+                if (int rc = errors(0, &mean, &worst, &n, nt)) return rc;
+                if (!have_rho || mean < best_mean) { best_mean = mean; best_rho = rhos[r]; have_rho = true; }
+            }
+            penalty_out[slot].rho = best_rho;
+        }
+        best.npenalty = m.npenalty;
+        if (int rc = errors(0, &best.fit_mean, &best.fit_max, &best.n_fit)) return rc;
+    }
     if (int rc = errors(1, &best.held_mean, &best.held_max, &best.n_held)) return rc;
     best.theta_us = comps[0].theta_us;
     *out = best;

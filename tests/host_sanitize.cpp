@@ -99,13 +99,19 @@ int main() {
         double t_alone = 0.0;
         if (lagom_model_fill(pts.data(), P, held.data(), &fd, fe.data(), ft.data(), fc.data(), &t_alone) != LAGOM_OK) { std::printf("fill failed: %s\n", lagom_last_error()); ++bad; }
         if (lagom_model_fill(pts.data(), P, nullptr, &fd, fe.data(), ft.data(), fc.data(), nullptr) != LAGOM_OK) ++bad;
-        lagom_model fm{256, 8.0e6, fc.data(), M, ft.data(), N, nullptr, nullptr, 0.25};
+        const lagom_penalty fixed_pen[2] = {{nt[0], 0.05}, {nt.back(), 0.2}};
+        lagom_model fm{256, 8.0e6, fc.data(), M, ft.data(), N, nullptr, nullptr, 0.25, fixed_pen, 2};
         if (lagom_tune(sp.data(), N, lagom_model_profile, &fm, LAGOM_HIDE_COMM, out.data(), nullptr) != LAGOM_OK) ++bad;
         const double sig[3] = {0.0, 0.5, 1.0};
         lagom_calibration cal{};
-        if (lagom_model_calibrate(pts.data(), P, held.data(), &fd, dep ? cac.data() : nullptr, dep ? cap.data() : nullptr, sig, 3, &cal) != LAGOM_OK) { std::printf("calibrate failed: %s\n", lagom_last_error()); ++bad; }
+        if (lagom_model_calibrate(pts.data(), P, held.data(), &fd, dep ? cac.data() : nullptr, dep ? cap.data() : nullptr, sig, 3, nullptr, 0, nullptr, 0, &cal) != LAGOM_OK) { std::printf("calibrate failed: %s\n", lagom_last_error()); ++bad; }
         if (cal.n_fit + cal.n_held != P) ++bad;
-        if (lagom_model_calibrate(pts.data(), P, held.data(), &fd, nullptr, nullptr, sig, 0, &cal) != LAGOM_EINVAL) ++bad;
+        const double rho[3] = {0.0, 0.1, 0.3};
+        std::vector<lagom_penalty> pen(nt.size());
+        if (lagom_model_calibrate(pts.data(), P, held.data(), &fd, dep ? cac.data() : nullptr, dep ? cap.data() : nullptr, sig, 3, rho, 3, pen.data(), (int)pen.size(), &cal) != LAGOM_OK) { std::printf("calibrate with penalties failed: %s\n", lagom_last_error()); ++bad; }
+        if (cal.npenalty < 1 || cal.npenalty > (int)nt.size()) ++bad;
+        if (nt.size() > 1 && lagom_model_calibrate(pts.data(), P, nullptr, &fd, nullptr, nullptr, sig, 3, rho, 3, pen.data(), 1, &cal) != LAGOM_EINVAL) ++bad;
+        if (lagom_model_calibrate(pts.data(), P, held.data(), &fd, nullptr, nullptr, sig, 0, nullptr, 0, nullptr, 0, &cal) != LAGOM_EINVAL) ++bad;
         std::vector<uint8_t> all_held(P, 1);
         if (lagom_model_fill(pts.data(), P, all_held.data(), &fd, fe.data(), ft.data(), fc.data(), nullptr) != LAGOM_EINVAL) ++bad;
         if (lagom_model_fill(pts.data(), 0, nullptr, &fd, fe.data(), ft.data(), fc.data(), nullptr) != LAGOM_EINVAL) ++bad;

@@ -143,6 +143,36 @@ def test_cost_model_with_a_corun_share_equals_oracle_bit_for_bit(golden_dir):
         assert e.value.code == lg.LAGOM_EINVAL
 
 
+def test_cost_model_with_a_resident_penalty_equals_oracle_bit_for_bit(golden_dir):
+    rng = np.random.default_rng(13)
+    for trial in range(300):
+        N, M = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+        mo, ml, cfgs = _random_model(rng, N, M)
+        mo.corun_share = ml.corun_share = float(rng.choice([0.0, 0.25, rng.uniform(0, 1)]))
+        pen = {int(nt): float(rng.choice([0.0, 0.05, rng.uniform(0, 0.5)])) for nt in rng.choice([128, 256, 512], size=int(rng.integers(0, 3)), replace=False)}
+        mo.resident_penalty, ml.resident_penalty = dict(pen), dict(pen)
+        if trial % 3 == 0:
+            mo_dep = [int(rng.integers(-1, min(i + 1, N))) for i in range(M)]
+            ml.comp_after_comm = mo_dep
+            po = ocm.predict(mo, cfgs, mo_dep, None)
+        else:
+            po = ocm.predict(mo, cfgs)
+        pl = lg.lagom_cost_model(ml, cfgs)
+        assert pl.x_us == po.x and pl.y_us == po.y and pl.g == po.g
+        assert (pl.X_us, pl.Y_us, pl.Z_us) == (po.X, po.Y, po.Z)
+    fx = json.load(open(os.path.join(golden_dir, "cost_model_worked.json")))
+    for case in fx["resident_penalty_cases"]:
+        tables = [{(c["nc"], 256, 65536): (c["x"], c["v"])} for c in case["comms"]]
+        model = lg.Model(fx["lambda"], fx["bw_peak"], [lg.CompModel(c["mu"], c["tb"], c["d_bytes"], c["theta"]) for c in case["comps"]],
+                         tables, corun_share=case["corun_share"], resident_penalty={int(k): v for k, v in case["penalty"].items()})
+        p = lg.lagom_cost_model(model, [(c["nc"], 256, 65536) for c in case["comms"]])
+        assert p.y_us == case["y"] and p.g == case["g"] and (p.X_us, p.Y_us, p.Z_us) == (case["X"], case["Y"], case["Z"])
+    for bad in (-0.1, float("nan")):
+        with pytest.raises(lg.LagomError) as e:
+            lg.lagom_cost_model(lg.Model(8, 100.0, [lg.CompModel(10, 1, 1.0, 1.0)], [{(2, 64, 64): (1.0, 1.0)}], resident_penalty={64: bad}), [(2, 64, 64)])
+        assert e.value.code == lg.LAGOM_EINVAL
+
+
 def test_cost_model_on_the_hand_worked_fixture(golden_dir):
     fx = json.load(open(os.path.join(golden_dir, "cost_model_worked.json")))
     for case in fx["cases"]:
@@ -470,11 +500,31 @@ def test_model_calibrate_equals_oracle_bit_for_bit():
                                       comp_after_comm=cac, comm_after_comp=cap)
         assert (cl.sigma, cl.fit_mean, cl.fit_max, cl.held_mean, cl.held_max, cl.n_fit, cl.n_held) == \
             (co.sigma, co.fit_mean, co.fit_max, co.held_mean, co.held_max, co.n_fit, co.n_held)
+    # with the resident penalty calibrated after sigma
+    rhos = [0.0, 0.02, 0.05, 0.1, 0.2, 0.4]
+    for trial in range(80):
+        lam, bw, geo, ncomp, nbytes, pts, opts = _fill_case(rng)
+        held = [i % 3 == 1 for i in range(len(pts))] if trial % 2 else None
+        cac = cap = None
+        if trial % 4 == 0:
+            cac = [int(rng.integers(-1, min(i + 1, len(nbytes)))) for i in range(ncomp)]
+            cap = [int(rng.integers(-1, min(j, ncomp))) if j > 0 else -1 for j in range(len(nbytes))]
+        co = omf.calibrate(opts, held, geo, ncomp, nbytes, lam, bw, sigmas, cac, cap, rhos=rhos)
+        cl = lg.lagom_model_calibrate(pts, lam, bw, geo.mu, geo.tb, geo.d_bytes, ncomp, nbytes, sigmas, held,
+                                      comp_after_comm=cac, comm_after_comp=cap, rhos=rhos)
+        assert (cl.sigma, cl.fit_mean, cl.fit_max, cl.held_mean, cl.held_max, cl.n_fit, cl.n_held) == \
+            (co.sigma, co.fit_mean, co.fit_max, co.held_mean, co.held_max, co.n_fit, co.n_held)
+        assert cl.penalty == co.penalty and list(cl.penalty) == sorted(cl.penalty)
     # the pencil-worked case
     fit = lg.SweepPoint((2, 64, 16), 0.0, 1000.0, 330.0, 400.0, 0.0, 0.0, 10.0)
     held = lg.SweepPoint((1, 64, 16), 0.0, 1000.0, 500.0, 350.0, 0.0, 0.0, 20.0)
     c = lg.lagom_model_calibrate([fit, held], 4, 100.0, 20, 2, 1000.0, 1, [4000.0], [0.0, 0.5, 1.0], [False, True])
     assert c.sigma == 0.5 and c.theta_us == 30.0 and c.fit_mean == pytest.approx(1 / 30, rel=1e-12)
     assert c.held_mean == pytest.approx(2.5 / 350, rel=1e-12)
+    c = lg.lagom_model_calibrate([fit, held], 4, 100.0, 20, 2, 1000.0, 1, [4000.0], [0.0, 0.5, 1.0], [False, True], rhos=[0.0, 0.05, 0.1])
+    assert c.sigma == 0.5 and c.penalty == {64: 0.05}
+    assert c.fit_mean == pytest.approx(6 / 400, rel=1e-12) and c.held_mean == pytest.approx(20.125 / 350, rel=1e-12)
     with pytest.raises(lg.LagomError):
         lg.lagom_model_calibrate([fit], 4, 100.0, 20, 2, 1000.0, 1, [4000.0], [1.5])
+    with pytest.raises(lg.LagomError):
+        lg.lagom_model_calibrate([fit], 4, 100.0, 20, 2, 1000.0, 1, [4000.0], [0.5], rhos=[-0.5])
