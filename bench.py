@@ -319,10 +319,33 @@ def run_config(name, args, s_comm, s_comp, dependent=False):
                                        comm_after_comp=dep_comm, **fill_args)
     cal_printed = lg.lagom_model_calibrate(usable, d_bytes=geo.d_bytes, sigmas=[0.0], held_out=held,
                                            comp_after_comm=dep_arg, comm_after_comp=dep_comm, **fill_args)
+    # the resident penalty rho(NT), calibrated after sigma on the same halves
+    rhos = [0.0, 0.01, 0.02, 0.03, 0.04, 0.05, 0.06, 0.08, 0.1, 0.125, 0.15, 0.2, 0.25, 0.3, 0.4, 0.5]
+    cal_pen = lg.lagom_model_calibrate(usable, d_bytes=geo.d_bytes_past_l2, sigmas=sigmas, held_out=held, rhos=rhos,
+                                       comp_after_comm=dep_arg, comm_after_comp=dep_comm, **fill_args)
+    cal_pen_all = lg.lagom_model_calibrate(usable, d_bytes=geo.d_bytes_past_l2, sigmas=sigmas, rhos=rhos,
+                                           comp_after_comm=dep_arg, comm_after_comp=dep_comm, **fill_args)
     model, _ = lg.lagom_model_fill(usable, d_bytes=geo.d_bytes_past_l2, comp_after_comm=dep_arg, comm_after_comp=dep_comm,
                                    corun_share=cal_all.sigma, **fill_args)
+    model_pen, _ = lg.lagom_model_fill(usable, d_bytes=geo.d_bytes_past_l2, comp_after_comm=dep_arg, comm_after_comp=dep_comm,
+                                       corun_share=cal_pen_all.sigma, resident_penalty=cal_pen_all.penalty, **fill_args)
     model_printed, _ = lg.lagom_model_fill(usable, d_bytes=geo.d_bytes, comp_after_comm=dep_arg, comm_after_comp=dep_comm,
                                            corun_share=0.0, **fill_args)
+
+    # which uniform configuration each model would pick among the swept ones, and what that pick measured
+    def uniform_pick(mdl):
+        z_of = {tuple(p.cfg): lg.lagom_cost_model(mdl, [tuple(p.cfg)] * ncomm).Z_us for p in usable}
+        pick = min(usable, key=lambda p: z_of[tuple(p.cfg)])
+        best = min(usable, key=lambda p: p.z_corun_us)
+        order_m = sorted(usable, key=lambda p: z_of[tuple(p.cfg)])
+        order_z = sorted(usable, key=lambda p: p.z_corun_us)
+        rank = {tuple(p.cfg): i for i, p in enumerate(order_z)}
+        return {"cfg": list(pick.cfg), "z_model_us": z_of[tuple(pick.cfg)], "z_measured_us": pick.z_corun_us,
+                "best_measured_cfg": list(best.cfg), "z_best_measured_us": best.z_corun_us,
+                "pick_over_best": pick.z_corun_us / best.z_corun_us, "rank_of_pick": rank[tuple(pick.cfg)], "of": len(usable),
+                "z_err_mean": float(np.mean([abs(z_of[tuple(p.cfg)] - p.z_corun_us) / p.z_corun_us for p in usable])),
+                "top5_overlap": len(set(tuple(p.cfg) for p in order_m[:5]) & set(tuple(p.cfg) for p in order_z[:5]))}
+    uniform_picks = {"as_printed": uniform_pick(model_printed), "sigma": uniform_pick(model), "sigma_and_rho": uniform_pick(model_pen)}
 
     # ---- ladders (lagom_ladder_chunks): the cut ladder is the graded one; the uncut and the fixed-chunk ones beside it
     def spaces_for(nc_grid, kind, pts, nt=None):
@@ -384,6 +407,13 @@ def run_config(name, args, s_comm, s_comp, dependent=False):
     tuned_model = lg.lagom_tune(spaces, model, lg.LAGOM_PRIORITY) if in_tables(spaces) else None
     model_tune_us = (time.perf_counter() - t0) * 1e6
     tuned_printed = lg.lagom_tune(spaces, model_printed, lg.LAGOM_PRIORITY) if in_tables(spaces) else None
+    # the model with the resident penalty as ProfileTime over the extended ladders
+    model_pen_searches = {}
+    for label, sp, mode in (("model_rho_priority_extended", spaces_ext, lg.LAGOM_PRIORITY),
+                            ("model_rho_free_steps_extended", spaces_ext, lg.LAGOM_PRIORITY_FREE),
+                            ("model_rho_free_steps_extended_nt_min", spaces_ext_ntmin, lg.LAGOM_PRIORITY_FREE)):
+        if in_tables(sp):
+            model_pen_searches[label] = lg.lagom_tune(sp, model_pen, mode)
 
     # ---- the first three pairs of the chain: priority search against exhaustive search over the same ladder
     first3 = None
@@ -423,7 +453,11 @@ def run_config(name, args, s_comm, s_comp, dependent=False):
     best_sweep = min(sweep, key=lambda p: p.z_corun_us)
     best_sweep_ext = min(all_sweep, key=lambda p: p.z_corun_us)
     comm_opt = min(sweep, key=lambda p: p.comm_alone_us)
-    cands = {"default": [DEFAULT_CFG] * ncomm, "tuned": tuned.cfgs, "tuned_uncut_ladder": tuned_full.cfgs,
+    # a second default: the library default's chunk clamped so that its eight channels all have a chunk of every launch
+    clamped = [(DEFAULT_CFG[0], DEFAULT_CFG[1], min(DEFAULT_CFG[2], lg.lagom_ladder_chunks(list(w.chunk_grid) + ([DEFAULT_CFG[2]] if DEFAULT_CFG[2] > max(w.chunk_grid) else []),
+                                                                                               DEFAULT_CFG[0], DEFAULT_CFG[1], per_src[j], lg.LAGOM_LADDER_CUT)[-1]))
+               for j in range(ncomm)]
+    cands = {"default": [DEFAULT_CFG] * ncomm, "default_chunk_clamped": clamped, "tuned": tuned.cfgs, "tuned_uncut_ladder": tuned_full.cfgs,
              "tuned_fixed_chunk": tuned_fixed.cfgs, "comm_descent": comm_cd.cfgs, "hide_comm": hide.cfgs,
              "best_swept": [best_sweep.cfg] * ncomm, "comm_optimal": [comm_opt.cfg] * ncomm,
              "tuned_free_steps": tuned_free.cfgs,
@@ -438,6 +472,9 @@ def run_config(name, args, s_comm, s_comp, dependent=False):
     if tuned_model is not None:
         cands["model_tuned"] = tuned_model.cfgs
         cands["printed_model_tuned"] = tuned_printed.cfgs
+    cands["model_rho_uniform_pick"] = [tuple(uniform_picks["sigma_and_rho"]["cfg"])] * ncomm
+    for label, r in model_pen_searches.items():
+        cands[label] = r.cfgs
     # the same parameters with every launch of a communication issued on its own (no lagom_comm_steps)
     separate = None
     if any(l.fuse for l in launches):
@@ -494,6 +531,8 @@ def run_config(name, args, s_comm, s_comp, dependent=False):
         "gemm": f"{M}x{N}x{K} bf16 x{len(comps)}", "dependent": dependent,
         "speedup_tuned_vs_default": results["tuned"]["speedup_vs_default"], "verdict": results["tuned"]["verdict"],
         "z_default_us": results["default"]["z_us"], "z_tuned_us": results["tuned"]["z_us"],
+        "z_default_chunk_clamped_us": results["default_chunk_clamped"]["z_us"],
+        "speedup_tuned_vs_default_chunk_clamped": results["default_chunk_clamped"]["z_us"] / results["tuned"]["z_us"],
         "z_comm_descent_us": results["comm_descent"]["z_us"], "z_best_swept_us": results["best_swept"]["z_us"],
         "z_tuned_free_steps_us": results["tuned_free_steps"]["z_us"],
         "z_tuned_extended_us": results["tuned_extended"]["z_us"], "z_tuned_free_steps_extended_us": results["tuned_free_steps_extended"]["z_us"],
@@ -509,6 +548,16 @@ def run_config(name, args, s_comm, s_comp, dependent=False):
                   "y_err_all_points": [cal_all.fit_mean, cal_all.fit_max],
                   "held_out": {"sigma_fitted_on_half": cal.sigma, "fit_half": [cal.fit_mean, cal.fit_max],
                                "held_half": [cal.held_mean, cal.held_max], "n_fit": cal.n_fit, "n_held": cal.n_held},
+                  "resident_penalty": {"rho_by_nt": {str(k): v for k, v in cal_pen_all.penalty.items()}, "sigma": cal_pen_all.sigma,
+                                       "y_err_all_points": [cal_pen_all.fit_mean, cal_pen_all.fit_max],
+                                       "rho_fitted_on_half": {str(k): v for k, v in cal_pen.penalty.items()},
+                                       "fit_half": [cal_pen.fit_mean, cal_pen.fit_max],
+                                       "held_half": [cal_pen.held_mean, cal_pen.held_max]},
+                  "uniform_pick_among_swept": uniform_picks,
+                  "searches_with_rho": {k: {"cfgs": [list(c) for c in r.cfgs], "calls": r.calls, "predicted_z_us": r.Z,
+                                            "measured_z_us": results[k]["z_us"],
+                                            "speedup_vs_default": results[k]["speedup_vs_default"]}
+                                        for k, r in model_pen_searches.items()},
                   "as_printed": {"d_bytes": geo.d_bytes, "theta_us": cal_printed.theta_us,
                                  "fit_half": [cal_printed.fit_mean, cal_printed.fit_max],
                                  "held_half": [cal_printed.held_mean, cal_printed.held_max]},

@@ -152,10 +152,13 @@ def test_gemm_b_kn_full_size_sampled_rows():
     b = inputs.normal_bf16(3, (K, N), scale=0.02)
     got = _gemm(a, b, False, "bf16")
     rng = np.random.default_rng(11)
-    rows = np.unique(np.concatenate([rng.integers(0, M, size=32), np.arange(0, 2), np.arange(M - 2, M)]))
+    rows = np.unique(np.concatenate([rng.integers(0, M, size=64), np.arange(0, 4), np.arange(M - 4, M)]))
     ref = og.gemm_f64(a, b, False, rows=rows)
     e_max, e_fro = og.rel_errors(got[rows], ref)
     assert e_max <= GATE and e_fro <= GATE, (e_max, e_fro)
+    corners = ref[:, np.r_[0:32, N - 32:N]]
+    e_max, e_fro = og.rel_errors(got[rows][:, np.r_[0:32, N - 32:N]], corners)
+    assert e_max <= GATE and e_fro <= GATE
 
 
 def test_b_kn_layout_rejects_unaligned_n():

@@ -107,12 +107,15 @@ def test_model_filled_from_a_measured_sweep_equals_the_oracle(chain):
     sigmas = [i / 8 for i in range(9)]
     opts = [omf.SweepPoint(p.cfg, p.comm_corun_us, p.comp_alone_us, p.comp_corun_us, p.v_corun) for p in sweep]
     ogeo = omf.Geometry(geo.mu, geo.tb, geo.d_bytes_past_l2)
-    co = omf.calibrate(opts, held, ogeo, ncomp, nbytes, lam, bw, sigmas)
-    cl = lg.lagom_model_calibrate(sweep, lam, bw, geo.mu, geo.tb, geo.d_bytes_past_l2, ncomp, nbytes, sigmas, held)
-    assert (cl.sigma, cl.fit_mean, cl.fit_max, cl.held_mean, cl.held_max, cl.n_fit, cl.n_held) == \
-        (co.sigma, co.fit_mean, co.fit_max, co.held_mean, co.held_max, co.n_fit, co.n_held)
-    ml, t_alone = lg.lagom_model_fill(sweep, lam, bw, geo.mu, geo.tb, geo.d_bytes_past_l2, ncomp, nbytes, corun_share=cl.sigma)
-    mo = omf.fill(opts, ogeo, ncomp, nbytes, lam, bw, co.sigma)
+    rhos = [0.0, 0.02, 0.05, 0.1, 0.2, 0.4]
+    for use_rhos in (None, rhos):
+        co = omf.calibrate(opts, held, ogeo, ncomp, nbytes, lam, bw, sigmas, rhos=use_rhos)
+        cl = lg.lagom_model_calibrate(sweep, lam, bw, geo.mu, geo.tb, geo.d_bytes_past_l2, ncomp, nbytes, sigmas, held, rhos=use_rhos)
+        assert (cl.sigma, cl.fit_mean, cl.fit_max, cl.held_mean, cl.held_max, cl.n_fit, cl.n_held, cl.penalty) == \
+            (co.sigma, co.fit_mean, co.fit_max, co.held_mean, co.held_max, co.n_fit, co.n_held, co.penalty)
+    ml, t_alone = lg.lagom_model_fill(sweep, lam, bw, geo.mu, geo.tb, geo.d_bytes_past_l2, ncomp, nbytes, corun_share=cl.sigma,
+                                      resident_penalty=cl.penalty)
+    mo = omf.fill(opts, ogeo, ncomp, nbytes, lam, bw, co.sigma, penalty=co.penalty)
     assert ml.tables == mo.tables and [c.theta_us for c in ml.comps] == [c.theta for c in mo.comps]
     rng = np.random.default_rng(5)
     for _ in range(50):
