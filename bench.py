@@ -408,10 +408,14 @@ def run_config(name, args, s_comm, s_comp, dependent=False):
     model_tune_us = (time.perf_counter() - t0) * 1e6
     tuned_printed = lg.lagom_tune(spaces, model_printed, lg.LAGOM_PRIORITY) if in_tables(spaces) else None
     # the model with the resident penalty as ProfileTime over the extended ladders
+    # (Eq. 5 needs NC < lambda, so these ladders end below it)
     model_pen_searches = {}
-    for label, sp, mode in (("model_rho_priority_extended", spaces_ext, lg.LAGOM_PRIORITY),
-                            ("model_rho_free_steps_extended", spaces_ext, lg.LAGOM_PRIORITY_FREE),
-                            ("model_rho_free_steps_extended_nt_min", spaces_ext_ntmin, lg.LAGOM_PRIORITY_FREE)):
+    nc_model = [n for n in ext_nc if n < LAMBDA]
+    sp_model = spaces_for(nc_model, lg.LAGOM_LADDER_FIXED_CHUNK, all_sweep)
+    sp_model_ntmin = spaces_for(nc_model, lg.LAGOM_LADDER_FIXED_CHUNK, all_sweep, [min(nt_all)])
+    for label, sp, mode in (("model_rho_priority_extended", sp_model, lg.LAGOM_PRIORITY),
+                            ("model_rho_free_steps_extended", sp_model, lg.LAGOM_PRIORITY_FREE),
+                            ("model_rho_free_steps_extended_nt_min", sp_model_ntmin, lg.LAGOM_PRIORITY_FREE)):
         if in_tables(sp):
             model_pen_searches[label] = lg.lagom_tune(sp, model_pen, mode)
 
