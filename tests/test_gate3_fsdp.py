@@ -22,22 +22,24 @@ def table(golden_dir):
     return t
 
 
-def _models(t, d_key, sigmas):
+def _models(t, d_key, sigmas, rhos=None):
     geo, lam, bw = t["geometry"], t["lambda"], t["bw_peak_bytes_per_us"]
     usable = [p for p in t["points"] if p["cfg"][0] < lam]
     lpts = [lg.SweepPoint(tuple(p["cfg"]), p["comm_alone_us"], p["comm_corun_us"], p["comp_alone_us"], p["comp_corun_us"],
                           p["z_corun_us"], p["v_alone"], p["v_corun"]) for p in usable]
     opts = [omf.SweepPoint(tuple(p["cfg"]), p["comm_corun_us"], p["comp_alone_us"], p["comp_corun_us"], p["v_corun"]) for p in usable]
     ogeo = omf.Geometry(geo["mu"], geo["tb"], geo[d_key])
-    cl = lg.lagom_model_calibrate(lpts, lam, bw, geo["mu"], geo["tb"], geo[d_key], t["ncomp"], t["bytes_per_comm"], sigmas)
-    co = omf.calibrate(opts, None, ogeo, t["ncomp"], t["bytes_per_comm"], lam, bw, sigmas)
-    assert (cl.sigma, cl.fit_mean, cl.fit_max) == (co.sigma, co.fit_mean, co.fit_max)
-    ml, _ = lg.lagom_model_fill(lpts, lam, bw, geo["mu"], geo["tb"], geo[d_key], t["ncomp"], t["bytes_per_comm"], corun_share=cl.sigma)
-    mo = omf.fill(opts, ogeo, t["ncomp"], t["bytes_per_comm"], lam, bw, co.sigma)
+    cl = lg.lagom_model_calibrate(lpts, lam, bw, geo["mu"], geo["tb"], geo[d_key], t["ncomp"], t["bytes_per_comm"], sigmas,
+                                  rhos=rhos)
+    co = omf.calibrate(opts, None, ogeo, t["ncomp"], t["bytes_per_comm"], lam, bw, sigmas, rhos=rhos)
+    assert (cl.sigma, cl.fit_mean, cl.fit_max, cl.penalty) == (co.sigma, co.fit_mean, co.fit_max, co.penalty)
+    ml, _ = lg.lagom_model_fill(lpts, lam, bw, geo["mu"], geo["tb"], geo[d_key], t["ncomp"], t["bytes_per_comm"], corun_share=cl.sigma,
+                                resident_penalty=cl.penalty)
+    mo = omf.fill(opts, ogeo, t["ncomp"], t["bytes_per_comm"], lam, bw, co.sigma, penalty=co.penalty)
     assert ml.tables == mo.tables
     # the first three pairs
-    ml3 = lg.Model(ml.lam, ml.bw_peak, ml.comps[:3], ml.tables[:3], corun_share=ml.corun_share)
-    mo3 = ocm.Model(mo.lam, mo.bw_peak, mo.comps[:3], mo.tables[:3], corun_share=mo.corun_share)
+    ml3 = lg.Model(ml.lam, ml.bw_peak, ml.comps[:3], ml.tables[:3], corun_share=ml.corun_share, resident_penalty=ml.resident_penalty)
+    mo3 = ocm.Model(mo.lam, mo.bw_peak, mo.comps[:3], mo.tables[:3], corun_share=mo.corun_share, resident_penalty=mo.resident_penalty)
     return ml3, mo3, cl
 
 
@@ -48,10 +50,11 @@ def _ladder(t):
     return t["nc_grid"][:6], chunks[:6]
 
 
-@pytest.mark.parametrize("which", ["calibrated", "as_printed"])
+@pytest.mark.parametrize("which", ["calibrated", "calibrated_with_penalty", "as_printed"])
 def test_priority_against_brute_force_on_the_first_three_pairs(table, which):
-    sigmas = [i / 8 for i in range(9)] if which == "calibrated" else [0.0]
-    ml3, mo3, cal = _models(table, "d_bytes_past_l2" if which == "calibrated" else "d_bytes", sigmas)
+    sigmas = [i / 8 for i in range(9)] if which != "as_printed" else [0.0]
+    rhos = [0.0, 0.02, 0.05, 0.1, 0.15, 0.2, 0.3] if which == "calibrated_with_penalty" else None
+    ml3, mo3, cal = _models(table, "d_bytes_past_l2" if which != "as_printed" else "d_bytes", sigmas, rhos)
     nc, chunks = _ladder(table)
     sl = [lg.Space(nc, [256], chunks) for _ in range(3)]
     so = [osr.Space(nc, [256], chunks) for _ in range(3)]
@@ -68,7 +71,7 @@ def test_priority_against_brute_force_on_the_first_three_pairs(table, which):
     assert ex.Z <= pr.Z and ex.Z <= fr.Z                       # brute force is the lower bound
     gap, gap_free = pr.Z / ex.Z - 1.0, fr.Z / ex.Z - 1.0
     same = sorted(pr.cfgs) == sorted(ex.cfgs)                  # the three pairs are identical: order is immaterial
-    print(f"\n[{which}, sigma {cal.sigma}] priority {pr.cfgs} Z={pr.Z:.2f} us ({pr.calls} calls) | exhaustive {ex.cfgs} "
+    print(f"\n[{which}, sigma {cal.sigma}, penalty {cal.penalty}, mean Y error {cal.fit_mean:.4f}] priority {pr.cfgs} Z={pr.Z:.2f} us ({pr.calls} calls) | exhaustive {ex.cfgs} "
           f"Z={ex.Z:.2f} us ({ex.calls} calls) | gap {100 * gap:.2f} % | same up to order: {same} | "
           f"free steps {fr.cfgs} Z={fr.Z:.2f} us, gap {100 * gap_free:.2f} %")
     # Gate 3 on this chain is not an identity: under the model filled from the recorded sweep the heuristic stops as soon
@@ -76,7 +79,10 @@ def test_priority_against_brute_force_on_the_first_three_pairs(table, which):
     # communication with a shorter computation.  What holds with the calibrated model, and is asserted: it ends within
     # 2 % of the optimum with at most 19 of 216 calls.  With the model as printed (every byte of a workgroup charged to
     # HBM, a channel taking a whole compute unit) the predicted computation is so long that the walk stops almost at
-    # once; the gap (30 % on the recorded table) is printed, not gated.
+    # once; the gap (30 % on the recorded table) is printed, not gated.  With the resident penalty calibrated as well
+    # the model follows the recorded Y four times more closely (mean error 0.029 against 0.115), and the closer it
+    # follows it the more the early stop costs: 8.8 % on the recorded table, printed, not gated -- the same order as
+    # the gap measured on the hardware between the priority search and the exhaustive search over this ladder.
     if which == "calibrated":
         assert gap <= 0.02 and gap_free <= 0.02
     if gap == 0.0:
