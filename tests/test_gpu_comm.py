@@ -364,3 +364,25 @@ def test_lds_staged_in_place_and_through_the_runner():
     bad = [launches[0], lg.CommLaunch(lg.LAGOM_REDUCE_COPY, lg.LAGOM_F32, [da, db2], [out], n, 0, fuse=True, lds_staged=True)]
     with pytest.raises(lg.LagomError):
         lg.lagom_overlap_run(bad, [(4, 256, 128 << 10)], comps, s1, s2, 0, 1, lg.LAGOM_ALONE_COMM)
+
+
+def test_full_size_launches_in_the_light_channel_and_roofline_shapes():
+    """The launch shapes the extended searches, the penalised model and the standalone bandwidth figure end at, at full
+    size, register path and LDS path: the 72 MiB eight-source reduce and the 64 MiB all-gather copy.  The oracle
+    computes sampled slices of the reduce and the whole gather."""
+    count = 4194304
+    srcs = [inputs.normal_bf16(20 + s, count) for s in range(8)]
+    rng = np.random.default_rng(7)
+    lows = [0, count - 4096] + [int(v) for v in rng.integers(0, count - 4096, size=10)]
+    wants = {lo: oc.reduce_copy([s[lo:lo + 4096] for s in srcs], oc.BF16)[0] for lo in lows}
+    for run, cfgs in ((_run, [(128, 128, 64 << 10), (256, 128, 32 << 10), (64, 128, 128 << 10), (512, 512, 16 << 10)]),
+                      (_run_lds, [(512, 512, 16 << 10), (128, 128, 64 << 10)])):
+        for cfg in cfgs:
+            got = run(lg.LAGOM_REDUCE_COPY, "bf16", srcs, 1, cfg, count)[0]
+            for lo, want in wants.items():
+                assert same_bits(got[lo:lo + 4096], want), (run.__name__, cfg, lo)
+    shards = [inputs.normal_bf16(3000 + p, 2097152, scale=0.02) for p in range(8)]
+    whole = oc.gather_copy(shards)[0]
+    for run, cfgs in ((_run, [(128, 128, 64 << 10), (256, 128, 32 << 10), (512, 512, 16 << 10)]), (_run_lds, [(512, 512, 16 << 10)])):
+        for cfg in cfgs:
+            assert same_bits(run(lg.LAGOM_GATHER_COPY, "bf16", shards, 1, cfg, 8 * 2097152)[0], whole), (run.__name__, cfg)
