@@ -200,6 +200,11 @@ typedef struct {
     double Ysum_us;   /* median over repetitions of sum_i y_i of that repetition        */
     double Ysum_mad_us;
     double Z_mad_us;
+    /* Release of each stream: common start to the start of its first kernel.  The common start is the earlier of
+     * the two (so one of them is 0, as is that of a stream that did not run); in a co-run without cross-stream
+     * dependencies they differ by a microsecond or so.                                                            */
+    double comm_start_us;
+    double comp_start_us;
 } lagom_timing;
 
 /*   launches[nlaunch] : communication kernels in stream order; cfgs[ncfg] their
@@ -207,7 +212,10 @@ typedef struct {
  *   comps[ncomp]      : GEMMs in stream order.
  *   comm_stream, comp_stream : two distinct hipStream_t of default priority.
  *   Each of warmup + iters repetitions starts both streams together behind a gate and
- *   drains both before the next; every value reported is the median over `iters`.
+ *   drains both before the next; every value reported is the median over `iters`.  In LAGOM_CORUN
+ *   the gate is a bounded delay kernel on either stream; the two agree on the instant of release
+ *   through 16 bytes of pinned host memory that the library allocates once per device and keeps
+ *   (calls that overlap in time on one device share it and may delay each other's release).
  *   Cross-stream dependencies (after_comp / after_comm_id) are enforced with events in
  *   LAGOM_CORUN; the two enqueue orders are merged on the host so that every awaited event
  *   has been recorded first, and a dependency cycle is LAGOM_EINVAL.  With dependencies X and

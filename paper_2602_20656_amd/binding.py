@@ -70,7 +70,8 @@ class lagom_gemm_desc(C.Structure):
 class lagom_timing(C.Structure):
     _fields_ = [("X_us", C.c_double), ("Y_us", C.c_double), ("Z_us", C.c_double),
                 ("x_us", C.POINTER(C.c_double)), ("y_us", C.POINTER(C.c_double)),
-                ("x_mad_us", C.POINTER(C.c_double)), ("Ysum_us", C.c_double), ("Ysum_mad_us", C.c_double), ("Z_mad_us", C.c_double)]
+                ("x_mad_us", C.POINTER(C.c_double)), ("Ysum_us", C.c_double), ("Ysum_mad_us", C.c_double), ("Z_mad_us", C.c_double),
+                ("comm_start_us", C.c_double), ("comp_start_us", C.c_double)]
 
 
 class lagom_sweep_point(C.Structure):
@@ -318,6 +319,8 @@ class Timing:
     Ysum_us: float = 0.0
     Ysum_mad_us: float = 0.0
     Z_mad_us: float = 0.0
+    comm_start_us: float = 0.0                            # common start to the first kernel of either stream
+    comp_start_us: float = 0.0
 
 
 class _Group:
@@ -369,7 +372,8 @@ def lagom_overlap_run(launches: Sequence[CommLaunch], cfgs: Sequence[CfgLike], c
                      C.cast(xm, C.POINTER(C.c_double)), 0.0, 0.0, 0.0)
     _check(lib().lagom_overlap_run(grp.L, grp.nlaunch, _cfg_array(cfgs), ncfg, grp.G, grp.ncomp,
                                    _stream(comm_stream), _stream(comp_stream), warmup, iters, mode, C.byref(t)))
-    return Timing(t.X_us, t.Y_us, t.Z_us, list(x)[:ncfg], list(y)[:grp.ncomp], list(xm)[:ncfg], t.Ysum_us, t.Ysum_mad_us, t.Z_mad_us)
+    return Timing(t.X_us, t.Y_us, t.Z_us, list(x)[:ncfg], list(y)[:grp.ncomp], list(xm)[:ncfg], t.Ysum_us, t.Ysum_mad_us, t.Z_mad_us,
+                  t.comm_start_us, t.comp_start_us)
 
 
 def lagom_overlap_steps(launches: Sequence[CommLaunch], cfgs: Sequence[CfgLike], comps: Sequence[GemmDesc],

@@ -3,13 +3,18 @@
 // Eq. 1) -- and time it with HIP events.  This is Alg. 2's ProfileTime and the experiment
 // behind Fig. 3.
 //
-// Both streams are released together: a short, bounded delay kernel runs on the
-// communication stream while the host enqueues every launch of both streams; the
-// computation stream waits on an event recorded right after it.  The kernels therefore
-// run back to back, unaffected by host launch latency, and start at a common instant.
+// Both streams are released together: each starts with a short, bounded delay kernel that holds it
+// while the host enqueues every launch of both streams.  The kernel on the communication stream picks
+// the tick of the constant-rate wall clock at which the hold ends and publishes it through a word of
+// pinned host memory; the kernel on the computation stream reads it and holds until the same tick.
+// (An event wait across streams instead of the second kernel released the computation stream 6 - 7 us
+// after the communication stream, which showed in Z of every computation-bound group.)  The kernels
+// therefore run back to back, unaffected by host launch latency, and start at a common instant.
 #include <hip/hip_runtime.h>
 #include <algorithm>
+#include <atomic>
 #include <cmath>
+#include <mutex>
 #include <vector>
 #include "common.h"
 
@@ -31,6 +36,63 @@ __global__ void gate_delay_kernel(long long ticks, int max_iter) {
             __builtin_amdgcn_s_sleep(64);
         }
     }
+}
+
+// The start gate of a co-run.  The leader publishes the tick at which both streams go on, then the
+// sequence number of this repetition (release); the follower waits for its sequence number (acquire),
+// reads the tick and holds until then.  Every loop is bounded by `max_iter` whatever memory or the
+// clock say; a follower that never sees its number just ends late.
+struct GateWord { unsigned long long deadline; unsigned long long seq; };
+
+__global__ void gate_leader_kernel(GateWord* g, unsigned long long seq, long long ticks, int max_iter) {
+    if (threadIdx.x == 0) {
+        const long long t0 = wall_clock64();
+        __hip_atomic_store(&g->deadline, (unsigned long long)(t0 + ticks), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        __hip_atomic_store(&g->seq, seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+        for (int i = 0; i < max_iter; ++i) {
+            if (wall_clock64() - t0 >= ticks) break;
+            __builtin_amdgcn_s_sleep(8);
+        }
+    }
+}
+
+__global__ void gate_follower_kernel(GateWord* g, unsigned long long seq, int max_iter) {
+    if (threadIdx.x == 0) {
+        long long deadline = 0;
+        bool known = false;
+        for (int i = 0; i < max_iter; ++i) {
+            if (!known && __hip_atomic_load(&g->seq, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_SYSTEM) == seq) {
+                deadline = (long long)__hip_atomic_load(&g->deadline, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                known = true;
+            }
+            if (known && wall_clock64() - deadline >= 0) break;
+            __builtin_amdgcn_s_sleep(8);
+        }
+    }
+}
+
+// One gate word of pinned host memory per device, allocated at the first co-run on that device and
+// kept until the process ends (16 bytes; pinned host memory, not device memory).
+int gate_word(int dev, GateWord** out) {
+    static std::mutex mu;
+    static std::vector<GateWord*> words;
+    std::lock_guard<std::mutex> lock(mu);
+    if (dev < 0) return lagom::fail(LAGOM_EINVAL, "bad device %d", dev);
+    if ((size_t)dev >= words.size()) words.resize((size_t)dev + 1, nullptr);
+    if (!words[dev]) {
+        void* p = nullptr;
+        HIP_TRY(hipHostMalloc(&p, sizeof(GateWord), hipHostMallocDefault));
+        GateWord* w = static_cast<GateWord*>(p);
+        w->deadline = 0; w->seq = 0;
+        words[dev] = w;
+    }
+    *out = words[dev];
+    return LAGOM_OK;
+}
+
+unsigned long long next_gate_seq() {
+    static std::atomic<unsigned long long> counter{0};
+    return counter.fetch_add(1) + 1;
 }
 
 struct Events {
@@ -264,9 +326,8 @@ extern "C" int lagom_overlap_run(const lagom_comm_desc* launches, int nlaunch, c
     const int ncomp_run = run_comp ? ncomp : 0;
     const bool deps = run_comm && run_comp;        // dependencies only matter when both streams run
     Events E;
-    if (int rc = E.make(1 + 2 * ngroups + 2 * ncomp_run)) return rc;
-    hipEvent_t gate = E.ev[0];
-    hipEvent_t* ga_start = E.ev.data() + 1;
+    if (int rc = E.make(2 * ngroups + 2 * ncomp_run)) return rc;
+    hipEvent_t* ga_start = E.ev.data();
     hipEvent_t* ga_end = ga_start + ngroups;
     hipEvent_t* gb_start = ga_end + ngroups;
     hipEvent_t* gb_end = gb_start + ncomp_run;
@@ -278,19 +339,29 @@ extern "C" int lagom_overlap_run(const lagom_comm_desc* launches, int nlaunch, c
     const int items = (run_comm ? nlaunch + 2 * ngroups : 0) + 3 * ncomp_run + 4;
     const double delay_us = 60.0 + 12.0 * items;
     const long long ticks = (long long)(delay_us * clock_khz / 1000.0);
-    const int max_iter = 1 << 14;
+    // a pass of the gates' loops takes 0.3 - 0.4 us: several times the passes the delay needs, and no more
+    const int max_iter = (int)std::min(8.0 * delay_us + 4096.0, 4.0e6);
+    GateWord* word = nullptr;
+    if (run_comm && run_comp)
+        if (int rc = gate_word(dev, &word)) return rc;
 
     std::vector<std::vector<double>> xs(ncfg), ys(ncomp);
-    std::vector<double> Xs, Ys, Zs;
+    std::vector<double> Xs, Ys, Zs, startsA, startsB;
     hipStream_t gate_stream = run_comm ? sa : sb;
 
     std::vector<double> Ysums;
     // one repetition: gate, both streams enqueued, both drained
     auto repetition = [&]() -> int {
-        hipLaunchKernelGGL(gate_delay_kernel, dim3(1), dim3(64), 0, gate_stream, ticks, max_iter);
-        HIP_TRY(hipGetLastError());
-        HIP_TRY(hipEventRecord(gate, gate_stream));
-        if (run_comm && run_comp) HIP_TRY(hipStreamWaitEvent(sb, gate, 0));
+        if (word) {
+            const unsigned long long seq = next_gate_seq();
+            hipLaunchKernelGGL(gate_leader_kernel, dim3(1), dim3(64), 0, sa, word, seq, ticks, max_iter);
+            HIP_TRY(hipGetLastError());
+            hipLaunchKernelGGL(gate_follower_kernel, dim3(1), dim3(64), 0, sb, word, seq, max_iter);
+            HIP_TRY(hipGetLastError());
+        } else {
+            hipLaunchKernelGGL(gate_delay_kernel, dim3(1), dim3(64), 0, gate_stream, ticks, max_iter);
+            HIP_TRY(hipGetLastError());
+        }
         if (int rc = enqueue_group(plan, launches, run_comm ? nlaunch : 0, cfgs, comps, ncomp_run, deps, sa, sb,
                                    ga_start, ga_end, gb_start, gb_end)) return rc;
         if (run_comm) HIP_TRY(hipStreamSynchronize(sa));
@@ -301,15 +372,25 @@ extern "C" int lagom_overlap_run(const lagom_comm_desc* launches, int nlaunch, c
         if (int rc = drained(repetition(), sa, sb)) return rc;
         if (it < warmup) continue;
 
+        // The common start: the start event of the stream whose first kernel follows its gate kernel directly.  With
+        // cross-stream dependencies the other stream's first start event is recorded behind a wait; without them the
+        // two are the instants at which the two gates opened, and the earlier one is taken.  (No event of its own
+        // behind the gate kernel: two event records in a row on one stream lie 5 us apart.)
         float ms = 0.f;
         double X = 0.0, Y = 0.0, endA = 0.0, endB = 0.0, ysum = 0.0;
+        hipEvent_t origin = run_comm ? ga_start[0] : gb_start[0];
+        if (run_comm && run_comp) {
+            HIP_TRY(hipEventElapsedTime(&ms, ga_start[0], gb_start[0]));
+            if (ms < 0.f) origin = gb_start[0];
+        }
         if (run_comm) {
             for (int g = 0; g < ngroups; ++g) {
                 HIP_TRY(hipEventElapsedTime(&ms, ga_start[g], ga_end[g]));
                 xs[group_id[g]].push_back((double)ms * 1000.0);
             }
             HIP_TRY(hipEventElapsedTime(&ms, ga_start[0], ga_end[ngroups - 1])); X = (double)ms * 1000.0;
-            HIP_TRY(hipEventElapsedTime(&ms, gate, ga_end[ngroups - 1])); endA = (double)ms * 1000.0;
+            HIP_TRY(hipEventElapsedTime(&ms, origin, ga_end[ngroups - 1])); endA = (double)ms * 1000.0;
+            HIP_TRY(hipEventElapsedTime(&ms, origin, ga_start[0])); startsA.push_back((double)ms * 1000.0);
         }
         if (run_comp) {
             for (int i = 0; i < ncomp; ++i) {
@@ -318,7 +399,8 @@ extern "C" int lagom_overlap_run(const lagom_comm_desc* launches, int nlaunch, c
                 ysum = ysum + (double)ms * 1000.0;
             }
             HIP_TRY(hipEventElapsedTime(&ms, gb_start[0], gb_end[ncomp - 1])); Y = (double)ms * 1000.0;
-            HIP_TRY(hipEventElapsedTime(&ms, gate, gb_end[ncomp - 1])); endB = (double)ms * 1000.0;
+            HIP_TRY(hipEventElapsedTime(&ms, origin, gb_end[ncomp - 1])); endB = (double)ms * 1000.0;
+            HIP_TRY(hipEventElapsedTime(&ms, origin, gb_start[0])); startsB.push_back((double)ms * 1000.0);
         }
         Xs.push_back(X); Ys.push_back(Y); Zs.push_back(endA > endB ? endA : endB); Ysums.push_back(ysum);
     }
@@ -328,6 +410,8 @@ extern "C" int lagom_overlap_run(const lagom_comm_desc* launches, int nlaunch, c
     out->Z_mad_us = mad(Zs, out->Z_us);
     out->Ysum_us = median(Ysums);
     out->Ysum_mad_us = mad(Ysums, out->Ysum_us);
+    out->comm_start_us = startsA.empty() ? 0.0 : median(startsA);
+    out->comp_start_us = startsB.empty() ? 0.0 : median(startsB);
     for (int j = 0; j < ncfg; ++j) {
         const double m = median(xs[j]);
         if (out->x_us) out->x_us[j] = m;

@@ -37,6 +37,22 @@ def test_corun_keeps_both_results_correct_and_times_are_consistent(tiny):
         assert getattr(r, which) > 0
 
 
+def test_both_streams_are_released_at_the_same_instant(tiny):
+    """The start gate: the first kernels of the two streams start within a few microseconds of each other (an event wait
+    across streams would release the computation stream 6 - 7 us late), Z is the later of the two ends, and a stream that
+    does not run reports no release."""
+    for cfg in [(4, 256, 128 << 10), (64, 256, 64 << 10)]:
+        t = lg.lagom_overlap_run(tiny["launches"], [cfg], tiny["comps"], tiny["s1"], tiny["s2"], 3, 15, lg.LAGOM_CORUN)
+        print(f"\nrelease after the gate: communication {t.comm_start_us:.2f} us, computation {t.comp_start_us:.2f} us; "
+              f"X {t.X_us:.1f} Y {t.Y_us:.1f} Z {t.Z_us:.1f}")
+        assert t.comm_start_us >= 0.0 and t.comp_start_us >= 0.0
+        assert abs(t.comm_start_us - t.comp_start_us) <= 4.0
+        later_end = max(t.comm_start_us + t.X_us, t.comp_start_us + t.Y_us)
+        assert t.Z_us == pytest.approx(later_end, abs=3.0)          # medians of different repetitions: not an identity
+    r = lg.lagom_overlap_run(tiny["launches"], [(4, 256, 128 << 10)], tiny["comps"], tiny["s1"], tiny["s2"], 1, 5, lg.LAGOM_ALONE_COMM)
+    assert r.comp_start_us == 0.0 and r.comm_start_us >= 0.0
+
+
 def test_streams_that_share_a_hardware_queue_are_detected_and_refused(tiny):
     assert lg.lagom_streams_overlap(tiny["s1"], tiny["s2"]) and not lg.lagom_streams_overlap(tiny["s1"], tiny["s1"])
     pool = [torch.cuda.Stream() for _ in range(8)]        # HIP has 4 hardware queues per process by default
