@@ -703,10 +703,13 @@ def main():
         "value_min_median_max": h["speedup_tuned_vs_default"], "verdict": h["verdict"],
         # the same ratio for the other searches of the headline workload (min, median, max over the rounds): Alg. 1/2 with
         # free steps on the fixed-chunk ladder of the task's grids; the same on the extended space (NC up to 256, channels of
-        # two wavefronts); the communication-only descent; the best point of the profiler's sweeps
+        # two wavefronts), driven by measurements and driven by the cost model with the resident penalty (no measurement
+        # during the search); the communication-only descent; the best point of the profiler's sweeps
         "value_other_searches": {k: h["candidates"][k]["speedup_vs_default"] for k in
-                                 ("tuned_free_steps", "tuned_free_steps_extended_nt_min", "comm_descent", "best_swept", "best_swept_extended")
+                                 ("tuned_free_steps", "tuned_free_steps_extended_nt_min", "model_rho_free_steps_extended_nt_min",
+                                  "comm_descent", "best_swept", "best_swept_extended")
                                  if k in h["candidates"]},
+        "value_sustained": h["chained_interleaved"]["tuned"]["speedup_vs_default"],   # the same ratio over back-to-back steps, no gate
         "z_tuned_us": h["z_tuned_us"], "z_default_us": h["z_default_us"],
         "comm_hbm_gbps": roofline_comm["achieved"], "gemm_mfma_util": h["gemm_mfma_util"],
         "gemm_mfma_util_by_shape": {c["roofline"]["shape"]: c["roofline"]["frac"] for c in configs.values()},
