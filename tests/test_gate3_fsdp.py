@@ -87,3 +87,41 @@ def test_priority_against_brute_force_on_the_first_three_pairs(table, which):
         assert gap <= 0.02 and gap_free <= 0.02
     if gap == 0.0:
         assert same
+
+
+def test_resident_penalty_on_the_recorded_extended_sweep(golden_dir):
+    """The recorded sweep with channels of 128 and of 256 threads and up to 256 of them: sigma, then rho per thread count,
+    fitted on every second point and scored on the others, library and oracle side by side.  On these recorded timings
+    the penalty cuts the held-out error of Y to less than half, the heavier channel gets the larger penalty, and the
+    model's choice among the swept points moves from a mid-field point to one within 2 % of the best measured one."""
+    t = json.load(open(os.path.join(golden_dir, "fsdp_chain_sweep_extended.json")))
+    total = float(sum(t["bytes_per_comm"]))
+    geo, lam, bw, ncomp, nbytes = t["geometry"], t["lambda"], t["bw_peak_bytes_per_us"], t["ncomp"], t["bytes_per_comm"]
+    usable = [p for p in t["points"] if p["cfg"][0] < lam]
+    lpts = [lg.SweepPoint(tuple(p["cfg"]), p["comm_alone_us"], p["comm_corun_us"], p["comp_alone_us"], p["comp_corun_us"],
+                          p["z_corun_us"], total / p["comm_alone_us"], total / p["comm_corun_us"]) for p in usable]
+    opts = [omf.SweepPoint(p.cfg, p.comm_corun_us, p.comp_alone_us, p.comp_corun_us, p.v_corun) for p in lpts]
+    ogeo = omf.Geometry(geo["mu"], geo["tb"], geo["d_bytes_past_l2"])
+    held = [i % 2 == 1 for i in range(len(lpts))]
+    sigmas = [i / 8 for i in range(9)]
+    rhos = [0.0, 0.01, 0.02, 0.03, 0.04, 0.05, 0.06, 0.08, 0.1, 0.125, 0.15, 0.2, 0.25, 0.3, 0.4, 0.5]
+    res = {}
+    for label, use in (("sigma", None), ("sigma_rho", rhos)):
+        cl = lg.lagom_model_calibrate(lpts, lam, bw, geo["mu"], geo["tb"], geo["d_bytes_past_l2"], ncomp, nbytes, sigmas, held, rhos=use)
+        co = omf.calibrate(opts, held, ogeo, ncomp, nbytes, lam, bw, sigmas, rhos=use)
+        assert (cl.sigma, cl.fit_mean, cl.fit_max, cl.held_mean, cl.held_max, cl.penalty) == \
+            (co.sigma, co.fit_mean, co.fit_max, co.held_mean, co.held_max, co.penalty)
+        model, _ = lg.lagom_model_fill(lpts, lam, bw, geo["mu"], geo["tb"], geo["d_bytes_past_l2"], ncomp, nbytes,
+                                       corun_share=cl.sigma, resident_penalty=cl.penalty)
+        z = {p.cfg: lg.lagom_cost_model(model, [p.cfg] * len(nbytes)).Z_us for p in lpts}
+        pick = min(lpts, key=lambda p: z[p.cfg])
+        best = min(lpts, key=lambda p: p.z_corun_us)
+        res[label] = (cl, pick, best)
+        print(f"\n[{label}] sigma {cl.sigma} penalty {cl.penalty}: Y error fitted {cl.fit_mean:.4f} held out {cl.held_mean:.4f} (max {cl.held_max:.4f}); "
+              f"picks {pick.cfg} measured {pick.z_corun_us:.1f} us, best measured {best.cfg} {best.z_corun_us:.1f} us")
+    plain, pen = res["sigma"][0], res["sigma_rho"][0]
+    assert sorted(pen.penalty) == [128, 256] and pen.penalty[256] > pen.penalty[128] > 0.0
+    assert pen.held_mean < 0.5 * plain.held_mean and pen.held_max < plain.held_max
+    pick, best = res["sigma_rho"][1], res["sigma_rho"][2]
+    assert pick.z_corun_us <= 1.02 * best.z_corun_us
+    assert res["sigma"][1].z_corun_us > 1.05 * best.z_corun_us
